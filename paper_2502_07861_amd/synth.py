@@ -1,0 +1,91 @@
+"""Seeded synthetic K/V/Q generators (inputs only -- none of the method's arithmetic).
+
+Stand-ins for the activations the paper measured on (Llama-3.1-8B / Qwen2.5
+prompts from LongBench, App. B): only the *shapes* (layers, KV heads, d, n, b,
+T) are taken from there; values are seeded Gaussians with the structure below.
+The same module feeds the oracle and the HIP path; whichever device the tensors
+are drawn on, the drawn bits are the input of both sides.
+
+  single_head_fp32  one head, keys alpha*(mu+z) with one shared mean direction,
+                    scaled so that q.k/sqrt(d) spans about [-6, 6]
+  gqa_layer_bf16    per-head mean mu_h (norm 2), 4 outlier channels scaled x8 on
+                    the keys only, values N(0,I), queries mu_h + z'
+"""
+from __future__ import annotations
+
+import math
+
+import torch
+
+
+def _gen(seed: int, device) -> torch.Generator:
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed) & (2**63 - 1))
+    return g
+
+
+def single_head_fp32(n=1024, d=64, nq=16, *, seed=0x250207861001, device="cpu", span=6.0):
+    """K,V [1,n,d] fp32, Q [1,1,nq,d] fp32 (one KV head, g = 1)."""
+    g = _gen(seed, device)
+    mu = torch.randn(d, generator=g, device=device, dtype=torch.float32)
+    mu = 2.0 * mu / mu.norm()
+    zk = torch.randn(n, d, generator=g, device=device, dtype=torch.float32)
+    zq = torch.randn(nq, d, generator=g, device=device, dtype=torch.float32)
+    V = torch.randn(n, d, generator=g, device=device, dtype=torch.float32)
+    K0, Q0 = mu + zk, mu + zq
+    peak = (Q0 @ K0.T).abs().max().item() / math.sqrt(d)
+    alpha = math.sqrt(span / peak)
+    return dict(K=(alpha * K0)[None].contiguous(), V=V[None].contiguous(),
+                Q=(alpha * Q0)[None, None].contiguous())
+
+
+def gqa_layer_bf16(n_seq=8, n=16384, d=128, g=4, nq=64, *, seed=0x250207861002, device="cpu",
+                   dtype=torch.bfloat16, outlier=8.0, n_outlier=4, mu_norm=2.0, chunk=16):
+    """K,V [n_seq,n,d], Q [n_seq,g,nq,d] in ``dtype``; n_seq = layers x KV heads."""
+    gen = _gen(seed, device)
+    mu = torch.randn(n_seq, d, generator=gen, device=device, dtype=torch.float32)
+    mu = mu_norm * mu / mu.norm(dim=1, keepdim=True)
+    order = torch.rand(n_seq, d, generator=gen, device=device).argsort(dim=1)[:, :n_outlier]
+    scale = torch.ones(n_seq, d, device=device, dtype=torch.float32)
+    scale.scatter_(1, order, outlier)
+    K = torch.empty(n_seq, n, d, device=device, dtype=dtype)
+    V = torch.empty(n_seq, n, d, device=device, dtype=dtype)
+    for s0 in range(0, n_seq, chunk):          # bounded fp32 temporaries
+        s1 = min(n_seq, s0 + chunk)
+        z = torch.randn(s1 - s0, n, d, generator=gen, device=device, dtype=torch.float32)
+        K[s0:s1] = ((mu[s0:s1, None, :] + z) * scale[s0:s1, None, :]).to(dtype)
+        z = torch.randn(s1 - s0, n, d, generator=gen, device=device, dtype=torch.float32)
+        V[s0:s1] = z.to(dtype)
+        del z
+    zq = torch.randn(n_seq, g, nq, d, generator=gen, device=device, dtype=torch.float32)
+    Q = (mu[:, None, None, :] + zq).to(dtype)
+    return dict(K=K, V=V, Q=Q)
+
+
+# The five workloads named by the benchmark description; n_seq = sessions*layers*KV heads.
+WORKLOADS = {
+    "cfg1": dict(kind="single_head_fp32", n_seq=1, n=1024, d=64, g=1, nq=16, block=256, rounds=1,
+                 dtype="f32", center=False, seed=0x250207861001),
+    "cfg2": dict(kind="gqa_layer_bf16", n_seq=8, n=16384, d=128, g=4, nq=64, block=512, rounds=2,
+                 dtype="bf16", center=True, seed=0x250207861002),
+    "cfg3": dict(kind="gqa_layer_bf16", n_seq=32 * 8, n=32768, d=128, g=4, nq=1, block=1024,
+                 rounds=2, dtype="bf16", center=True, seed=0x250207861003),
+    "cfg4": dict(kind="gqa_layer_bf16", n_seq=64 * 8, n=131072, d=128, g=4, nq=1, block=1024,
+                 rounds=3, dtype="bf16", center=True, seed=0x250207861004),
+    "cfg5": dict(kind="gqa_layer_bf16", n_seq=16 * 32 * 8, n=32768, d=128, g=4, nq=1, block=1024,
+                 rounds=2, dtype="bf16", center=True, seed=0x250207861005,
+                 decode_block=512, decode_rounds=2, decode_tokens=1024),
+}
+
+
+def make_workload(name: str, device="cpu", **over):
+    """Tensors of one named workload (optionally with overridden sizes)."""
+    cfg = dict(WORKLOADS[name])
+    cfg.update(over)
+    if cfg["kind"] == "single_head_fp32":
+        t = single_head_fp32(cfg["n"], cfg["d"], cfg["nq"], seed=cfg["seed"], device=device)
+    else:
+        t = gqa_layer_bf16(cfg["n_seq"], cfg["n"], cfg["d"], cfg["g"], cfg["nq"], seed=cfg["seed"],
+                           device=device)
+    t["cfg"] = cfg
+    return t

@@ -1,0 +1,188 @@
+/*
+ * balancekv.h -- C ABI of the MI355X (gfx950) BalanceKV hot path.
+ *
+ * BalanceKV (arXiv 2502.07861) compresses a key/value cache by repeated
+ * discrepancy-based halving and answers decode attention from the weighted
+ * survivors.  This library implements, in hand-written HIP, the four verbs of
+ * the paper's streaming problem statement (Section 2.1):
+ *
+ *   bkv_compress_block   one halving of independent blocks        (Alg. 2)
+ *   bkv_merge_reduce     T rounds of block-parallel halving        (Alg. 3, offline
+ *                        form in the proof of Thm 3.3; App. B "Implementation Detail")
+ *   bkv_append_token     one streaming step incl. carries          (Alg. 3)
+ *   bkv_attend           weighted softmax estimator                (Alg. 1, output line)
+ *
+ * Conventions
+ *  - Plain C, no exceptions.  Every tensor pointer is a DEVICE pointer owned by
+ *    the caller unless stated otherwise; the library never frees or keeps it
+ *    beyond the call, except the storage handed to bkv_cache_init.
+ *  - Scratch memory comes from the caller: query the size, pass `workspace`.
+ *  - Every call only enqueues work on `hip_stream` (a hipStream_t passed as
+ *    void*, NULL = default stream) and returns; nothing synchronises.
+ *  - Return value: BKV_OK or a negative code for misuse / launch failure.
+ *    Algorithmic events (the FAIL branch of Alg. 2, near-tie decisions) are
+ *    NOT errors: they are written to per-instance device arrays.
+ *  - Layout: row-major, head dimension fastest.  A "sequence" is one
+ *    (session, layer, KV head) stream; sequences are independent.
+ *  - Supported: d in {64,128}; block in {64,128,...,1024} (multiple of 64);
+ *    dtype BKV_F32 or BKV_BF16 (inputs, outputs and queries share it; all
+ *    accumulation is fp32).  Strict halving only (exactly block/2 survivors).
+ */
+#ifndef BALANCEKV_H
+#define BALANCEKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* dtype */
+#define BKV_F32  0
+#define BKV_BF16 1
+
+/* flags */
+#define BKV_CENTER_KEYS 1u  /* shift keys by the block mean for the selection (App. B.5 item 1) */
+#define BKV_STRICT_HALF 2u  /* keep exactly block/2 per block (App. B, Implementation Detail); required */
+#define BKV_VALUE_GRAM  4u  /* multiply kernel weights by <v_i,v_j>/r_value^2 (Alg. 2 line 5); not built: BKV_ESHAPE */
+
+/* return codes */
+#define BKV_OK          0
+#define BKV_EINVAL     -1   /* null / misaligned pointer, negative size, bad handle             */
+#define BKV_ESHAPE     -2   /* unsupported d / block / rounds / dtype / flags, or n not a      */
+                            /* multiple of block * 2^rounds                                    */
+#define BKV_EWORKSPACE -3   /* workspace missing or too small                                  */
+#define BKV_EHIP       -4   /* a HIP call failed; see bkv_last_hip_error()                     */
+#define BKV_ECAPACITY  -5   /* the streaming cache is full                                     */
+
+/* status word written per instance (bkv_compress_block) */
+#define BKV_STATUS_FAIL 1   /* bit 0: |y^T eta| > c R^2 happened (Alg. 2 line 6); p was clamped */
+/* bits 8..31: number of decisions whose margin |u_j - p_j| was below 1e-4 */
+
+typedef struct bkv_params {
+    int32_t  d;        /* head dimension                                                       */
+    int32_t  block;    /* b: block length (the batch size t of Alg. 3)                          */
+    int32_t  rounds;   /* T: halving rounds; compression rate 2^-T                              */
+    int32_t  dtype;    /* BKV_F32 | BKV_BF16                                                    */
+    float    log_c;    /* ln c of Alg. 2 line 3; NaN => ln(30 ln(block/delta))                  */
+    float    delta;    /* failure probability of Alg. 2; only read when log_c is NaN            */
+    float    r_key;    /* key radius of Alg. 2; <= 0 => largest (centred) key norm of the block */
+    float    r_value;  /* value radius; only read with BKV_VALUE_GRAM                           */
+    uint64_t seed;     /* key of the counter-based generator behind "with probability p_j"      */
+    uint32_t flags;    /* BKV_* flags                                                           */
+    uint32_t reserved; /* must be 0                                                             */
+} bkv_params;
+
+/* ---- misc ------------------------------------------------------------------------------- */
+const char* bkv_version(void);
+const char* bkv_error_string(int code);
+int         bkv_last_hip_error(void);          /* hipError_t of the last BKV_EHIP on this thread */
+
+/* The uniform draw of decision `ctr` in stream `stream`: top 24 bits of two rounds of the
+ * SplitMix64 mixer over (seed, stream, ctr); u = bits * 2^-24 in [0,1).  Host function, same
+ * integers as the device code.  Alg. 2 line 8 sets eta_j = +1 iff u_j < p_j.                    */
+uint32_t bkv_uniform_bits(uint64_t seed, uint64_t stream, uint64_t ctr);
+
+/* ---- Alg. 2: one halving of n_inst independent blocks ---------------------------------------
+ * K, V          [n_inst, block, d] device, dtype as params.  V may be NULL (then V_out must be).
+ * inst_ids      [n_inst] device or NULL: generator stream of each instance (NULL: 0,1,2,...);
+ *               decision j of an instance draws u = uniform(seed, stream, j).
+ * w_in          weight carried by every input token (2^level); survivors get 2*w_in.
+ * uniforms      [n_inst, block] fp32 device or NULL: if given, replaces the generator (test hook).
+ * K_out, V_out  [n_inst, block/2, d] survivors, rows of the ORIGINAL K, V, ascending input index.
+ * w_out         [n_inst, block/2] fp32 or NULL.
+ * idx_out       [n_inst, block/2] int32 or NULL: index within the block of each survivor.
+ * signs_out     [n_inst, block] int8 (+1/-1) or NULL: eta of Alg. 2 before the output step.
+ * status_out    [n_inst] int32 or NULL (BKV_STATUS_*).
+ * stats_out     [n_inst, 2] fp32 or NULL: {min_j |u_j - p_j|, max_j |y^T eta|/(c R^2)}.
+ * workspace     bkv_compress_workspace_bytes() bytes (may be 0 => NULL allowed).
+ * Kernel weights are exp((<k_i,k_j> - r_key^2)/sqrt(d) - ln c) (Alg. 2 lines 2-7 divided
+ * through by c R^2), keys optionally centred by the block mean; n_inst == 0 is a no-op.          */
+size_t bkv_compress_workspace_bytes(const bkv_params* p, int64_t n_inst);
+int bkv_compress_block(const bkv_params* p, const void* K, const void* V, int64_t n_inst,
+                       const uint64_t* inst_ids, float w_in, const float* uniforms,
+                       void* K_out, void* V_out, float* w_out, int32_t* idx_out,
+                       int8_t* signs_out, int32_t* status_out, float* stats_out,
+                       void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* The kernel-weight matrix itself, for inspection: G_out [n_inst, block, block] fp32, entry
+ * (i,j) = exp((<k_i,k_j> - r_key^2)/sqrt(d) - ln c) as the walk sees it (Alg. 2 line 5, v = 1).
+ * Symmetric; produced by the same tile code as the walk.                                        */
+int bkv_kernel_weights(const bkv_params* p, const void* K, int64_t n_inst, float* G_out,
+                       void* hip_stream);
+
+/* ---- Alg. 3 offline: T = p->rounds rounds over n_seq sequences of n tokens ---------------------
+ * K, V          [n_seq, n, d] device.  n must be a multiple of block * 2^T.
+ * Round r views the n>>r surviving tokens of a sequence as blocks of `block` (a merged block is
+ * the left child's survivors then the right child's) and halves each.  Decision j of block blk in
+ * round r of sequence s draws uniform(seed, 64*(seq_base+s) + r, blk*block + j).
+ * K_out, V_out  [n_seq, n>>T, d]; w_out [n_seq, n>>T] fp32 (= 2^T) or NULL;
+ * idx_out       [n_seq, n>>T] int32 or NULL: original token index of each survivor (ascending).
+ * signs_out     int8 or NULL: eta of every round, round r at offset n_seq*(2n - (2n>>r)),
+ *               laid out [n_seq, n>>r].
+ * status_out    [n_seq, T] int32 or NULL: per sequence and round, bit 0 = any FAIL, bits 8.. =
+ *               total number of margin decisions (|u-p| < 1e-4).
+ * workspace     bkv_merge_reduce_workspace_bytes() bytes.  rounds == 0 copies the input.          */
+size_t bkv_merge_reduce_workspace_bytes(const bkv_params* p, int64_t n_seq, int64_t n);
+int bkv_merge_reduce(const bkv_params* p, const void* K, const void* V, int64_t n_seq, int64_t n,
+                     int64_t seq_base, void* K_out, void* V_out, float* w_out, int32_t* idx_out,
+                     int8_t* signs_out, int32_t* status_out,
+                     void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* ---- Alg. 1 output line on a flat weighted cache -------------------------------------------------
+ * K_c, V_c      [n_seq, stride_tokens, d] device; only the first `count` tokens of each sequence
+ *               are read.  w [n_seq, stride_tokens] fp32 (2^level; w == 0 marks an absent token).
+ * Q             [n_seq, g, nq, d]: g query heads share each KV sequence (GQA), nq queries each.
+ * out           [n_seq, g, nq, d] (dtype as params);  lse_out [n_seq, g, nq] fp32 or NULL: natural
+ *               log of the estimator's denominator, so partial results over disjoint token ranges
+ *               can be merged.  out = sum_i w_i e^{<k_i,q>/sqrt d} v_i / sum_i w_i e^{<k_i,q>/sqrt d}.
+ * count == 0 writes zeros and lse = -inf.                                                          */
+size_t bkv_attend_workspace_bytes(const bkv_params* p, int64_t n_seq, int64_t count, int32_t g,
+                                  int32_t nq);   /* an upper bound valid for any smaller count too */
+int bkv_attend_kv(const bkv_params* p, const void* K_c, const void* V_c, const float* w,
+                  int64_t n_seq, int64_t count, int64_t stride_tokens, const void* Q, int32_t g,
+                  int32_t nq, void* out, float* lse_out, void* workspace, size_t ws_bytes,
+                  void* hip_stream);
+
+/* ---- Alg. 3 streaming: the levels C^0..C^T of n_seq sequences --------------------------------------
+ * The levels of one sequence live in one flat array, highest level first: level-T survivors, then
+ * levels T-1..1 (each empty or block/2 tokens), then the raw tail C^0.  A carry halves the last
+ * `block` tokens in place, so no token ever moves while it is live.  All sequences of a cache
+ * advance in lock step (one token each per bkv_append_token), hence one host-side counter.
+ * device_storage: bkv_cache_bytes() bytes, 256-byte aligned, caller-owned, must outlive the handle.
+ * max_tokens: capacity in stored tokens per sequence (survivors + tail), >= block.
+ * p->rounds and p->block govern the streaming phase; p->seed keys its draws: decision j of the
+ * blk-th block reaching level l of sequence s draws uniform(seed, 64*s + l, blk*block + j).        */
+typedef struct bkv_cache bkv_cache;
+size_t bkv_cache_bytes(const bkv_params* p, int64_t n_seq, int64_t max_tokens);
+int bkv_cache_init(bkv_cache** out, const bkv_params* p, int64_t n_seq, int64_t max_tokens,
+                   void* device_storage, size_t bytes, void* hip_stream);
+/* Adopt compressed tokens (e.g. a bkv_merge_reduce result) as already-final survivors:
+ * K_c, V_c [n_seq, count, d], w [n_seq, count].  Resets the streaming counter.                      */
+int bkv_cache_load(bkv_cache* c, const void* K_c, const void* V_c, const float* w, int64_t count,
+                   void* hip_stream);
+int bkv_cache_free(bkv_cache* c);                      /* host handle only                          */
+int64_t bkv_cache_count(const bkv_cache* c);           /* stored tokens per sequence                */
+int64_t bkv_cache_tokens_seen(const bkv_cache* c);     /* tokens appended since init / load (j)     */
+/* Device views of the storage: K, V [n_seq, max_tokens, d], w [n_seq, max_tokens].                  */
+int bkv_cache_views(const bkv_cache* c, void** K, void** V, float** w);
+
+/* One streaming step: k, v [n_seq, d] (one new token per sequence) go to the tail with weight 1;
+ * after every block-th token the carry loop of Alg. 3 runs (up to T halvings of the last `block`
+ * tokens).  Returns the number of halvings performed (>= 0) or a negative code.
+ * status_out [n_seq, T] int32 or NULL is OR-ed/added to as in bkv_merge_reduce (never cleared here). */
+size_t bkv_append_workspace_bytes(const bkv_cache* c);
+int bkv_append_token(bkv_cache* c, const void* k, const void* v, int32_t* status_out,
+                     void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* Alg. 1 output line over everything the cache holds (all levels, weights 2^level).
+ * Q, out, lse_out as in bkv_attend_kv.                                                              */
+size_t bkv_cache_attend_workspace_bytes(const bkv_cache* c, int32_t g, int32_t nq);
+int bkv_attend(const bkv_cache* c, const void* Q, int32_t g, int32_t nq, void* out, float* lse_out,
+               void* workspace, size_t ws_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BALANCEKV_H */

@@ -1,0 +1,377 @@
+// C ABI of libbalancekv: argument validation, workspace carving, launch orchestration, and the
+// host-side bookkeeping of Alg. 3 (arXiv 2502.07861).  Every step of the path runs in the kernels of
+// compress.hip / attend.hip; nothing here touches tensor contents on the host.
+#include <math.h>
+#include <new>
+#include <string.h>
+
+#include "bkv_device.h"
+#include "bkv_host.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return BKV_EHIP;
+}
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int check_params(const bkv_params* p) {
+    if (!p) return BKV_EINVAL;
+    if (p->reserved != 0) return BKV_EINVAL;
+    if (p->d != 64 && p->d != 128) return BKV_ESHAPE;
+    if (p->block < 64 || p->block > 1024 || (p->block & 63)) return BKV_ESHAPE;
+    if (p->rounds < 0 || p->rounds > 30) return BKV_ESHAPE;
+    if (p->dtype != BKV_F32 && p->dtype != BKV_BF16) return BKV_ESHAPE;
+    if (p->flags & ~(BKV_CENTER_KEYS | BKV_STRICT_HALF | BKV_VALUE_GRAM)) return BKV_EINVAL;
+    if (p->flags & BKV_VALUE_GRAM) return BKV_ESHAPE;          // value factor of Alg. 2 line 5 not built
+    if (!(p->flags & BKV_STRICT_HALF)) return BKV_ESHAPE;      // variable-size output not built
+    if (isnan(p->log_c) && !(p->delta > 0.f && p->delta < (float)p->block)) return BKV_EINVAL;
+    return BKV_OK;
+}
+inline int elem_bytes(const bkv_params* p) { return p->dtype == BKV_BF16 ? 2 : 4; }
+inline int row_bytes(const bkv_params* p) { return p->d * elem_bytes(p); }
+
+// ln c: given, or c = 30 ln(block/delta) (Alg. 2 line 3 with n = the block handed to the call)
+inline float resolve_log_c(const bkv_params* p) {
+    if (!isnan(p->log_c)) return p->log_c;
+    return logf(30.0f * logf((float)p->block / p->delta));
+}
+
+void fill_common(bkv::CompressArgs& a, const bkv_params* p) {
+    memset(&a, 0, sizeof(a));
+    a.b = p->block;
+    a.seed = p->seed;
+    a.flags = p->flags;
+    a.alpha = (float)(1.4426950408889634 / sqrt((double)p->d));
+    a.cterm = (float)(-sqrt((double)p->d) * (double)resolve_log_c(p));
+    a.rkey2 = p->r_key > 0.f ? p->r_key * p->r_key : 0.f;
+}
+
+}  // namespace
+
+struct bkv_cache {
+    bkv_params p;
+    int64_t n_seq, cap;
+    char* K;
+    char* V;
+    float* w;
+    int64_t count;        // stored tokens per sequence
+    int64_t base_count;   // adopted survivors (never touched by carries)
+    int64_t stream_j;     // tokens appended since init/load (the j of Alg. 3)
+};
+
+extern "C" {
+
+const char* bkv_version(void) { return "balancekv-gfx950 0.1"; }
+
+const char* bkv_error_string(int code) {
+    switch (code) {
+        case BKV_OK: return "ok";
+        case BKV_EINVAL: return "invalid argument";
+        case BKV_ESHAPE: return "unsupported shape, dtype or mode";
+        case BKV_EWORKSPACE: return "workspace missing or too small";
+        case BKV_EHIP: return "HIP error";
+        case BKV_ECAPACITY: return "cache capacity exceeded";
+        default: return "unknown";
+    }
+}
+
+int bkv_last_hip_error(void) { return g_last_hip_error; }
+
+uint32_t bkv_uniform_bits(uint64_t seed, uint64_t stream, uint64_t ctr) { return bkv::draw_bits(seed, stream, ctr); }
+
+// ------------------------------------------------------------------------------------------ Alg. 2
+size_t bkv_compress_workspace_bytes(const bkv_params* p, int64_t n_inst) {
+    (void)p; (void)n_inst;
+    return 0;
+}
+
+int bkv_compress_block(const bkv_params* p, const void* K, const void* V, int64_t n_inst,
+                       const uint64_t* inst_ids, float w_in, const float* uniforms, void* K_out, void* V_out,
+                       float* w_out, int32_t* idx_out, int8_t* signs_out, int32_t* status_out, float* stats_out,
+                       void* workspace, size_t ws_bytes, void* hip_stream) {
+    (void)workspace; (void)ws_bytes;
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (n_inst < 0) return BKV_EINVAL;
+    if (n_inst == 0) return BKV_OK;
+    if (!K || !aligned16(K) || (K_out && !aligned16(K_out))) return BKV_EINVAL;
+    if (V_out && (!V || !aligned16(V) || !aligned16(V_out))) return BKV_EINVAL;
+    if (!(w_in > 0.f)) return BKV_EINVAL;
+    bkv::CompressArgs a;
+    fill_common(a, p);
+    a.K = (const char*)K; a.V = (const char*)V; a.K_out = (char*)K_out; a.V_out = (char*)V_out;
+    a.w_out = w_out; a.idx_out = idx_out; a.signs_out = signs_out; a.status_out = status_out; a.stats_out = stats_out;
+    a.inst_ids = inst_ids; a.uniforms = uniforms;
+    a.in_seq_stride = p->block; a.out_seq_stride = p->block / 2; a.blocks_per_seq = 1;
+    a.tree_mode = 0; a.w_out_val = 2.f * w_in;
+    hipError_t e = bkv::launch_compress(p->dtype, p->d, false, a, n_inst, (hipStream_t)hip_stream);
+    return e == hipSuccess ? BKV_OK : hip_fail(e);
+}
+
+int bkv_kernel_weights(const bkv_params* p, const void* K, int64_t n_inst, float* G_out, void* hip_stream) {
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (n_inst < 0) return BKV_EINVAL;
+    if (n_inst == 0) return BKV_OK;
+    if (!K || !aligned16(K) || !G_out) return BKV_EINVAL;
+    bkv::CompressArgs a;
+    fill_common(a, p);
+    a.K = (const char*)K; a.G_out = G_out;
+    a.in_seq_stride = p->block; a.out_seq_stride = p->block / 2; a.blocks_per_seq = 1;
+    a.w_out_val = 2.f;
+    hipError_t e = bkv::launch_compress(p->dtype, p->d, true, a, n_inst, (hipStream_t)hip_stream);
+    return e == hipSuccess ? BKV_OK : hip_fail(e);
+}
+
+// ------------------------------------------------------------------------------------------ Alg. 3 offline
+// workspace: K ping [n_seq, n/2, d] | K pong [n_seq, n/4, d] | idx ping [n_seq, n/2] | idx pong [n_seq, n/4]
+size_t bkv_merge_reduce_workspace_bytes(const bkv_params* p, int64_t n_seq, int64_t n) {
+    if (check_params(p) || n_seq < 0 || n < 0) return 0;
+    if (p->rounds <= 1) return 256;      // a single round writes straight to the outputs
+    const size_t rb = (size_t)row_bytes(p);
+    size_t bytes = 0;
+    bytes += align_up((size_t)n_seq * (n / 2) * rb, 256);
+    bytes += align_up((size_t)n_seq * (n / 4) * rb, 256);
+    bytes += align_up((size_t)n_seq * (n / 2) * 4, 256);
+    bytes += align_up((size_t)n_seq * (n / 4) * 4, 256);
+    return bytes + 256;
+}
+
+int bkv_merge_reduce(const bkv_params* p, const void* K, const void* V, int64_t n_seq, int64_t n,
+                     int64_t seq_base, void* K_out, void* V_out, float* w_out, int32_t* idx_out,
+                     int8_t* signs_out, int32_t* status_out, void* workspace, size_t ws_bytes, void* hip_stream) {
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (n_seq < 0 || n < 0 || seq_base < 0) return BKV_EINVAL;
+    const int T = p->rounds, b = p->block;
+    if (n % ((int64_t)b << T) != 0) return BKV_ESHAPE;
+    if (n_seq == 0 || n == 0) return BKV_OK;
+    if (n_seq * (n / b) > (1ll << 30) || n > (1ll << 31) - 1) return BKV_ESHAPE;
+    if (!K || !V || !K_out || !V_out) return BKV_EINVAL;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(K_out) || !aligned16(V_out)) return BKV_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t rb = (size_t)row_bytes(p);
+    hipError_t e;
+    if (T == 0) {   // nothing to halve: weights 1
+        if (idx_out) return BKV_ESHAPE;   // identity indices are not materialised
+        if ((e = bkv::launch_copy_rows(K, K_out, n_seq, n, n, n, (int)rb, st)) != hipSuccess) return hip_fail(e);
+        if ((e = bkv::launch_copy_rows(V, V_out, n_seq, n, n, n, (int)rb, st)) != hipSuccess) return hip_fail(e);
+        if (w_out && (e = bkv::launch_fill_w(w_out, n_seq, n, 0, n, 1.f, st)) != hipSuccess) return hip_fail(e);
+        return BKV_OK;
+    }
+    const size_t need = bkv_merge_reduce_workspace_bytes(p, n_seq, n);
+    char* kbuf[2] = {nullptr, nullptr};
+    int32_t* ibuf[2] = {nullptr, nullptr};
+    int32_t* idx_final = idx_out;
+    if (T > 1) {
+        if (!workspace || ws_bytes < need || !aligned16(workspace)) return BKV_EWORKSPACE;
+        char* ws = (char*)workspace;
+        kbuf[0] = ws; ws += align_up((size_t)n_seq * (n / 2) * rb, 256);
+        kbuf[1] = ws; ws += align_up((size_t)n_seq * (n / 4) * rb, 256);
+        ibuf[0] = (int32_t*)ws; ws += align_up((size_t)n_seq * (n / 2) * 4, 256);
+        ibuf[1] = (int32_t*)ws;
+    }
+    if (!idx_final) {     // the value gather needs the survivor indices even if the caller does not
+        if (T > 1) idx_final = ibuf[(T - 1) & 1];      // free at the last round (its input is the other one)
+        else return BKV_EINVAL;                        // T == 1: idx_out is required
+    }
+    if (status_out && (e = bkv::launch_fill_u32(status_out, 0u, n_seq * T, st)) != hipSuccess) return hip_fail(e);
+
+    const char* k_in = (const char*)K;
+    const int32_t* i_in = nullptr;
+    int64_t m = n;
+    for (int r = 0; r < T; ++r) {
+        const bool last = (r == T - 1);
+        bkv::CompressArgs a;
+        fill_common(a, p);
+        a.K = k_in; a.V = nullptr;
+        a.K_out = last ? (char*)K_out : kbuf[r & 1];
+        a.V_out = nullptr;
+        a.w_out = last ? w_out : nullptr;
+        a.idx_in = i_in;
+        a.idx_out = last ? idx_final : ibuf[r & 1];
+        a.signs_out = signs_out ? signs_out + (size_t)n_seq * (size_t)(2 * n - ((2 * n) >> r)) : nullptr;
+        a.status_out = status_out; a.status_stride = T;
+        a.in_seq_stride = m; a.out_seq_stride = m / 2; a.blocks_per_seq = (int32_t)(m / b);
+        a.tree_mode = 1; a.round = r; a.seq_base = seq_base; a.blk_base = 0;
+        a.w_out_val = (float)(1u << (r + 1));
+        e = bkv::launch_compress(p->dtype, p->d, false, a, n_seq * (m / b), st);
+        if (e != hipSuccess) return hip_fail(e);
+        k_in = a.K_out; i_in = a.idx_out; m /= 2;
+    }
+    // values of the survivors, gathered once from the original V
+    e = bkv::launch_gather_rows(V, idx_final, V_out, n_seq, n, m, (int)rb, st);
+    return e == hipSuccess ? BKV_OK : hip_fail(e);
+}
+
+// ------------------------------------------------------------------------------------------ estimator
+size_t bkv_attend_workspace_bytes(const bkv_params* p, int64_t n_seq, int64_t count, int32_t g, int32_t nq) {
+    if (check_params(p) || n_seq < 0 || count < 0 || g <= 0 || nq <= 0) return 0;
+    return bkv::attend_workspace_bytes(p->d, n_seq, g * nq);
+}
+
+int bkv_attend_kv(const bkv_params* p, const void* K_c, const void* V_c, const float* w, int64_t n_seq,
+                  int64_t count, int64_t stride_tokens, const void* Q, int32_t g, int32_t nq, void* out,
+                  float* lse_out, void* workspace, size_t ws_bytes, void* hip_stream) {
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (n_seq < 0 || count < 0 || stride_tokens < count || g <= 0 || nq <= 0) return BKV_EINVAL;
+    if (n_seq == 0) return BKV_OK;
+    if (n_seq > 65535 || (int64_t)g * nq > 4 * 65535) return BKV_ESHAPE;
+    if (!Q || !out || !aligned16(Q) || !aligned16(out)) return BKV_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipError_t e;
+    const int n_q = g * nq;
+    if (count == 0) {   // empty cache: zeros, lse = -inf
+        const int64_t words = n_seq * n_q * (int64_t)row_bytes(p) / 4;
+        if ((e = bkv::launch_fill_u32(out, 0u, words, st)) != hipSuccess) return hip_fail(e);
+        if (lse_out && (e = bkv::launch_fill_u32(lse_out, 0xff800000u, n_seq * n_q, st)) != hipSuccess) return hip_fail(e);
+        return BKV_OK;
+    }
+    if (!K_c || !V_c || !w || !aligned16(K_c) || !aligned16(V_c)) return BKV_EINVAL;
+    const size_t need = bkv::attend_workspace_bytes(p->d, n_seq, n_q);
+    if (!workspace || ws_bytes < need || !aligned16(workspace)) return BKV_EWORKSPACE;
+    bkv::AttendArgs a;
+    memset(&a, 0, sizeof(a));
+    a.K = (const char*)K_c; a.V = (const char*)V_c; a.w = w; a.Q = (const char*)Q; a.out = (char*)out;
+    a.lse_out = lse_out; a.stride_tokens = stride_tokens; a.count = count; a.n_q = n_q;
+    a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)p->d));
+    e = bkv::launch_attend(p->dtype, p->d, a, n_seq, workspace, st);
+    return e == hipSuccess ? BKV_OK : hip_fail(e);
+}
+
+// ------------------------------------------------------------------------------------------ Alg. 3 streaming
+size_t bkv_cache_bytes(const bkv_params* p, int64_t n_seq, int64_t max_tokens) {
+    if (check_params(p) || n_seq <= 0 || max_tokens < p->block) return 0;
+    const size_t rb = (size_t)row_bytes(p);
+    return 2 * align_up((size_t)n_seq * max_tokens * rb, 256) + align_up((size_t)n_seq * max_tokens * 4, 256);
+}
+
+int bkv_cache_init(bkv_cache** out, const bkv_params* p, int64_t n_seq, int64_t max_tokens, void* device_storage,
+                   size_t bytes, void* hip_stream) {
+    if (!out) return BKV_EINVAL;
+    *out = nullptr;
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (n_seq <= 0 || n_seq > 65535 || max_tokens < p->block) return BKV_EINVAL;
+    const size_t need = bkv_cache_bytes(p, n_seq, max_tokens);
+    if (!device_storage || (reinterpret_cast<uintptr_t>(device_storage) & 255u) || bytes < need) return BKV_EINVAL;
+    bkv_cache* c = new (std::nothrow) bkv_cache;
+    if (!c) return BKV_EINVAL;
+    c->p = *p; c->n_seq = n_seq; c->cap = max_tokens;
+    const size_t rb = (size_t)row_bytes(p);
+    const size_t kv = align_up((size_t)n_seq * max_tokens * rb, 256);
+    c->K = (char*)device_storage; c->V = c->K + kv; c->w = (float*)(c->V + kv);
+    c->count = c->base_count = c->stream_j = 0;
+    // weights start at 0 (= absent); K, V start finite so that masked lanes never meet NaN payloads
+    hipError_t e = bkv::launch_fill_u32(device_storage, 0u, (int64_t)(need / 4), (hipStream_t)hip_stream);
+    if (e != hipSuccess) { delete c; return hip_fail(e); }
+    *out = c;
+    return BKV_OK;
+}
+
+int bkv_cache_load(bkv_cache* c, const void* K_c, const void* V_c, const float* w, int64_t count, void* hip_stream) {
+    if (!c || count < 0 || count > c->cap) return BKV_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (count > 0) {
+        if (!K_c || !V_c || !w || !aligned16(K_c) || !aligned16(V_c)) return BKV_EINVAL;
+        const int rb = row_bytes(&c->p);
+        hipError_t e;
+        if ((e = bkv::launch_copy_rows(K_c, c->K, c->n_seq, count, c->cap, count, rb, st)) != hipSuccess) return hip_fail(e);
+        if ((e = bkv::launch_copy_rows(V_c, c->V, c->n_seq, count, c->cap, count, rb, st)) != hipSuccess) return hip_fail(e);
+        if ((e = bkv::launch_copy_f32(w, c->w, c->n_seq, count, c->cap, count, st)) != hipSuccess) return hip_fail(e);
+    }
+    c->count = c->base_count = count;
+    c->stream_j = 0;
+    return BKV_OK;
+}
+
+int bkv_cache_free(bkv_cache* c) {
+    if (!c) return BKV_EINVAL;
+    delete c;
+    return BKV_OK;
+}
+
+int64_t bkv_cache_count(const bkv_cache* c) { return c ? c->count : (int64_t)BKV_EINVAL; }
+int64_t bkv_cache_tokens_seen(const bkv_cache* c) { return c ? c->stream_j : (int64_t)BKV_EINVAL; }
+
+int bkv_cache_views(const bkv_cache* c, void** K, void** V, float** w) {
+    if (!c) return BKV_EINVAL;
+    if (K) *K = c->K;
+    if (V) *V = c->V;
+    if (w) *w = c->w;
+    return BKV_OK;
+}
+
+// workspace of a carry: survivors K, V [n_seq, block/2, d]
+size_t bkv_append_workspace_bytes(const bkv_cache* c) {
+    if (!c) return 0;
+    return 2 * align_up((size_t)c->n_seq * (c->p.block / 2) * row_bytes(&c->p), 256) + 256;
+}
+
+int bkv_append_token(bkv_cache* c, const void* k, const void* v, int32_t* status_out, void* workspace,
+                     size_t ws_bytes, void* hip_stream) {
+    if (!c || !k || !v || !aligned16(k) || !aligned16(v)) return BKV_EINVAL;
+    if (c->count + 1 > c->cap) return BKV_ECAPACITY;
+    const int b = c->p.block, T = c->p.rounds;
+    const int rb = row_bytes(&c->p);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int64_t j = c->stream_j + 1;
+    int halvings = 0;
+    if (T > 0 && j % b == 0) {       // p = j/t is an integer: carry while p stays integral and i < T
+        const int64_t pnum = j / b;
+        while (halvings < T && pnum % (1ll << halvings) == 0) ++halvings;
+        if (!workspace || ws_bytes < bkv_append_workspace_bytes(c) || !aligned16(workspace)) return BKV_EWORKSPACE;
+    }
+    hipError_t e;
+    // C^0 <- C^0 U {(k_j, v_j)}, weight 1
+    if ((e = bkv::launch_copy_rows(k, c->K + (size_t)c->count * rb, c->n_seq, 1, c->cap, 1, rb, st)) != hipSuccess) return hip_fail(e);
+    if ((e = bkv::launch_copy_rows(v, c->V + (size_t)c->count * rb, c->n_seq, 1, c->cap, 1, rb, st)) != hipSuccess) return hip_fail(e);
+    if ((e = bkv::launch_fill_w(c->w, c->n_seq, c->cap, c->count, 1, 1.f, st)) != hipSuccess) return hip_fail(e);
+    c->count += 1;
+    c->stream_j = j;
+    if (halvings == 0) return 0;
+
+    char* tmpK = (char*)workspace;
+    char* tmpV = tmpK + align_up((size_t)c->n_seq * (b / 2) * rb, 256);
+    for (int i = 0; i < halvings; ++i) {
+        // C^{i+1} <- C^{i+1} U SoftmaxBalance(C^i): C^i is the last b stored tokens; survivors land where it began
+        const int64_t first = c->count - b;
+        bkv::CompressArgs a;
+        fill_common(a, &c->p);
+        a.K = c->K + (size_t)first * rb; a.V = c->V + (size_t)first * rb;
+        a.K_out = tmpK; a.V_out = tmpV;
+        a.status_out = status_out; a.status_stride = T;
+        a.in_seq_stride = c->cap; a.out_seq_stride = b / 2; a.blocks_per_seq = 1;
+        a.tree_mode = 1; a.round = i; a.seq_base = 0;
+        a.blk_base = (j / b) / (1ll << i) - 1;           // how many blocks reached level i before this one
+        a.w_out_val = (float)(1u << (i + 1));
+        e = bkv::launch_compress(c->p.dtype, c->p.d, false, a, c->n_seq, st);
+        if (e != hipSuccess) return hip_fail(e);
+        if ((e = bkv::launch_copy_rows(tmpK, c->K + (size_t)first * rb, c->n_seq, b / 2, c->cap, b / 2, rb, st)) != hipSuccess) return hip_fail(e);
+        if ((e = bkv::launch_copy_rows(tmpV, c->V + (size_t)first * rb, c->n_seq, b / 2, c->cap, b / 2, rb, st)) != hipSuccess) return hip_fail(e);
+        if ((e = bkv::launch_fill_w(c->w, c->n_seq, c->cap, first, b / 2, a.w_out_val, st)) != hipSuccess) return hip_fail(e);
+        if ((e = bkv::launch_fill_w(c->w, c->n_seq, c->cap, first + b / 2, b / 2, 0.f, st)) != hipSuccess) return hip_fail(e);
+        c->count -= b / 2;
+    }
+    return halvings;
+}
+
+size_t bkv_cache_attend_workspace_bytes(const bkv_cache* c, int32_t g, int32_t nq) {
+    if (!c || g <= 0 || nq <= 0) return 0;
+    return bkv::attend_workspace_bytes(c->p.d, c->n_seq, g * nq);
+}
+
+int bkv_attend(const bkv_cache* c, const void* Q, int32_t g, int32_t nq, void* out, float* lse_out, void* workspace,
+               size_t ws_bytes, void* hip_stream) {
+    if (!c) return BKV_EINVAL;
+    return bkv_attend_kv(&c->p, c->K, c->V, c->w, c->n_seq, c->count, c->cap, Q, g, nq, out, lse_out, workspace,
+                         ws_bytes, hip_stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,254 @@
+// Decode attention against the compressed, weighted cache (Alg. 1 output line of arXiv 2502.07861):
+//   z = sum_i w_i e^{<k_i,q>/sqrt d} v_i / sum_i w_i e^{<k_i,q>/sqrt d},  w_i = 2^level(i).
+// w_i e^x = 2^{x log2(e) + log2 w_i}: a softmax with logit bias log2 w_i, evaluated with a running
+// maximum.  The pass is one stream over K, V, w (HBM bound): every lane owns a 16-byte slice of a
+// row, a group of kSlices lanes owns a row, each wavefront covers 64/kSlices rows per step, and up to
+// QT query vectors that share the KV sequence (GQA) are served from the same loads.  The token range
+// is split over workgroups; partial (max, denominator, numerator) triples are merged by a second
+// small kernel, which also emits the log-denominator so callers can merge further partials.
+#include "bkv_device.h"
+#include "bkv_host.h"
+
+namespace bkv {
+
+constexpr int kQT = 4;           // query vectors per pass over the cache
+constexpr int kAttWaves = 4;
+constexpr int kUnroll = 4;       // rows in flight per lane group
+constexpr float kNeg = -1.0e30f; // "minus infinity" that stays finite under subtraction
+
+template <int SL> __device__ __forceinline__ float group_sum(float x) {
+    // all-reduce over SL consecutive lanes (SL in {8,16,32}) with DPP adds
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));  // row_half_mirror
+    if (SL >= 16)
+        x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));  // row_mirror
+    if (SL >= 32) x += __shfl_xor(x, 16);
+    return x;
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const AttendArgs a) {
+    constexpr int ROWB = D * (int)sizeof(T);
+    constexpr int SL = ROWB / 16;              // lanes per row
+    constexpr int RPW = 64 / SL;               // rows per wavefront per step
+    constexpr int EPL = Elem<T>::kPerFrag;     // elements per lane
+    constexpr int ROWS_IT = kAttWaves * RPW * kUnroll;
+
+    __shared__ float red[kAttWaves][kQT][D + 2];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sl = lane % SL, lg = lane / SL;
+    const int split = blockIdx.x, qg = blockIdx.y;
+    const int64_t seq = blockIdx.z;
+    const int64_t r_begin = (int64_t)split * a.rows_per_split;
+    const int64_t r_end = min(a.count, r_begin + a.rows_per_split);
+
+    const char* Kb = a.K + (size_t)seq * a.stride_tokens * ROWB;
+    const char* Vb = a.V + (size_t)seq * a.stride_tokens * ROWB;
+    const float* wb = a.w + (size_t)seq * a.stride_tokens;
+
+    float qf[kQT][EPL];
+#pragma unroll
+    for (int qi = 0; qi < kQT; ++qi) {
+        const int q = qg * kQT + qi;
+        if (q < a.n_q) {
+            uintx4 raw = *reinterpret_cast<const uintx4*>(a.Q + ((size_t)seq * a.n_q + q) * ROWB + sl * 16);
+            Elem<T>::unpack(raw, qf[qi]);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) qf[qi][e] *= a.scale_log2;
+        } else {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) qf[qi][e] = 0.f;
+        }
+    }
+    float m[kQT], l[kQT], o[kQT][EPL];
+#pragma unroll
+    for (int qi = 0; qi < kQT; ++qi) {
+        m[qi] = kNeg; l[qi] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[qi][e] = 0.f;
+    }
+
+    for (int64_t base = r_begin; base < r_end; base += ROWS_IT) {
+        uintx4 kraw[kUnroll], vraw[kUnroll];
+        float wv[kUnroll];
+        bool ok[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t row = base + (u * kAttWaves + wave) * RPW + lg;
+            ok[u] = row < r_end;
+            const int64_t rr = ok[u] ? row : r_end - 1;          // stay in bounds; masked below
+            kraw[u] = *reinterpret_cast<const uintx4*>(Kb + (size_t)rr * ROWB + sl * 16);
+            vraw[u] = *reinterpret_cast<const uintx4*>(Vb + (size_t)rr * ROWB + sl * 16);
+            wv[u] = wb[rr];
+        }
+        float lg2[kUnroll][kQT];
+        float mb[kQT];
+#pragma unroll
+        for (int qi = 0; qi < kQT; ++qi) mb[qi] = kNeg;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            float kf[EPL];
+            Elem<T>::unpack(kraw[u], kf);
+            const bool live = ok[u] && wv[u] > 0.f;
+            const float bias = live ? __builtin_amdgcn_logf(wv[u]) : 0.f;    // v_log_f32 = log2
+#pragma unroll
+            for (int qi = 0; qi < kQT; ++qi) {
+                float part = 0.f;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) part = fmaf(qf[qi][e], kf[e], part);
+                part = group_sum<SL>(part);
+                lg2[u][qi] = live ? part + bias : kNeg;
+                mb[qi] = fmaxf(mb[qi], lg2[u][qi]);
+            }
+        }
+#pragma unroll
+        for (int qi = 0; qi < kQT; ++qi) {
+            const float mnew = fmaxf(m[qi], mb[qi]);
+            const float sc = fast_exp2(m[qi] - mnew);
+            m[qi] = mnew;
+            l[qi] *= sc;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) o[qi][e] *= sc;
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            float vf[EPL];
+            Elem<T>::unpack(vraw[u], vf);
+#pragma unroll
+            for (int qi = 0; qi < kQT; ++qi) {
+                const float p = (lg2[u][qi] > 0.5f * kNeg) ? fast_exp2(lg2[u][qi] - m[qi]) : 0.f;
+                l[qi] += p;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) o[qi][e] = fmaf(p, vf[e], o[qi][e]);
+            }
+        }
+    }
+
+    // merge the lane groups of a wavefront (each saw different rows)
+#pragma unroll
+    for (int off = SL; off < 64; off <<= 1) {
+#pragma unroll
+        for (int qi = 0; qi < kQT; ++qi) {
+            const float mo = __shfl_xor(m[qi], off);
+            const float lo = __shfl_xor(l[qi], off);
+            const float mn = fmaxf(m[qi], mo);
+            const float s0 = fast_exp2(m[qi] - mn), s1 = fast_exp2(mo - mn);
+            l[qi] = l[qi] * s0 + lo * s1;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) o[qi][e] = o[qi][e] * s0 + __shfl_xor(o[qi][e], off) * s1;
+            m[qi] = mn;
+        }
+    }
+    if (lg == 0) {
+#pragma unroll
+        for (int qi = 0; qi < kQT; ++qi) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) red[wave][qi][sl * EPL + e] = o[qi][e];
+            if (sl == 0) { red[wave][qi][D] = m[qi]; red[wave][qi][D + 1] = l[qi]; }
+        }
+    }
+    __syncthreads();
+    // merge the wavefronts and store the partial: [seq][qg][split][qi][D + 2]
+    float* dst = a.partial + ((((size_t)seq * gridDim.y + qg) * a.n_splits + split) * kQT) * (D + 2);
+    for (int t = tid; t < kQT * (D + 2); t += kAttWaves * 64) {
+        const int qi = t / (D + 2), c = t - qi * (D + 2);
+        float M = red[0][qi][D];
+#pragma unroll
+        for (int w = 1; w < kAttWaves; ++w) M = fmaxf(M, red[w][qi][D]);
+        float val;
+        if (c == D) val = M;
+        else {
+            val = 0.f;
+#pragma unroll
+            for (int w = 0; w < kAttWaves; ++w) val += red[w][qi][c] * fast_exp2(red[w][qi][D] - M);
+        }
+        dst[qi * (D + 2) + c] = val;
+    }
+}
+
+// One workgroup per (sequence, query): merge the split partials, normalise, store.
+template <typename T, int D>
+__global__ __launch_bounds__(64) void attend_merge_kernel(const AttendArgs a, int n_qgroups) {
+    const int64_t seq = blockIdx.y;
+    const int q = blockIdx.x;
+    const int qg = q / kQT, qi = q % kQT;
+    const float* src = a.partial + (((size_t)seq * n_qgroups + qg) * a.n_splits * kQT) * (D + 2);
+    float M = kNeg;
+    for (int s = 0; s < a.n_splits; ++s) M = fmaxf(M, src[((size_t)s * kQT + qi) * (D + 2) + D]);
+    float L = 0.f;
+    for (int s = 0; s < a.n_splits; ++s) {
+        const float* p = src + ((size_t)s * kQT + qi) * (D + 2);
+        L += p[D + 1] * fast_exp2(p[D] - M);
+    }
+    const float inv = L > 0.f ? 1.f / L : 0.f;
+    for (int c = threadIdx.x; c < D; c += 64) {
+        float acc = 0.f;
+        for (int s = 0; s < a.n_splits; ++s) {
+            const float* p = src + ((size_t)s * kQT + qi) * (D + 2);
+            acc += p[c] * fast_exp2(p[D] - M);
+        }
+        const float z = acc * inv;
+        const size_t oi = ((size_t)seq * a.n_q + q) * D + c;
+        if (sizeof(T) == 2) reinterpret_cast<unsigned short*>(a.out)[oi] = (unsigned short)f32_to_bf16_bits(z);
+        else reinterpret_cast<float*>(a.out)[oi] = z;
+    }
+    if (a.lse_out && threadIdx.x == 0)
+        a.lse_out[(size_t)seq * a.n_q + q] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f : -INFINITY;
+}
+
+static void attend_plan(int d, int dtype_bytes, int64_t n_seq, int64_t count, int n_q, int* n_qg, int* n_splits,
+                        int* rows_per_split) {
+    const int sl = d * dtype_bytes / 16;
+    const int rows_it = kAttWaves * (64 / sl) * kUnroll;
+    *n_qg = (n_q + kQT - 1) / kQT;
+    int64_t wgs = n_seq * (*n_qg);
+    int64_t want = wgs > 0 ? (2048 + wgs - 1) / wgs : 1;
+    int64_t max_splits = (count + 4 * rows_it - 1) / (4 * rows_it);
+    if (max_splits < 1) max_splits = 1;
+    if (want > max_splits) want = max_splits;
+    if (want < 1) want = 1;
+    int64_t rps = (count + want - 1) / want;
+    rps = (rps + rows_it - 1) / rows_it * rows_it;
+    if (rps < rows_it) rps = rows_it;
+    int64_t ns = (count + rps - 1) / rps;
+    if (ns < 1) ns = 1;
+    *n_splits = (int)ns;
+    *rows_per_split = (int)rps;
+}
+
+size_t attend_workspace_bytes(int d, int64_t n_seq, int n_q) {
+    // the split count never exceeds ceil(2048 / workgroups-without-splitting), whatever the token count
+    const int64_t n_qg = (n_q + kQT - 1) / kQT;
+    const int64_t wgs = n_seq * n_qg;
+    const int64_t ns = wgs > 0 ? (2048 + wgs - 1) / wgs : 1;
+    return (size_t)(wgs * ns) * kQT * (d + 2) * sizeof(float) + 256;
+}
+
+template <typename T, int D>
+static hipError_t launch_attend_t(AttendArgs& a, int64_t n_seq, int n_qg, hipStream_t st) {
+    hipLaunchKernelGGL((attend_partial_kernel<T, D>), dim3(a.n_splits, n_qg, (unsigned)n_seq), dim3(kAttWaves * 64), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((attend_merge_kernel<T, D>), dim3(a.n_q, (unsigned)n_seq), dim3(64), 0, st, a, n_qg);
+    return hipGetLastError();
+}
+
+hipError_t launch_attend(int dtype, int d, AttendArgs& a, int64_t n_seq, void* workspace, hipStream_t st) {
+    if (n_seq <= 0 || a.n_q <= 0) return hipSuccess;
+    if (n_seq > 65535) return hipErrorInvalidValue;
+    int n_qg, ns, rps;
+    attend_plan(d, dtype == BKV_BF16 ? 2 : 4, n_seq, a.count, a.n_q, &n_qg, &ns, &rps);
+    if (n_qg > 65535) return hipErrorInvalidValue;
+    a.n_splits = ns;
+    a.rows_per_split = rps;
+    a.partial = reinterpret_cast<float*>(workspace);
+    if (dtype == BKV_BF16 && d == 128) return launch_attend_t<__bf16, 128>(a, n_seq, n_qg, st);
+    if (dtype == BKV_BF16 && d == 64) return launch_attend_t<__bf16, 64>(a, n_seq, n_qg, st);
+    if (dtype == BKV_F32 && d == 128) return launch_attend_t<float, 128>(a, n_seq, n_qg, st);
+    if (dtype == BKV_F32 && d == 64) return launch_attend_t<float, 64>(a, n_seq, n_qg, st);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace bkv

@@ -1,0 +1,98 @@
+// Device-side building blocks shared by the BalanceKV kernels (gfx950 / CDNA4 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/balancekv.h"
+
+namespace bkv {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------------------------
+// Counter-based draws for "eta_j = +1 with probability p_j" (Alg. 2 line 8): two rounds of the
+// SplitMix64 output mixer over (seed, stream, counter); the top 24 bits give u = bits * 2^-24.
+// Integer-only, so host and device agree bit for bit.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ inline uint64_t mix64(uint64_t z) {
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27; z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+__host__ __device__ inline uint64_t stream_key(uint64_t seed, uint64_t stream) {
+    return mix64(seed + 0x9E3779B97F4A7C15ull * (stream + 1));
+}
+__host__ __device__ inline uint32_t draw_bits_keyed(uint64_t key, uint64_t ctr) {
+    return (uint32_t)(mix64(key + 0x9E3779B97F4A7C15ull * (ctr + 1)) >> 40);
+}
+__host__ __device__ inline uint32_t draw_bits(uint64_t seed, uint64_t stream, uint64_t ctr) {
+    return draw_bits_keyed(stream_key(seed, stream), ctr);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Element traits: 16-byte operand fragments and the MFMA step that consumes one pair of them.
+// A fragment is what one lane contributes to a 32-row (or 32-column) operand for one "k-group"
+// of 32 bytes per row: lane (n = lane%32, h = lane/32) holds bytes [32g + 16h, 32g + 16h + 16)
+// of row n.  Both operands of the Gram use the same mapping, so the contraction visits every
+// column of K exactly once whatever order the hardware pairs the sub-elements in.
+// ---------------------------------------------------------------------------------------------
+template <typename T> struct Elem;
+
+template <> struct Elem<__bf16> {
+    typedef bf16x8_t Frag;
+    static constexpr int kPerFrag = 8;                 // elements in 16 bytes
+    static __device__ __forceinline__ void mma(floatx16& acc, Frag a, Frag b) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void unpack(const uintx4& raw, float (&f)[8]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(raw[i] << 16);
+            f[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
+        }
+    }
+};
+
+template <> struct Elem<float> {
+    typedef floatx4 Frag;
+    static constexpr int kPerFrag = 4;
+    static __device__ __forceinline__ void mma(floatx16& acc, Frag a, Frag b) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], b[e], acc, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void unpack(const uintx4& raw, float (&f)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(raw[i]);
+    }
+};
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ unsigned int f32_to_bf16_bits(float x) {
+    unsigned int u = __float_as_uint(x);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+}  // namespace bkv

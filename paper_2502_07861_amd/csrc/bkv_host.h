@@ -1,0 +1,72 @@
+// Host-side declarations shared by the translation units of libbalancekv (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/balancekv.h"
+
+namespace bkv {
+
+struct CompressArgs {
+    const char* K;            // input keys, dtype T
+    const char* V;            // input values or null
+    char* K_out;              // survivors or null
+    char* V_out;
+    float* w_out;
+    int32_t* idx_out;
+    const int32_t* idx_in;    // original index of each input token, or null (position in sequence)
+    int8_t* signs_out;
+    int32_t* status_out;
+    float* stats_out;
+    const uint64_t* inst_ids;
+    const float* uniforms;
+    float* G_out;             // kernel-weight dump (EMIT_G variant only)
+    int64_t in_seq_stride;    // tokens between consecutive sequences in K / V / idx_in
+    int64_t out_seq_stride;   // tokens between consecutive sequences in K_out / V_out / w_out / idx_out
+    int64_t seq_base;         // added to the sequence number in the generator stream id
+    int64_t blk_base;         // added to the block number in the generator counter
+    uint64_t seed;
+    int32_t blocks_per_seq;
+    int32_t b;
+    int32_t chunk_rows;
+    int32_t round;            // level of the tree this launch halves
+    int32_t tree_mode;        // 1: stream = 64*(seq_base+seq)+round, ctr = (blk_base+blk)*b + j ; 0: stream = inst, ctr = j
+    int32_t status_stride;    // tree mode: status_out[seq*status_stride + round] accumulated atomically
+    float w_out_val;
+    float alpha;              // log2(e)/sqrt(d)
+    float cterm;              // -sqrt(d) * ln c
+    float rkey2;              // r_key^2, <= 0: measure
+    uint32_t flags;
+};
+
+size_t compress_lds_bytes(int row_bytes, int b);
+hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64_t n_inst, hipStream_t st);
+hipError_t launch_gather_rows(const void* in, const int32_t* idx, void* out, int64_t n_seq,
+                              int64_t in_seq_stride, int64_t rows_out, int row_bytes, hipStream_t st);
+hipError_t launch_fill_u32(void* p, uint32_t v, int64_t n, hipStream_t st);
+hipError_t launch_copy_rows(const void* src, void* dst, int64_t n_seq, int64_t src_seq_stride,
+                            int64_t dst_seq_stride, int64_t rows, int row_bytes, hipStream_t st);
+hipError_t launch_copy_f32(const float* src, float* dst, int64_t n_seq, int64_t src_seq_stride,
+                           int64_t dst_seq_stride, int64_t rows, hipStream_t st);
+hipError_t launch_fill_w(float* w, int64_t n_seq, int64_t seq_stride, int64_t off, int64_t rows, float val,
+                         hipStream_t st);
+
+struct AttendArgs {
+    const char* K;            // [n_seq, stride_tokens, d]
+    const char* V;
+    const float* w;           // [n_seq, stride_tokens]
+    const char* Q;            // [n_seq, n_q, d]   (n_q = g * nq query vectors per sequence)
+    char* out;                // [n_seq, n_q, d]
+    float* lse_out;           // [n_seq, n_q] or null
+    float* partial;           // workspace: [n_seq, n_qgroups, n_splits, QT, d + 2]
+    int64_t stride_tokens;
+    int64_t count;
+    int32_t n_q;
+    int32_t n_splits;
+    int32_t rows_per_split;
+    float scale_log2;         // log2(e)/sqrt(d)
+};
+size_t attend_workspace_bytes(int d, int64_t n_seq, int n_q);
+hipError_t launch_attend(int dtype, int d, AttendArgs& a, int64_t n_seq, void* workspace, hipStream_t st);
+
+}  // namespace bkv

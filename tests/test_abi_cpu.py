@@ -1,0 +1,96 @@
+"""Host-side checks of libbalancekv that need no GPU: the library loads, exports every symbol the
+header declares, rejects misuse with the documented codes before touching the device, and its
+host copy of the draw generator equals the oracle's."""
+import ctypes as C
+import math
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def bk():
+    from paper_2502_07861_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2502_07861_amd.build import build
+        build()
+    binding.lib()
+    return binding
+
+
+def test_header_symbols_are_exported(bk):
+    hdr = open(os.path.join(ROOT, "include", "balancekv.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(bkv_[a-z0-9_]+)\s*\(", hdr))
+    assert len(declared) >= 20
+    raw = C.CDLL(bk.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(raw, name), name
+    assert declared == set(bk.EXPORTS)          # the binding covers exactly the header
+
+
+def test_params_struct_layout(bk):
+    assert C.sizeof(bk.bkv_params) == 48
+    assert bk.bkv_params.seed.offset == 32 and bk.bkv_params.flags.offset == 40
+
+
+def test_version_and_error_strings(bk):
+    assert b"balancekv" in bk.lib().bkv_version()
+    assert bk.error_string(0) == "ok"
+    assert "workspace" in bk.error_string(bk.BKV_EWORKSPACE)
+
+
+def test_host_generator_equals_oracle(bk, oracle):
+    """Both sides implement the same counter-based generator; compare the raw 24-bit draws."""
+    cases = [(0, 0, 0), (1, 2, 3), (0x250207861002, 64 * 7 + 1, 511 * 3), (2**64 - 1, 2**63, 2**40)]
+    for s in range(50):
+        cases.append((s * 7919 + 1, s * 31, s * s))
+    for seed, stream, ctr in cases:
+        assert bk.uniform_bits(seed, stream, ctr) == oracle.uniform_bits(seed, stream, ctr)
+
+
+def test_misuse_is_rejected_before_any_launch(bk):
+    L = bk.lib()
+    ok = bk.make_params(128, 512, 2, bk.BKV_BF16, log_c=0.0)
+    one = C.c_void_p(0x1000)     # never dereferenced: every call below must fail validation first
+    def compress(p, K=one, n_inst=4, w_in=1.0):
+        return L.bkv_compress_block(C.byref(p), K, None, n_inst, None, w_in, None, None, None, None, None, None, None,
+                                    None, None, 0, None)
+    assert compress(bk.make_params(96, 512, 2, bk.BKV_BF16, log_c=0.0)) == bk.BKV_ESHAPE       # d
+    assert compress(bk.make_params(128, 100, 2, bk.BKV_BF16, log_c=0.0)) == bk.BKV_ESHAPE      # block
+    assert compress(bk.make_params(128, 2048, 2, bk.BKV_BF16, log_c=0.0)) == bk.BKV_ESHAPE
+    assert compress(bk.make_params(128, 512, 2, 7, log_c=0.0)) == bk.BKV_ESHAPE                # dtype
+    assert compress(bk.make_params(128, 512, 2, bk.BKV_BF16, log_c=0.0, strict=False)) == bk.BKV_ESHAPE
+    assert compress(bk.make_params(128, 512, 2, bk.BKV_BF16, log_c=0.0, value_gram=True)) == bk.BKV_ESHAPE
+    assert compress(bk.make_params(128, 512, 2, bk.BKV_BF16)) == bk.BKV_EINVAL                 # NaN log_c, no delta
+    assert compress(ok, K=None) == bk.BKV_EINVAL
+    assert compress(ok, K=C.c_void_p(0x1004)) == bk.BKV_EINVAL                                 # misaligned
+    assert compress(ok, n_inst=-1) == bk.BKV_EINVAL
+    assert compress(ok, w_in=0.0) == bk.BKV_EINVAL
+    assert compress(ok, n_inst=0) == bk.BKV_OK                                                 # empty: no-op
+    # merge_reduce: n must be a multiple of block * 2^T; workspace must be there
+    mr = lambda n, ws, wsb: L.bkv_merge_reduce(C.byref(ok), one, one, 2, n, 0, one, one, None, None, None, None, ws, wsb, None)
+    assert mr(512 * 4 + 512, None, 0) == bk.BKV_ESHAPE
+    assert mr(512 * 4, None, 0) == bk.BKV_EWORKSPACE
+    assert mr(512 * 4, one, 16) == bk.BKV_EWORKSPACE
+    assert L.bkv_merge_reduce_workspace_bytes(C.byref(ok), 2, 2048) >= 2 * (1024 + 512) * 256
+    # attend
+    at = lambda count, stride, g: L.bkv_attend_kv(C.byref(ok), one, one, one, 2, count, stride, one, g, 1, one, None, None, 0, None)
+    assert at(10, 5, 4) == bk.BKV_EINVAL
+    assert at(10, 10, 0) == bk.BKV_EINVAL
+    assert at(10, 10, 4) == bk.BKV_EWORKSPACE
+    # cache
+    h = C.c_void_p()
+    assert L.bkv_cache_init(C.byref(h), C.byref(ok), 4, 100, one, 1 << 30, None) == bk.BKV_EINVAL   # cap < block
+    assert L.bkv_cache_init(C.byref(h), C.byref(ok), 4, 4096, None, 0, None) == bk.BKV_EINVAL
+    assert L.bkv_cache_bytes(C.byref(ok), 4, 4096) == 2 * 4 * 4096 * 256 + 4 * 4096 * 4
+    assert L.bkv_append_token(None, one, one, None, None, 0, None) == bk.BKV_EINVAL
+    assert L.bkv_attend(None, one, 4, 1, one, None, None, 0, None) == bk.BKV_EINVAL
+
+
+def test_literal_log_c(bk, oracle):
+    assert abs(bk.literal_log_c(512, 1e-6) - oracle.log_c_literal(512, 1e-6)) < 1e-12
+    assert abs(bk.literal_log_c(512, 1e-6) - math.log(30 * math.log(512e6))) < 1e-12

@@ -307,7 +307,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 const unsigned long long m = __ballot(sv < tau);
                 if (lane == 0) etaMask[I] = m;
                 any_fail |= (__ballot(fabsf(sv) > 1.f) != 0ull);
-                const float margin = 0.5f * fabsf(sv - tau);
+                const float margin = 0.5f * fabsf(fminf(fmaxf(sv, -1.f), 1.f) - tau);   // |u - clamp(p)|
                 n_margin += __popcll(__ballot(margin < 1e-4f));
                 min_margin = fminf(min_margin, margin);
                 max_sigma = fmaxf(max_sigma, fabsf(sv));

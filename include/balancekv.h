@@ -162,6 +162,13 @@ int bkv_cache_init(bkv_cache** out, const bkv_params* p, int64_t n_seq, int64_t 
  * K_c, V_c [n_seq, count, d], w [n_seq, count].  Resets the streaming counter.                      */
 int bkv_cache_load(bkv_cache* c, const void* K_c, const void* V_c, const float* w, int64_t count,
                    void* hip_stream);
+/* Prefill: run bkv_merge_reduce (parameters `pre`: its block, rounds, seed, ln c; d and dtype must
+ * equal the cache's) on K, V [n_seq, n, d] and leave the survivors directly in the cache as final
+ * survivors of weight 2^pre->rounds (no intermediate copy).  Resets the streaming counter.
+ * Workspace as bkv_merge_reduce.  BKV_ECAPACITY if n >> rounds exceeds max_tokens.                   */
+size_t bkv_cache_prefill_workspace_bytes(const bkv_cache* c, const bkv_params* pre, int64_t n);
+int bkv_cache_prefill(bkv_cache* c, const bkv_params* pre, const void* K, const void* V, int64_t n,
+                      int32_t* status_out, void* workspace, size_t ws_bytes, void* hip_stream);
 int bkv_cache_free(bkv_cache* c);                      /* host handle only                          */
 int64_t bkv_cache_count(const bkv_cache* c);           /* stored tokens per sequence                */
 int64_t bkv_cache_tokens_seen(const bkv_cache* c);     /* tokens appended since init / load (j)     */
@@ -181,6 +188,16 @@ int bkv_append_token(bkv_cache* c, const void* k, const void* v, int32_t* status
 size_t bkv_cache_attend_workspace_bytes(const bkv_cache* c, int32_t g, int32_t nq);
 int bkv_attend(const bkv_cache* c, const void* Q, int32_t g, int32_t nq, void* out, float* lse_out,
                void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* ---- diagnostics: per-launch kernel times ---------------------------------------------------------
+ * For callers that want the duration of the individual kernels behind a call (benchmarks): after
+ * bkv_profile_enable(n > 0) the library brackets each kernel launch with a pair of HIP events on the
+ * caller's stream (up to n launches; creating the events allocates).  bkv_profile_read waits for the
+ * recorded launches, returns how many were written and clears the log.  kind: 0 halving kernel,
+ * 1 value gather, 2 attend pass, 3 attend merge; units: tokens the launch consumed.
+ * bkv_profile_enable(0) turns it off.  Not thread-safe; off by default.                             */
+int bkv_profile_enable(int32_t max_records);
+int bkv_profile_read(int32_t* kind, float* ms, int64_t* units, int32_t cap);
 
 #ifdef __cplusplus
 }

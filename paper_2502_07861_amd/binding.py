@@ -53,6 +53,8 @@ _SIGNATURES = {
     "bkv_cache_bytes": (_sz, [_PP, _i64, _i64]),
     "bkv_cache_init": (C.c_int, [C.POINTER(_vp), _PP, _i64, _i64, _vp, _sz, _vp]),
     "bkv_cache_load": (C.c_int, [_vp, _vp, _vp, _vp, _i64, _vp]),
+    "bkv_cache_prefill_workspace_bytes": (_sz, [_vp, _PP, _i64]),
+    "bkv_cache_prefill": (C.c_int, [_vp, _PP, _vp, _vp, _i64, _vp, _vp, _sz, _vp]),
     "bkv_cache_free": (C.c_int, [_vp]),
     "bkv_cache_count": (_i64, [_vp]),
     "bkv_cache_tokens_seen": (_i64, [_vp]),
@@ -61,6 +63,8 @@ _SIGNATURES = {
     "bkv_append_token": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bkv_cache_attend_workspace_bytes": (_sz, [_vp, _i32, _i32]),
     "bkv_attend": (C.c_int, [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
+    "bkv_profile_enable": (C.c_int, [_i32]),
+    "bkv_profile_read": (C.c_int, [_vp, _vp, _vp, _i32]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -255,6 +259,16 @@ class Cache:
         _check(lib().bkv_cache_load(self.h, _ptr(K_c, dt, "K_c"), _ptr(V_c, dt, "V_c"), _ptr(w, torch.float32, "w"),
                                     count, _stream()), "bkv_cache_load")
 
+    def prefill(self, pre, K, V, status=None, workspace=None):
+        """bkv_cache_prefill: compress K, V [n_seq, n, d] straight into the cache."""
+        dt = _torch_dtype(self.p)
+        n = K.shape[1]
+        if workspace is None:
+            workspace = torch.empty(int(lib().bkv_cache_prefill_workspace_bytes(self.h, C.byref(pre), n)),
+                                    device=K.device, dtype=torch.uint8)
+        _check(lib().bkv_cache_prefill(self.h, C.byref(pre), _ptr(K, dt, "K"), _ptr(V, dt, "V"), n, _ptr(status),
+                                       _ptr(workspace), workspace.numel(), _stream()), "bkv_cache_prefill")
+
     def append_token(self, k, v, status=None):
         dt = _torch_dtype(self.p)
         return _check(lib().bkv_append_token(self.h, _ptr(k, dt, "k"), _ptr(v, dt, "v"), _ptr(status),
@@ -286,6 +300,19 @@ class Cache:
         V = self.storage[off + kv:off + kv + self.n_seq * self.cap * self.p.d * es].view(dt).view(self.n_seq, self.cap, self.p.d)
         w = self.storage[off + 2 * kv:off + 2 * kv + self.n_seq * self.cap * 4].view(torch.float32).view(self.n_seq, self.cap)
         return K, V, w
+
+
+def profile_enable(n: int):
+    _check(lib().bkv_profile_enable(int(n)), "bkv_profile_enable")
+
+
+def profile_read(cap: int = 4096):
+    """[(kind, ms, units)] of the launches recorded since the last read (waits for them)."""
+    kind = (C.c_int32 * cap)()
+    ms = (C.c_float * cap)()
+    units = (C.c_int64 * cap)()
+    n = _check(lib().bkv_profile_read(kind, ms, units, cap), "bkv_profile_read")
+    return [(int(kind[i]), float(ms[i]), int(units[i])) for i in range(n)]
 
 
 def literal_log_c(block: int, delta: float) -> float:

@@ -107,7 +107,7 @@ int bkv_compress_block(const bkv_params* p, const void* K, const void* V, int64_
     a.K = (const char*)K; a.V = (const char*)V; a.K_out = (char*)K_out; a.V_out = (char*)V_out;
     a.w_out = w_out; a.idx_out = idx_out; a.signs_out = signs_out; a.status_out = status_out; a.stats_out = stats_out;
     a.inst_ids = inst_ids; a.uniforms = uniforms;
-    a.in_seq_stride = p->block; a.out_seq_stride = p->block / 2; a.blocks_per_seq = 1;
+    a.in_seq_stride = p->block; a.out_seq_stride = a.idx_out_seq_stride = p->block / 2; a.blocks_per_seq = 1;
     a.tree_mode = 0; a.w_out_val = 2.f * w_in;
     hipError_t e = bkv::launch_compress(p->dtype, p->d, false, a, n_inst, (hipStream_t)hip_stream);
     return e == hipSuccess ? BKV_OK : hip_fail(e);
@@ -122,7 +122,7 @@ int bkv_kernel_weights(const bkv_params* p, const void* K, int64_t n_inst, float
     bkv::CompressArgs a;
     fill_common(a, p);
     a.K = (const char*)K; a.G_out = G_out;
-    a.in_seq_stride = p->block; a.out_seq_stride = p->block / 2; a.blocks_per_seq = 1;
+    a.in_seq_stride = p->block; a.out_seq_stride = a.idx_out_seq_stride = p->block / 2; a.blocks_per_seq = 1;
     a.w_out_val = 2.f;
     hipError_t e = bkv::launch_compress(p->dtype, p->d, true, a, n_inst, (hipStream_t)hip_stream);
     return e == hipSuccess ? BKV_OK : hip_fail(e);
@@ -132,7 +132,7 @@ int bkv_kernel_weights(const bkv_params* p, const void* K, int64_t n_inst, float
 // workspace: K ping [n_seq, n/2, d] | K pong [n_seq, n/4, d] | idx ping [n_seq, n/2] | idx pong [n_seq, n/4]
 size_t bkv_merge_reduce_workspace_bytes(const bkv_params* p, int64_t n_seq, int64_t n) {
     if (check_params(p) || n_seq < 0 || n < 0) return 0;
-    if (p->rounds <= 1) return 256;      // a single round writes straight to the outputs
+    if (p->rounds <= 1) return align_up((size_t)n_seq * (n / 2) * 4, 256) + 256;   // survivor indices only
     const size_t rb = (size_t)row_bytes(p);
     size_t bytes = 0;
     bytes += align_up((size_t)n_seq * (n / 2) * rb, 256);
@@ -142,9 +142,14 @@ size_t bkv_merge_reduce_workspace_bytes(const bkv_params* p, int64_t n_seq, int6
     return bytes + 256;
 }
 
-int bkv_merge_reduce(const bkv_params* p, const void* K, const void* V, int64_t n_seq, int64_t n,
-                     int64_t seq_base, void* K_out, void* V_out, float* w_out, int32_t* idx_out,
-                     int8_t* signs_out, int32_t* status_out, void* workspace, size_t ws_bytes, void* hip_stream) {
+}  // extern "C"
+
+// T rounds; the last round writes K_out / V_out / w_out with `out_stride` tokens between sequences
+// (idx_out, if given, is always dense [n_seq, n >> T]).
+static int merge_reduce_impl(const bkv_params* p, const void* K, const void* V, int64_t n_seq, int64_t n,
+                             int64_t seq_base, void* K_out, void* V_out, float* w_out, int64_t out_stride,
+                             int32_t* idx_out, int8_t* signs_out, int32_t* status_out, void* workspace,
+                             size_t ws_bytes, void* hip_stream) {
     int rc = check_params(p);
     if (rc) return rc;
     if (n_seq < 0 || n < 0 || seq_base < 0) return BKV_EINVAL;
@@ -159,9 +164,9 @@ int bkv_merge_reduce(const bkv_params* p, const void* K, const void* V, int64_t 
     hipError_t e;
     if (T == 0) {   // nothing to halve: weights 1
         if (idx_out) return BKV_ESHAPE;   // identity indices are not materialised
-        if ((e = bkv::launch_copy_rows(K, K_out, n_seq, n, n, n, (int)rb, st)) != hipSuccess) return hip_fail(e);
-        if ((e = bkv::launch_copy_rows(V, V_out, n_seq, n, n, n, (int)rb, st)) != hipSuccess) return hip_fail(e);
-        if (w_out && (e = bkv::launch_fill_w(w_out, n_seq, n, 0, n, 1.f, st)) != hipSuccess) return hip_fail(e);
+        if ((e = bkv::launch_copy_rows(K, K_out, n_seq, n, out_stride, n, (int)rb, st)) != hipSuccess) return hip_fail(e);
+        if ((e = bkv::launch_copy_rows(V, V_out, n_seq, n, out_stride, n, (int)rb, st)) != hipSuccess) return hip_fail(e);
+        if (w_out && (e = bkv::launch_fill_w(w_out, n_seq, out_stride, 0, n, 1.f, st)) != hipSuccess) return hip_fail(e);
         return BKV_OK;
     }
     const size_t need = bkv_merge_reduce_workspace_bytes(p, n_seq, n);
@@ -178,7 +183,10 @@ int bkv_merge_reduce(const bkv_params* p, const void* K, const void* V, int64_t 
     }
     if (!idx_final) {     // the value gather needs the survivor indices even if the caller does not
         if (T > 1) idx_final = ibuf[(T - 1) & 1];      // free at the last round (its input is the other one)
-        else return BKV_EINVAL;                        // T == 1: idx_out is required
+        else {                                         // T == 1: a small index buffer from the workspace
+            if (!workspace || ws_bytes < need || !aligned16(workspace)) return BKV_EWORKSPACE;
+            idx_final = (int32_t*)workspace;
+        }
     }
     if (status_out && (e = bkv::launch_fill_u32(status_out, 0u, n_seq * T, st)) != hipSuccess) return hip_fail(e);
 
@@ -197,7 +205,8 @@ int bkv_merge_reduce(const bkv_params* p, const void* K, const void* V, int64_t 
         a.idx_out = last ? idx_final : ibuf[r & 1];
         a.signs_out = signs_out ? signs_out + (size_t)n_seq * (size_t)(2 * n - ((2 * n) >> r)) : nullptr;
         a.status_out = status_out; a.status_stride = T;
-        a.in_seq_stride = m; a.out_seq_stride = m / 2; a.blocks_per_seq = (int32_t)(m / b);
+        a.in_seq_stride = m; a.out_seq_stride = last ? out_stride : m / 2; a.idx_out_seq_stride = m / 2;
+        a.blocks_per_seq = (int32_t)(m / b);
         a.tree_mode = 1; a.round = r; a.seq_base = seq_base; a.blk_base = 0;
         a.w_out_val = (float)(1u << (r + 1));
         e = bkv::launch_compress(p->dtype, p->d, false, a, n_seq * (m / b), st);
@@ -205,8 +214,24 @@ int bkv_merge_reduce(const bkv_params* p, const void* K, const void* V, int64_t 
         k_in = a.K_out; i_in = a.idx_out; m /= 2;
     }
     // values of the survivors, gathered once from the original V
-    e = bkv::launch_gather_rows(V, idx_final, V_out, n_seq, n, m, (int)rb, st);
+    e = bkv::launch_gather_rows(V, idx_final, V_out, n_seq, n, out_stride, m, (int)rb, st);
     return e == hipSuccess ? BKV_OK : hip_fail(e);
+}
+
+extern "C" {
+
+int bkv_merge_reduce(const bkv_params* p, const void* K, const void* V, int64_t n_seq, int64_t n,
+                     int64_t seq_base, void* K_out, void* V_out, float* w_out, int32_t* idx_out,
+                     int8_t* signs_out, int32_t* status_out, void* workspace, size_t ws_bytes, void* hip_stream) {
+    if (!p) return BKV_EINVAL;
+    return merge_reduce_impl(p, K, V, n_seq, n, seq_base, K_out, V_out, w_out, n >> (p->rounds & 31), idx_out,
+                             signs_out, status_out, workspace, ws_bytes, hip_stream);
+}
+
+int bkv_profile_enable(int32_t max_records) { return bkv::prof_enable(max_records) == 0 ? BKV_OK : BKV_EHIP; }
+int bkv_profile_read(int32_t* kind, float* ms, int64_t* units, int32_t cap) {
+    if (!kind || !ms || !units || cap < 0) return BKV_EINVAL;
+    return bkv::prof_read(kind, ms, units, cap);
 }
 
 // ------------------------------------------------------------------------------------------ estimator
@@ -291,6 +316,26 @@ int bkv_cache_load(bkv_cache* c, const void* K_c, const void* V_c, const float* 
     return BKV_OK;
 }
 
+size_t bkv_cache_prefill_workspace_bytes(const bkv_cache* c, const bkv_params* p, int64_t n) {
+    if (!c) return 0;
+    return bkv_merge_reduce_workspace_bytes(p, c->n_seq, n);
+}
+
+int bkv_cache_prefill(bkv_cache* c, const bkv_params* p, const void* K, const void* V, int64_t n, int32_t* status_out,
+                      void* workspace, size_t ws_bytes, void* hip_stream) {
+    if (!c || !p) return BKV_EINVAL;
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (p->d != c->p.d || p->dtype != c->p.dtype) return BKV_ESHAPE;
+    if (n < 0 || (n >> p->rounds) > c->cap) return BKV_ECAPACITY;
+    rc = merge_reduce_impl(p, K, V, c->n_seq, n, 0, c->K, c->V, c->w, c->cap, nullptr, nullptr, status_out, workspace,
+                           ws_bytes, hip_stream);
+    if (rc) return rc;
+    c->count = c->base_count = n >> p->rounds;
+    c->stream_j = 0;
+    return BKV_OK;
+}
+
 int bkv_cache_free(bkv_cache* c) {
     if (!c) return BKV_EINVAL;
     delete c;
@@ -347,7 +392,7 @@ int bkv_append_token(bkv_cache* c, const void* k, const void* v, int32_t* status
         a.K = c->K + (size_t)first * rb; a.V = c->V + (size_t)first * rb;
         a.K_out = tmpK; a.V_out = tmpV;
         a.status_out = status_out; a.status_stride = T;
-        a.in_seq_stride = c->cap; a.out_seq_stride = b / 2; a.blocks_per_seq = 1;
+        a.in_seq_stride = c->cap; a.out_seq_stride = a.idx_out_seq_stride = b / 2; a.blocks_per_seq = 1;
         a.tree_mode = 1; a.round = i; a.seq_base = 0;
         a.blk_base = (j / b) / (1ll << i) - 1;           // how many blocks reached level i before this one
         a.w_out_val = (float)(1u << (i + 1));

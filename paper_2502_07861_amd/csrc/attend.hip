@@ -228,9 +228,14 @@ size_t attend_workspace_bytes(int d, int64_t n_seq, int n_q) {
 
 template <typename T, int D>
 static hipError_t launch_attend_t(AttendArgs& a, int64_t n_seq, int n_qg, hipStream_t st) {
-    hipLaunchKernelGGL((attend_partial_kernel<T, D>), dim3(a.n_splits, n_qg, (unsigned)n_seq), dim3(kAttWaves * 64), 0, st, a);
-    hipError_t e = hipGetLastError();
+    hipError_t e;
+    {
+        ProfScope prof(kProfAttend, n_seq * a.count, st);
+        hipLaunchKernelGGL((attend_partial_kernel<T, D>), dim3(a.n_splits, n_qg, (unsigned)n_seq), dim3(kAttWaves * 64), 0, st, a);
+        e = hipGetLastError();
+    }
     if (e != hipSuccess) return e;
+    ProfScope prof(kProfAttendMerge, n_seq * a.n_q, st);
     hipLaunchKernelGGL((attend_merge_kernel<T, D>), dim3(a.n_q, (unsigned)n_seq), dim3(64), 0, st, a, n_qg);
     return hipGetLastError();
 }

@@ -22,7 +22,8 @@ struct CompressArgs {
     const float* uniforms;
     float* G_out;             // kernel-weight dump (EMIT_G variant only)
     int64_t in_seq_stride;    // tokens between consecutive sequences in K / V / idx_in
-    int64_t out_seq_stride;   // tokens between consecutive sequences in K_out / V_out / w_out / idx_out
+    int64_t out_seq_stride;   // tokens between consecutive sequences in K_out / V_out / w_out
+    int64_t idx_out_seq_stride;  // tokens between consecutive sequences in idx_out
     int64_t seq_base;         // added to the sequence number in the generator stream id
     int64_t blk_base;         // added to the block number in the generator counter
     uint64_t seed;
@@ -41,8 +42,8 @@ struct CompressArgs {
 
 size_t compress_lds_bytes(int row_bytes, int b);
 hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64_t n_inst, hipStream_t st);
-hipError_t launch_gather_rows(const void* in, const int32_t* idx, void* out, int64_t n_seq,
-                              int64_t in_seq_stride, int64_t rows_out, int row_bytes, hipStream_t st);
+hipError_t launch_gather_rows(const void* in, const int32_t* idx, void* out, int64_t n_seq, int64_t in_seq_stride,
+                              int64_t out_seq_stride, int64_t rows_out, int row_bytes, hipStream_t st);
 hipError_t launch_fill_u32(void* p, uint32_t v, int64_t n, hipStream_t st);
 hipError_t launch_copy_rows(const void* src, void* dst, int64_t n_seq, int64_t src_seq_stride,
                             int64_t dst_seq_stride, int64_t rows, int row_bytes, hipStream_t st);
@@ -50,6 +51,17 @@ hipError_t launch_copy_f32(const float* src, float* dst, int64_t n_seq, int64_t 
                            int64_t dst_seq_stride, int64_t rows, hipStream_t st);
 hipError_t launch_fill_w(float* w, int64_t n_seq, int64_t seq_stride, int64_t off, int64_t rows, float val,
                          hipStream_t st);
+
+// Opt-in per-launch timing with HIP events on the caller's stream (diagnostics).
+enum { kProfCompress = 0, kProfGather = 1, kProfAttend = 2, kProfAttendMerge = 3 };
+int prof_enable(int n);
+int prof_read(int32_t* kind, float* ms, int64_t* units, int cap);
+struct ProfScope {
+    ProfScope(int kind, int64_t units, hipStream_t st);
+    ~ProfScope();
+    int slot_;
+    hipStream_t st_;
+};
 
 struct AttendArgs {
     const char* K;            // [n_seq, stride_tokens, d]

@@ -413,7 +413,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         if (a.w_out) a.w_out[out_tok0 + r] = a.w_out_val;
         if (a.idx_out) {
             const int src = keptIdx[r];
-            a.idx_out[out_tok0 + r] = a.idx_in ? a.idx_in[in_tok0 + src] : blk * b + src;
+            a.idx_out[seq * a.idx_out_seq_stride + (int64_t)blk * half + r] = a.idx_in ? a.idx_in[in_tok0 + src] : blk * b + src;
         }
     }
 }
@@ -430,6 +430,7 @@ static hipError_t launch_one(const CompressArgs& a, int64_t n_inst, hipStream_t 
         if (e != hipSuccess) return e;
         configured = lds;
     }
+    ProfScope prof(kProfCompress, n_inst * a.b, st);
     hipLaunchKernelGGL(kern, dim3((unsigned)n_inst), dim3(kThreads), lds, st, a);
     return hipGetLastError();
 }
@@ -456,7 +457,7 @@ hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64
 // Row gather: out[seq, r, :] = in[seq, idx[seq, r], :]  (values of the final survivors).
 // ------------------------------------------------------------------------------------------------
 __global__ void gather_rows_kernel(const char* in, const int32_t* idx, char* out, int64_t in_seq_stride,
-                                   int64_t rows_out, int row_bytes, int64_t total_slices) {
+                                   int64_t out_seq_stride, int64_t rows_out, int row_bytes, int64_t total_slices) {
     const int slices = row_bytes >> 4;
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total_slices;
          t += (int64_t)gridDim.x * blockDim.x) {
@@ -464,19 +465,21 @@ __global__ void gather_rows_kernel(const char* in, const int32_t* idx, char* out
         const int s = (int)(t - row * slices);
         const int64_t seq = row / rows_out;
         const int64_t src = seq * in_seq_stride + idx[row];
-        *reinterpret_cast<uintx4*>(out + (size_t)row * row_bytes + s * 16) =
+        const int64_t dst = seq * out_seq_stride + (row - seq * rows_out);
+        *reinterpret_cast<uintx4*>(out + (size_t)dst * row_bytes + s * 16) =
             *reinterpret_cast<const uintx4*>(in + (size_t)src * row_bytes + s * 16);
     }
 }
 
-hipError_t launch_gather_rows(const void* in, const int32_t* idx, void* out, int64_t n_seq,
-                              int64_t in_seq_stride, int64_t rows_out, int row_bytes, hipStream_t st) {
+hipError_t launch_gather_rows(const void* in, const int32_t* idx, void* out, int64_t n_seq, int64_t in_seq_stride,
+                              int64_t out_seq_stride, int64_t rows_out, int row_bytes, hipStream_t st) {
     const int64_t total = n_seq * rows_out * (row_bytes >> 4);
     if (total <= 0) return hipSuccess;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
+    ProfScope prof(kProfGather, n_seq * rows_out, st);
     hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const char*)in, idx,
-                       (char*)out, in_seq_stride, rows_out, row_bytes, total);
+                       (char*)out, in_seq_stride, out_seq_stride, rows_out, row_bytes, total);
     return hipGetLastError();
 }
 
@@ -553,6 +556,50 @@ hipError_t launch_fill_w(float* w, int64_t n_seq, int64_t seq_stride, int64_t of
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(fill_w_kernel, dim3((unsigned)blocks), dim3(256), 0, st, w, seq_stride, off, rows, val, total);
     return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Opt-in per-launch timing (diagnostics): HIP events recorded around kernel launches on the
+// caller's stream.  Disabled unless bkv_profile_enable(n > 0) was called.
+// ------------------------------------------------------------------------------------------------
+namespace {
+struct ProfRec { hipEvent_t a, b; int kind; int64_t units; };
+ProfRec* g_prof = nullptr;
+int g_prof_cap = 0, g_prof_n = 0;
+}  // namespace
+
+int prof_enable(int n) {
+    for (int i = 0; i < g_prof_cap; ++i) { (void)hipEventDestroy(g_prof[i].a); (void)hipEventDestroy(g_prof[i].b); }
+    delete[] g_prof;
+    g_prof = nullptr; g_prof_cap = 0; g_prof_n = 0;
+    if (n <= 0) return 0;
+    g_prof = new ProfRec[n];
+    for (int i = 0; i < n; ++i) {
+        if (hipEventCreate(&g_prof[i].a) != hipSuccess || hipEventCreate(&g_prof[i].b) != hipSuccess) return -1;
+        g_prof_cap = i + 1;
+    }
+    return 0;
+}
+int prof_read(int32_t* kind, float* ms, int64_t* units, int cap) {
+    int n = 0;
+    for (int i = 0; i < g_prof_n && n < cap; ++i) {
+        float t = 0.f;
+        if (hipEventSynchronize(g_prof[i].b) != hipSuccess) break;
+        if (hipEventElapsedTime(&t, g_prof[i].a, g_prof[i].b) != hipSuccess) break;
+        kind[n] = g_prof[i].kind; ms[n] = t; units[n] = g_prof[i].units; ++n;
+    }
+    g_prof_n = 0;
+    return n;
+}
+ProfScope::ProfScope(int kind, int64_t units, hipStream_t st) : slot_(-1), st_(st) {
+    if (g_prof_n < g_prof_cap) {
+        slot_ = g_prof_n++;
+        g_prof[slot_].kind = kind; g_prof[slot_].units = units;
+        (void)hipEventRecord(g_prof[slot_].a, st_);
+    }
+}
+ProfScope::~ProfScope() {
+    if (slot_ >= 0) (void)hipEventRecord(g_prof[slot_].b, st_);
 }
 
 }  // namespace bkv

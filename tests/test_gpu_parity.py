@@ -476,3 +476,31 @@ def test_cache_load_then_stream(bk, synth, oracle):
     assert small.count == 32
     cache.close()
     small.close()
+
+
+def test_cache_prefill_equals_merge_reduce(bk, synth):
+    """Prefill straight into the cache == bkv_merge_reduce followed by bkv_cache_load (one and two rounds)."""
+    d, n_seq, n = 128, 3, 2048
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=n, d=d, g=4, nq=1, seed=8, device="cpu")
+    K, V, Q = t["K"].cuda(), t["V"].cuda(), t["Q"].cuda()
+    for T in (1, 2):
+        pre = bk.make_params(d, 256, T, torch.bfloat16, log_c=-60.0, seed=3, center=True)
+        ref = bk.merge_reduce(pre, K, V)
+        dec = bk.make_params(d, 64, 2, torch.bfloat16, log_c=-60.0, seed=4, center=True)
+        cache = bk.Cache(dec, n_seq, max_tokens=n)
+        status = torch.zeros(n_seq, T, dtype=torch.int32, device="cuda")
+        cache.prefill(pre, K, V, status=status)
+        Kv, Vv, wv = cache.views()
+        cnt = cache.count
+        assert cnt == n >> T
+        assert torch.equal(Kv[:, :cnt], ref["K"]) and torch.equal(Vv[:, :cnt], ref["V"])
+        assert torch.all(wv[:, :cnt] == float(2 ** T)) and torch.all(wv[:, cnt:] == 0)
+        assert torch.equal(status, ref["status"])
+        o1, _ = cache.attend(Q)
+        o2, _ = bk.attend_kv(pre, ref["K"], ref["V"], ref["w"], Q)
+        assert torch.equal(o1, o2)
+        cache.close()
+    with pytest.raises(bk.BkvError) as e:
+        small = bk.Cache(dec, n_seq, max_tokens=256)
+        small.prefill(bk.make_params(d, 256, 1, torch.bfloat16, log_c=0.0), K, V)
+    assert e.value.code == -5

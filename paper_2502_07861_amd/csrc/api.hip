@@ -107,8 +107,8 @@ int bkv_compress_block(const bkv_params* p, const void* K, const void* V, int64_
     a.K = (const char*)K; a.V = (const char*)V; a.K_out = (char*)K_out; a.V_out = (char*)V_out;
     a.w_out = w_out; a.idx_out = idx_out; a.signs_out = signs_out; a.status_out = status_out; a.stats_out = stats_out;
     a.inst_ids = inst_ids; a.uniforms = uniforms;
-    a.in_seq_stride = p->block; a.out_seq_stride = a.idx_out_seq_stride = p->block / 2; a.blocks_per_seq = 1;
-    a.tree_mode = 0; a.w_out_val = 2.f * w_in;
+    a.in_seq_stride = a.v_seq_stride = p->block; a.out_seq_stride = a.idx_out_seq_stride = p->block / 2;
+    a.blocks_per_seq = 1; a.tree_mode = 0; a.w_out_val = 2.f * w_in;
     hipError_t e = bkv::launch_compress(p->dtype, p->d, false, a, n_inst, (hipStream_t)hip_stream);
     return e == hipSuccess ? BKV_OK : hip_fail(e);
 }
@@ -197,9 +197,11 @@ static int merge_reduce_impl(const bkv_params* p, const void* K, const void* V, 
         const bool last = (r == T - 1);
         bkv::CompressArgs a;
         fill_common(a, p);
-        a.K = k_in; a.V = nullptr;
+        a.K = k_in;
         a.K_out = last ? (char*)K_out : kbuf[r & 1];
-        a.V_out = nullptr;
+        a.V = last ? (const char*)V : nullptr;          // values are gathered once, from the original rows
+        a.V_out = last ? (char*)V_out : nullptr;
+        a.v_seq_stride = n;
         a.w_out = last ? w_out : nullptr;
         a.idx_in = i_in;
         a.idx_out = last ? idx_final : ibuf[r & 1];
@@ -213,9 +215,7 @@ static int merge_reduce_impl(const bkv_params* p, const void* K, const void* V, 
         if (e != hipSuccess) return hip_fail(e);
         k_in = a.K_out; i_in = a.idx_out; m /= 2;
     }
-    // values of the survivors, gathered once from the original V
-    e = bkv::launch_gather_rows(V, idx_final, V_out, n_seq, n, out_stride, m, (int)rb, st);
-    return e == hipSuccess ? BKV_OK : hip_fail(e);
+    return BKV_OK;
 }
 
 extern "C" {
@@ -392,7 +392,7 @@ int bkv_append_token(bkv_cache* c, const void* k, const void* v, int32_t* status
         a.K = c->K + (size_t)first * rb; a.V = c->V + (size_t)first * rb;
         a.K_out = tmpK; a.V_out = tmpV;
         a.status_out = status_out; a.status_stride = T;
-        a.in_seq_stride = c->cap; a.out_seq_stride = a.idx_out_seq_stride = b / 2; a.blocks_per_seq = 1;
+        a.in_seq_stride = a.v_seq_stride = c->cap; a.out_seq_stride = a.idx_out_seq_stride = b / 2; a.blocks_per_seq = 1;
         a.tree_mode = 1; a.round = i; a.seq_base = 0;
         a.blk_base = (j / b) / (1ll << i) - 1;           // how many blocks reached level i before this one
         a.w_out_val = (float)(1u << (i + 1));

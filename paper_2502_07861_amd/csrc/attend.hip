@@ -16,17 +16,6 @@ constexpr int kAttWaves = 4;
 constexpr int kUnroll = 4;       // rows in flight per lane group
 constexpr float kNeg = -1.0e30f; // "minus infinity" that stays finite under subtraction
 
-template <int SL> __device__ __forceinline__ float group_sum(float x) {
-    // all-reduce over SL consecutive lanes (SL in {8,16,32}) with DPP adds
-    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
-    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
-    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));  // row_half_mirror
-    if (SL >= 16)
-        x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));  // row_mirror
-    if (SL >= 32) x += __shfl_xor(x, 16);
-    return x;
-}
-
 template <typename T, int D>
 __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const AttendArgs a) {
     constexpr int ROWB = D * (int)sizeof(T);

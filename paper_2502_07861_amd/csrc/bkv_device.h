@@ -95,4 +95,16 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// all-reduce (sum) over SL consecutive lanes, SL in {8,16,32}: DPP adds inside a row of 16 lanes
+template <int SL> __device__ __forceinline__ float group_sum(float x) {
+    // all-reduce over SL consecutive lanes (SL in {8,16,32}) with DPP adds
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));  // row_half_mirror
+    if (SL >= 16)
+        x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));  // row_mirror
+    if (SL >= 32) x += __shfl_xor(x, 16);
+    return x;
+}
+
 }  // namespace bkv

@@ -24,6 +24,7 @@ struct CompressArgs {
     int64_t in_seq_stride;    // tokens between consecutive sequences in K / V / idx_in
     int64_t out_seq_stride;   // tokens between consecutive sequences in K_out / V_out / w_out
     int64_t idx_out_seq_stride;  // tokens between consecutive sequences in idx_out
+    int64_t v_seq_stride;     // tokens between consecutive sequences in V; survivors are read at their ORIGINAL token index
     int64_t seq_base;         // added to the sequence number in the generator stream id
     int64_t blk_base;         // added to the block number in the generator counter
     uint64_t seed;

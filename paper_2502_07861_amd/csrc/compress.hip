@@ -1,23 +1,33 @@
 // SoftmaxBalance (Alg. 2 of arXiv 2502.07861) on gfx950: Gram tiles on MFMA, kernel weights and
 // the self-balancing walk on chip, strict halving, gather of the survivors.
 //
-// One workgroup (8 wavefronts) owns one block of b tokens.  The block's keys are staged in LDS in
-// chunks of up to kChunkRows rows.  The walk is organised right-looking over 64-row panels:
+// One workgroup (8 wavefronts) owns one block of b tokens; its keys are staged in LDS in chunks of
+// up to kChunkRows rows.  The walk is organised over 64-token panels.  sigma[l] (LDS) accumulates
+// sum_{i signed so far} eta_i g_il for every column l.  Wavefront 0 is the walker: for panel I it
+// reads the strictly-upper part of the 64x64 diagonal tile of kernel weights as "one column per
+// lane" registers and takes the 64 sequential decisions of Alg. 2 (lane j compares sigma_j with
+// 1 - 2 u_j; its outcome is broadcast with a readlane and every later lane adds eta_j g_jl).
+// Wavefronts 1..7 form tiles on MFMA while the walker walks, in a static schedule:
 //
-//   sigma[l] (LDS) holds sum_{i already signed} eta_i g_il for every column l of the block.
-//   For panel I:  wavefront 0 forms the 64x64 diagonal tile of kernel weights, transposes it into
-//                 "one column per lane" registers and runs the 64 sequential decisions
-//                 (lane j compares sigma_j with 1 - 2 u_j; the outcome is broadcast with a ballot);
-//                 then all wavefronts form the tiles (I, J), J > I, multiply row i by eta_i, sum
-//                 over rows and add the column sums into sigma[J].
-//   Rows of earlier chunks (b larger than one chunk) are streamed from global memory as the
-//   A operand against the resident chunk before its own panels are walked.
+//   superstep I:   walker            walk(I)
+//                  wave 1            diagonal tile of panel I+1  -> LDS (double buffered)
+//                  wave 2            tile (I, I+1) without signs, kept in registers
+//                  waves 3..7 (,1)   tiles (I-1, J), J > I: multiply row i by eta_i, sum over rows,
+//                                    add the column sums into sigma[J]          (eta_{I-1} is known)
+//                  barrier; wave 2 applies eta_I to its tile -> sigma[I+1]; barrier
 //
-// The kernel weight is g_ij = exp((<k_i,k_j> - a_i - a_j + |mu|^2 - A)/sqrt(d) - ln c) with
-// a_i = <k_i, mu> (mu = block mean when keys are centred, else 0) and A = r_key^2 or the largest
-// centred squared norm: Alg. 2's y_i / (c R^2), v = 1, never forming R^2.  The accumulator of each
-// tile is initialised with t_i + t_j, t_i = -a_i + (|mu|^2 - A - sqrt(d) ln c)/2, so that the
-// exponent is a single multiply of the MFMA result.
+// so the only work between two walks is one signed column sum.  Rows of earlier chunks (b larger
+// than one chunk) are streamed from global memory as the A operand against the resident chunk
+// before its own panels are walked.
+//
+// Kernel weight: g_ij = exp((<k_i,k_j> - a_i - a_j + |mu|^2 - A)/sqrt(d) - ln c), a_i = <k_i,mu>
+// (mu = block mean when keys are centred, else 0), A = r_key^2 or the largest centred squared norm:
+// Alg. 2's y_i / (c R^2) with v = 1, never forming R^2.  It is evaluated as
+// exp2(alpha <k_i,k_j> - alpha a_i + rc) * exp2(-alpha a_j) with alpha = log2(e)/sqrt(d) and
+// rc = alpha (|mu|^2 - A) - ln c log2(e), so that each entry costs one FMA and one exp2 and the
+// column factor is applied once per column sum.
+#include <utility>
+
 #include "bkv_device.h"
 #include "bkv_host.h"
 
@@ -28,24 +38,26 @@ template <typename T, int D> struct Geo {
     static constexpr int kLdsRow = kRowBytes + 16;          // +16 B: conflict-free 16-byte reads
     static constexpr int kGroups = kRowBytes / 32;          // k-groups of 32 bytes per row
     static constexpr int kSlices = kRowBytes / 16;          // 16-byte slices per row
-    static constexpr int kChunkRows = kRowBytes == 128 ? 1024 : (kRowBytes == 256 ? 512 : 256);
 };
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
+constexpr int kDiagFloats = 63 * 64;                        // rows 0..62 of a 64x64 diagonal tile (row 63 is never read)
+
+static inline int chunk_rows_for(int row_bytes, int b) {
+    const int chunk_max = row_bytes <= 256 ? 512 : 256;
+    return b < chunk_max ? b : chunk_max;
+}
 
 size_t compress_lds_bytes(int row_bytes, int b) {
-    int chunk_max = row_bytes == 128 ? 1024 : (row_bytes == 256 ? 512 : 256);
-    int ch = b < chunk_max ? b : chunk_max;
-    size_t bytes = (size_t)ch * (row_bytes + 16);
-    if (bytes < 16384) bytes = 16384;   // the chunk region doubles as scratch for the mean reduction
-    bytes += (size_t)b * 4 * 2;      // sigma, t
-    bytes += 16 * 8;                 // eta masks
-    bytes += (size_t)(b / 2) * 4;    // survivor list
-    bytes += (size_t)row_bytes * 4;  // mu (fp32, at most row_bytes/2 entries; generous)
-    bytes += 256;                    // scalars / wave partials
+    size_t bytes = (size_t)chunk_rows_for(row_bytes, b) * (row_bytes + 16);
+    bytes += (size_t)b * 4 * 2;          // sigma, aterm
+    bytes += 16 * 8;                     // eta of each panel, packed for the accumulator layout
+    bytes += kDiagFloats * 4;            // diagonal tile (also: mean partials, survivor list)
+    bytes += 64;                         // scalars
     return bytes;
 }
+
 
 template <typename T, int D>
 struct TileOps {
@@ -62,23 +74,12 @@ struct TileOps {
                 F[g][rb] = *reinterpret_cast<const Frag*>(base + (size_t)(32 * rb + n) * row_stride + 32 * g + 16 * h);
     }
 
-    // acc[rb][cb] = t_row + t_col, then += A_I * B_J^T with B read from LDS rows ldsB[0..63].
+    // acc = A_I * B_J^T with B read from LDS rows ldsB[0..63].
     // Accumulator layout (32x32 MFMA): register r of lane (n,h) is row 8*(r/4) + 4*h + r%4, column n.
     static __device__ __forceinline__ void gram(floatx16 (&acc)[2][2], const Frag (&A)[G::kGroups][2],
-                                                const char* ldsB, const float* t_rows,
-                                                const float* t_cols, int n, int h) {
-        float tc[2] = {t_cols[n], t_cols[32 + n]};
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                floatx4 tr = *reinterpret_cast<const floatx4*>(t_rows + 32 * rb + 8 * q + 4 * h);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    acc[rb][0][4 * q + e] = tr[e] + tc[0];
-                    acc[rb][1][4 * q + e] = tr[e] + tc[1];
-                }
-            }
+                                                const char* ldsB, int n, int h) {
+        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        acc[0][0] = zero; acc[0][1] = zero; acc[1][0] = zero; acc[1][1] = zero;    // folds into the first MFMA's C operand
 #pragma unroll
         for (int g = 0; g < G::kGroups; ++g) {
             Frag b0 = *reinterpret_cast<const Frag*>(ldsB + (size_t)n * G::kLdsRow + 32 * g + 16 * h);
@@ -89,8 +90,91 @@ struct TileOps {
             Elem<T>::mma(acc[1][1], A[g][1], b1);
         }
     }
+
+    // acc <- exp2(alpha * acc + rterm[row])  (kernel weight without the column factor)
+    static __device__ __forceinline__ void weights(floatx16 (&acc)[2][2], const float* aterm_panel, float alpha, int h) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const floatx4 at = *reinterpret_cast<const floatx4*>(aterm_panel + 32 * rb + 8 * q + 4 * h);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc[rb][0][4 * q + e] = fast_exp2(fmaf(acc[rb][0][4 * q + e], alpha, at[e]));
+                    acc[rb][1][4 * q + e] = fast_exp2(fmaf(acc[rb][1][4 * q + e], alpha, at[e]));
+                }
+            }
+    }
+
+    // sum over the 64 rows of eta_row * weight, per column; returns this lane's column 32*h + n
+    // (before the column factor).  The signs of a row panel come packed for this register layout:
+    // word h holds, at bit 16*rb + r, the sign of row 32*rb + 8*(r/4) + 4*h + r%4 (1 = '+').
+    static __device__ __forceinline__ float signed_colsum(const floatx16 (&v)[2][2], uint2 packed, int h) {
+        const unsigned int nb = ~(h ? packed.y : packed.x);          // bit set = '-'
+        float cs0 = 0.f, cs1 = 0.f;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int k = 16 * rb + r;
+                const float sg = __uint_as_float(((nb << (31 - k)) & 0x80000000u) | 0x3f800000u);   // +1 or -1
+                cs0 = fmaf(sg, v[rb][0][r], cs0);
+                cs1 = fmaf(sg, v[rb][1][r], cs1);
+            }
+        cs0 += __shfl_xor(cs0, 32);
+        cs1 += __shfl_xor(cs1, 32);
+        return h ? cs1 : cs0;
+    }
+    // v (a diagonal tile, column factors e0/e1 applied here) -> LDS [row][col], rows 0..62
+    static __device__ __forceinline__ void store_diag(float* diag, const floatx16 (&v)[2][2], float e0, float e1, int n, int h) {
+        float* dst = diag + (4 * h) * 64 + n;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row0 = 32 * rb + 8 * (r >> 2) + (r & 3);            // + 4*h
+                if (row0 + 4 < 63 || h == 0) {                                // row 63 has no later column
+                    dst[row0 * 64] = v[rb][0][r] * e0;
+                    dst[row0 * 64 + 32] = v[rb][1][r] * e1;
+                }
+            }
+    }
+    // eta mask of a panel (bit j = 1 iff eta_j = +1) -> the two packed words above
+    static __device__ __forceinline__ uint2 pack_signs(unsigned long long m) {
+        unsigned int lo = 0, hi = 0;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            lo |= (unsigned int)((m >> (8 * t)) & 0xFull) << (4 * t);
+            hi |= (unsigned int)((m >> (8 * t + 4)) & 0xFull) << (4 * t);
+        }
+        return make_uint2(lo, hi);
+    }
+    static __device__ __forceinline__ unsigned long long unpack_signs(uint2 pk) {
+        unsigned long long m = 0;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            m |= (unsigned long long)((pk.x >> (4 * t)) & 0xFu) << (8 * t);
+            m |= (unsigned long long)((pk.y >> (4 * t)) & 0xFu) << (8 * t + 4);
+        }
+        return m;
+    }
 };
 
+// One decision of the walk (Alg. 2 lines 5-9 for token j of the panel): every lane compares its sigma
+// with its threshold, lane j's outcome is picked out of the compare mask on the scalar unit and comes
+// back as the scalar +1/-1 that multiplies row j of the diagonal tile.  Two vector instructions per
+// step; lanes <= j hold g[j] = 0, so their sigma stays at its decision-time value.
+template <int J>
+__device__ __forceinline__ void walk_step(float& sv, float tau, const float (&g)[64]) {
+    float sg;
+    asm volatile("v_cmp_lt_f32 vcc, %1, %2\n\ts_bitcmp1_b64 vcc, %3\n\ts_cselect_b32 %0, 1.0, -1.0"
+                 : "=s"(sg) : "v"(sv), "v"(tau), "n"(J) : "vcc", "scc");
+    sv = fmaf(sg, g[J], sv);
+}
+template <int... Js>
+__device__ __forceinline__ void walk_panel(float& sv, float tau, const float (&g)[64], std::integer_sequence<int, Js...>) {
+    (walk_step<Js>(sv, tau, g), ...);
+}
 
 template <typename T, int D, bool EMIT_G>
 __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a) {
@@ -99,21 +183,23 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     typedef typename Elem<T>::Frag Frag;
     constexpr int EPL = Elem<T>::kPerFrag;
     constexpr int SL = G::kSlices;
-    constexpr int RG = kThreads / SL;
+    constexpr int RG = kThreads / SL;          // row groups: rows handled concurrently by the workgroup
+    constexpr int GPW = 64 / SL;               // row groups per wavefront
 
     extern __shared__ __align__(16) char smem[];
     const int b = a.b, nP = b >> 6, CH = a.chunk_rows;
     char* ldsK = smem;
-    const size_t chunk_bytes = (size_t)CH * G::kLdsRow < 16384 ? 16384 : (size_t)CH * G::kLdsRow;
-    float* sigma = reinterpret_cast<float*>(smem + chunk_bytes);
-    float* tterm = sigma + b;
-    unsigned long long* etaMask = reinterpret_cast<unsigned long long*>(tterm + b);
-    int* keptIdx = reinterpret_cast<int*>(etaMask + 16);
-    float* mu = reinterpret_cast<float*>(keptIdx + b / 2);
-    float* scal = mu + D;                       // [0] |mu|^2, [1] A, [8..8+kWaves) wave partials
-    float* scratch = reinterpret_cast<float*>(ldsK);   // aliases the key chunk before it is loaded
+    float* sigma = reinterpret_cast<float*>(smem + (size_t)CH * G::kLdsRow);
+    float* aterm = sigma + b;                                      // -alpha * a_i; column factor = exp2(aterm)
+    uint2* etaPack = reinterpret_cast<uint2*>(aterm + b);          // signs of each panel, packed for the accumulator layout
+    float* diag = reinterpret_cast<float*>(etaPack + 16);          // [63][64]
+    float* scal = diag + kDiagFloats;                              // [0] |mu|^2, [1] A, [2..2+kWaves) partial maxima
+    float* mu = diag;                                              // [D]          (statistics phase only)
+    float* wpart = diag + 128;                                     // [kWaves][D]  (statistics phase only)
+    int* keptIdx = reinterpret_cast<int*>(diag);                   // [b/2]        (output phase only)
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: roles branch on scalars
     const int n = lane & 31, h = lane >> 5;
     const int64_t inst = blockIdx.x;
     const int64_t seq = inst / a.blocks_per_seq;
@@ -123,81 +209,11 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     const char* Kin = a.K + in_tok0 * G::kRowBytes;
     const int sl = tid % SL, rg = tid / SL;
     const bool center = (a.flags & BKV_CENTER_KEYS) != 0;
+    const bool need_norm = !(a.rkey2 > 0.f);
+    const bool single_chunk = (CH == b);
+    const float alpha = a.alpha;
+    float* Gi = EMIT_G ? a.G_out + (size_t)inst * b * b : nullptr;
 
-    // ------------------------------------------------------------------ block statistics
-    // mu = mean key (fp32), a_i = <k_i, mu>, |k_i|^2, A = max centred squared norm.
-    if (center) {
-        float part[EPL];
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) part[e] = 0.f;
-        for (int i = rg; i < b; i += RG) {
-            uintx4 raw = *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
-            float f[EPL];
-            Elem<T>::unpack(raw, f);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) part[e] += f[e];
-        }
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) scratch[rg * D + sl * EPL + e] = part[e];
-        __syncthreads();
-        if (tid < D) {
-            float s = 0.f;
-            for (int r = 0; r < RG; ++r) s += scratch[r * D + tid];
-            mu[tid] = s / (float)b;
-        }
-        __syncthreads();
-        if (wave == 0) {
-            float s = 0.f;
-            for (int c = lane; c < D; c += 64) s += mu[c] * mu[c];
-            s = wave_sum(s);
-            if (lane == 0) scal[0] = s;
-        }
-    } else {
-        if (tid < D) mu[tid] = 0.f;
-        if (tid == 0) scal[0] = 0.f;
-    }
-    __syncthreads();
-    const float mumu = scal[0];
-    {
-        float mloc[EPL];
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) mloc[e] = mu[sl * EPL + e];
-        float amax = -3.0e38f;
-        const bool need_norm = !(a.rkey2 > 0.f);
-        if (center || need_norm) {
-            for (int i = rg; i < b; i += RG) {
-                uintx4 raw = *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
-                float f[EPL];
-                Elem<T>::unpack(raw, f);
-                float pa = 0.f, pn = 0.f;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) { pa += f[e] * mloc[e]; pn += f[e] * f[e]; }
-#pragma unroll
-                for (int o = SL / 2; o > 0; o >>= 1) { pa += __shfl_xor(pa, o); pn += __shfl_xor(pn, o); }
-                if (sl == 0) tterm[i] = pa;                       // a_i for now
-                amax = fmaxf(amax, pn - 2.f * pa + mumu);
-            }
-            amax = wave_max(amax);
-            if (lane == 0) scal[8 + wave] = amax;
-        } else {
-            for (int i = tid; i < b; i += kThreads) tterm[i] = 0.f;
-        }
-        __syncthreads();
-        if (tid == 0) {
-            float A = a.rkey2;
-            if (need_norm) {
-                A = scal[8];
-                for (int w = 1; w < kWaves; ++w) A = fmaxf(A, scal[8 + w]);
-            }
-            scal[1] = A;
-        }
-        __syncthreads();
-        const float half_const = 0.5f * (mumu - scal[1] + a.cterm);
-        for (int i = tid; i < b; i += kThreads) {
-            tterm[i] = half_const - tterm[i];
-            sigma[i] = 0.f;
-        }
-    }
     // generator stream of this instance
     uint64_t stream = a.tree_mode ? (uint64_t)(64 * (a.seq_base + seq) + a.round) : (uint64_t)inst;
     if (a.inst_ids) stream = a.inst_ids[inst];
@@ -208,16 +224,130 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     int n_margin = 0, any_fail = 0;
     float min_margin = 3.0e38f, max_sigma = 0.f;
 
+    // 16-byte slice `sl` of row i: from the resident chunk (single-chunk blocks) or from global memory
+    auto row_slice = [&](int i) -> uintx4 {
+        if (single_chunk) return *reinterpret_cast<const uintx4*>(ldsK + (size_t)i * G::kLdsRow + sl * 16);
+        return *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
+    };
+
     const int n_chunks = (b + CH - 1) / CH;
     for (int c = 0; c < n_chunks; ++c) {
         const int row0 = c * CH;                       // first row of the chunk
-        const int p0 = row0 >> 6, p1 = min(nP, (row0 + CH) >> 6);
-        __syncthreads();                               // previous users of ldsK / scratch are done
-        for (int i = rg; i < CH && row0 + i < b; i += RG) {
-            uintx4 raw = *reinterpret_cast<const uintx4*>(Kin + (size_t)(row0 + i) * G::kRowBytes + sl * 16);
-            *reinterpret_cast<uintx4*>(ldsK + (size_t)i * G::kLdsRow + sl * 16) = raw;
+        const int rows_here = min(CH, b - row0);
+        const int p0 = row0 >> 6, p1 = (row0 + rows_here) >> 6;
+        __syncthreads();                               // previous users of ldsK are done
+        {
+            constexpr int U = 8;
+            for (int i0 = rg; i0 < rows_here; i0 += RG * U) {
+                uintx4 raw[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int i = i0 + u * RG;
+                    if (i < rows_here) raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)(row0 + i) * G::kRowBytes + sl * 16);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int i = i0 + u * RG;
+                    if (i < rows_here) *reinterpret_cast<uintx4*>(ldsK + (size_t)i * G::kLdsRow + sl * 16) = raw[u];
+                }
+            }
         }
         __syncthreads();
+
+        if (c == 0) {
+            // ---------------------------------------------------------- block statistics
+            // mu = mean key (fp32), a_i = <k_i, mu>, A = largest centred squared norm (or r_key^2)
+            if (center) {
+                float part[EPL];
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) part[e] = 0.f;
+                constexpr int U = 8;
+                for (int i0 = rg; i0 < b; i0 += RG * U) {
+                    uintx4 raw[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) raw[u] = row_slice(min(i0 + u * RG, b - 1));
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        float f[EPL];
+                        Elem<T>::unpack(raw[u], f);
+                        if (i0 + u * RG < b)
+#pragma unroll
+                            for (int e = 0; e < EPL; ++e) part[e] += f[e];
+                    }
+                }
+#pragma unroll
+                for (int o = SL; o < 64; o <<= 1)
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) part[e] += __shfl_xor(part[e], o);
+                if (lane < SL)
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) wpart[wave * D + sl * EPL + e] = part[e];
+                __syncthreads();
+                if (tid < D) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) s += wpart[w * D + tid];
+                    mu[tid] = s / (float)b;
+                }
+                __syncthreads();
+                if (wave == 0) {
+                    float s = 0.f;
+                    for (int cc = lane; cc < D; cc += 64) s += mu[cc] * mu[cc];
+                    s = wave_sum(s);
+                    if (lane == 0) scal[0] = s;
+                }
+            } else {
+                if (tid < D) mu[tid] = 0.f;
+                if (tid == 0) scal[0] = 0.f;
+            }
+            __syncthreads();
+            const float mumu = scal[0];
+            if (center || need_norm) {
+                float mloc[EPL];
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) mloc[e] = mu[sl * EPL + e];
+                float amax = -3.0e38f;
+                constexpr int U = 4;
+                for (int i0 = rg; i0 < b; i0 += RG * U) {          // b is a multiple of 64 >= RG; rows past b are skipped
+                    uintx4 raw[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) raw[u] = row_slice(min(i0 + u * RG, b - 1));
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int i = i0 + u * RG;
+                        float f[EPL];
+                        Elem<T>::unpack(raw[u], f);
+                        float pa = 0.f, pn = 0.f;
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) { pa = fmaf(f[e], mloc[e], pa); pn = fmaf(f[e], f[e], pn); }
+                        pa = group_sum<SL>(pa);
+                        pn = group_sum<SL>(pn);
+                        if (i < b) {
+                            if (sl == 0) aterm[i] = -alpha * pa;
+                            amax = fmaxf(amax, pn - 2.f * pa + mumu);
+                        }
+                    }
+                }
+                amax = wave_max(amax);
+                if (lane == 0) scal[2 + wave] = amax;
+            } else {
+                for (int i = tid; i < b; i += kThreads) aterm[i] = 0.f;
+            }
+            __syncthreads();                                        // mu / wpart (aliasing diag) are dead from here
+            {
+                float A = a.rkey2;
+                if (need_norm) {
+                    A = scal[2];
+#pragma unroll
+                    for (int w = 1; w < kWaves; ++w) A = fmaxf(A, scal[2 + w]);
+                }
+                const float rc = alpha * (mumu - A + a.cterm);       // row constant of the exponent
+                for (int i = tid; i < b; i += kThreads) { aterm[i] += rc; sigma[i] = 0.f; }
+                if (tid == 0) scal[1] = rc;
+            }
+            __syncthreads();
+        }
+        const float row_const = scal[1];
 
         // ---------------------------------------------------------- rows of earlier chunks
         if (c > 0) {
@@ -228,143 +358,197 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     Frag A[G::kGroups][2];
                     Ops::load_frags(A, Kin + (size_t)(I << 6) * G::kRowBytes, G::kRowBytes, n, h);
                     floatx16 acc[2][2];
-                    Ops::gram(acc, A, ldsB, tterm + (I << 6), tterm + (J << 6), n, h);
-                    const unsigned long long em = etaMask[I] >> (4 * h);
-                    float cs0 = 0.f, cs1 = 0.f;
+                    Ops::gram(acc, A, ldsB, n, h);
+                    Ops::weights(acc, aterm + (I << 6), alpha, h);
+                    if (EMIT_G) {
+                        const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
 #pragma unroll
-                    for (int rb = 0; rb < 2; ++rb)
+                        for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int bit = 32 * rb + 8 * (r >> 2) + (r & 3);
-                            const float sg = ((em >> bit) & 1ull) ? 1.f : -1.f;
-                            const float v0 = fast_exp2(a.alpha * acc[rb][0][r]);
-                            const float v1 = fast_exp2(a.alpha * acc[rb][1][r]);
-                            cs0 = fmaf(sg, v0, cs0);
-                            cs1 = fmaf(sg, v1, cs1);
-                            if (EMIT_G) {
-                                const int row = (I << 6) + bit + 4 * h;
-                                float* Gi = a.G_out + (size_t)inst * b * b;
-                                Gi[(size_t)row * b + (J << 6) + n] = v0;
-                                Gi[(size_t)row * b + (J << 6) + 32 + n] = v1;
-                                Gi[(size_t)((J << 6) + n) * b + row] = v0;
-                                Gi[(size_t)((J << 6) + 32 + n) * b + row] = v1;
+                            for (int r = 0; r < 16; ++r) {
+                                const int row = (I << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+                                Gi[(size_t)row * b + (J << 6) + n] = acc[rb][0][r] * e0;
+                                Gi[(size_t)row * b + (J << 6) + 32 + n] = acc[rb][1][r] * e1;
+                                Gi[(size_t)((J << 6) + n) * b + row] = acc[rb][0][r] * e0;
+                                Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r] * e1;
                             }
-                        }
-                    cs0 += __shfl_xor(cs0, 32);
-                    cs1 += __shfl_xor(cs1, 32);
-                    csum += h ? cs1 : cs0;
+                    }
+                    csum += Ops::signed_colsum(acc, etaPack[I], h);
                 }
-                sigma[(J << 6) + lane] += csum;
+                sigma[(J << 6) + lane] = fmaf(csum, fast_exp2(aterm[(J << 6) + lane] - row_const), sigma[(J << 6) + lane]);
             }
-            __syncthreads();
         }
-
-        // ---------------------------------------------------------- panels of this chunk
-        for (int I = p0; I < p1; ++I) {
-            const char* ldsA = ldsK + (size_t)((I << 6) - row0) * G::kLdsRow;
-            if (wave == 0) {
-                // diagonal tile -> one column per lane
-                Frag A[G::kGroups][2];
-                Ops::load_frags(A, ldsA, G::kLdsRow, n, h);
-                floatx16 acc[2][2];
-                Ops::gram(acc, A, ldsA, tterm + (I << 6), tterm + (I << 6), n, h);
-                float g[64];
+        // diagonal tile of the chunk's first panel
+        if (wave == 1) {
+            const char* ldsA = ldsK + (size_t)((p0 << 6) - row0) * G::kLdsRow;
+            Frag A[G::kGroups][2];
+            Ops::load_frags(A, ldsA, G::kLdsRow, n, h);
+            floatx16 acc[2][2];
+            Ops::gram(acc, A, ldsA, n, h);
+            Ops::weights(acc, aterm + (p0 << 6), alpha, h);
+            const float e0 = fast_exp2(aterm[(p0 << 6) + n] - row_const), e1 = fast_exp2(aterm[(p0 << 6) + 32 + n] - row_const);
+            Ops::store_diag(diag, acc, e0, e1, n, h);
+            if (EMIT_G) {
 #pragma unroll
                 for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const float v0 = fast_exp2(a.alpha * acc[rb][0][r]);
-                        const float v1 = fast_exp2(a.alpha * acc[rb][1][r]);
-                        if (EMIT_G) {
-                            const int row = (I << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-                            float* Gi = a.G_out + (size_t)inst * b * b;
-                            Gi[(size_t)row * b + (I << 6) + n] = v0;
-                            Gi[(size_t)row * b + (I << 6) + 32 + n] = v1;
-                        }
-                        // my column is 32*h + n: rows of pattern h are mine, pattern 1-h sit in lane^32
-                        const float mine = h ? v1 : v0;
-                        const float send = h ? v0 : v1;
-                        const float recv = __shfl_xor(send, 32);
-                        const int j_same = 32 * rb + 8 * (r >> 2) + (r & 3);   // + 4*h
-                        // rows j_same + 4*h (mine) and j_same + 4*(1-h) (received)
-                        g[j_same] = h ? recv : mine;          // row j_same     has pattern 0
-                        g[j_same + 4] = h ? mine : recv;      // row j_same + 4 has pattern 1
+                        const int row = 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+                        Gi[(size_t)((p0 << 6) + row) * b + (p0 << 6) + n] = acc[rb][0][r] * e0;
+                        Gi[(size_t)((p0 << 6) + row) * b + (p0 << 6) + 32 + n] = acc[rb][1][r] * e1;
                     }
-#pragma unroll
-                for (int j = 0; j < 64; ++j) g[j] = (j < lane) ? g[j] : 0.f;   // strictly earlier rows only
+            }
+        }
+        __syncthreads();
 
+        // ---------------------------------------------------------- panels of this chunk
+        // Every wavefront passes exactly two barriers per superstep; the three roles keep their
+        // registers apart by living in separate branches.
+        if (wave == 0) {
+            for (int I = p0; I < p1; ++I) {
+                // ------------------------------------------------ the walk over panel I (Alg. 2 lines 4-10)
+                int ln = lane;
+                asm volatile("" : "+v"(ln));                  // keep the 63 lane masks local to this panel
+                const float* src = diag + ln;
+                float g[64];
+#pragma unroll
+                for (int j = 0; j < 63; ++j) {
+                    const float v = src[j * 64];              // row j of the tile, this lane's column
+                    g[j] = (ln > j) ? v : 0.f;                // strictly earlier tokens only
+                }
+                g[63] = 0.f;
                 float sv = sigma[(I << 6) + lane];
                 float u;
                 if (a.uniforms) u = a.uniforms[(size_t)inst * b + (I << 6) + lane];
                 else u = (float)draw_bits_keyed(key, ctr0 + (uint64_t)((I << 6) + lane)) * (1.0f / 16777216.0f);
                 const float tau = 1.f - 2.f * u;              // eta = +1  <=>  u < 1/2 - sigma/2  <=>  sigma < tau
-#pragma unroll
-                for (int j = 0; j < 64; ++j) {
-                    const unsigned long long m = __ballot(sv < tau);
-                    const float sg = ((m >> j) & 1ull) ? 1.f : -1.f;
-                    sv = fmaf(sg, g[j], sv);
-                }
+                __builtin_amdgcn_s_setprio(3);                // the serial chain goes first on its SIMD
+                walk_panel(sv, tau, g, std::make_integer_sequence<int, 64>{});
+                __builtin_amdgcn_s_setprio(0);
                 const unsigned long long m = __ballot(sv < tau);
-                if (lane == 0) etaMask[I] = m;
+                if (lane == 0) etaPack[I] = Ops::pack_signs(m);
                 any_fail |= (__ballot(fabsf(sv) > 1.f) != 0ull);
                 const float margin = 0.5f * fabsf(fminf(fmaxf(sv, -1.f), 1.f) - tau);   // |u - clamp(p)|
                 n_margin += __popcll(__ballot(margin < 1e-4f));
                 min_margin = fminf(min_margin, margin);
                 max_sigma = fmaxf(max_sigma, fabsf(sv));
+                __syncthreads();                               // eta_I is visible
+                __syncthreads();                               // sigma[I+1] is complete
             }
-            __syncthreads();
-            if (I + 1 + wave < p1) {
-                Frag A[G::kGroups][2];
-                Ops::load_frags(A, ldsA, G::kLdsRow, n, h);
-                const unsigned long long em = etaMask[I] >> (4 * h);
-                float sgn[2][16];
-#pragma unroll
-                for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        sgn[rb][r] = ((em >> (32 * rb + 8 * (r >> 2) + (r & 3))) & 1ull) ? 1.f : -1.f;
-                for (int J = I + 1 + wave; J < p1; J += kWaves) {
+        } else if (wave == 2) {
+            for (int I = p0; I + 1 < p1; ++I) {
+                // ------------------------------------------------ tile (I, I+1): weights now, signs after the walk
+                const int J = I + 1;
+                floatx16 held[2][2];
+                {
+                    const char* ldsA = ldsK + (size_t)((I << 6) - row0) * G::kLdsRow;
                     const char* ldsB = ldsK + (size_t)((J << 6) - row0) * G::kLdsRow;
-                    floatx16 acc[2][2];
-                    Ops::gram(acc, A, ldsB, tterm + (I << 6), tterm + (J << 6), n, h);
-                    float cs0 = 0.f, cs1 = 0.f;
+                    Frag A[G::kGroups][2];
+                    Ops::load_frags(A, ldsA, G::kLdsRow, n, h);
+                    Ops::gram(held, A, ldsB, n, h);
+                    Ops::weights(held, aterm + (I << 6), alpha, h);
+                }
+                __syncthreads();                               // eta_I is visible
+                if (EMIT_G) {
+                    const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
 #pragma unroll
                     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
-                            const float v0 = fast_exp2(a.alpha * acc[rb][0][r]);
-                            const float v1 = fast_exp2(a.alpha * acc[rb][1][r]);
-                            cs0 = fmaf(sgn[rb][r], v0, cs0);
-                            cs1 = fmaf(sgn[rb][r], v1, cs1);
-                            if (EMIT_G) {
-                                const int row = (I << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-                                float* Gi = a.G_out + (size_t)inst * b * b;
-                                Gi[(size_t)row * b + (J << 6) + n] = v0;
-                                Gi[(size_t)row * b + (J << 6) + 32 + n] = v1;
-                                Gi[(size_t)((J << 6) + n) * b + row] = v0;
-                                Gi[(size_t)((J << 6) + 32 + n) * b + row] = v1;
-                            }
+                            const int row = (I << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+                            Gi[(size_t)row * b + (J << 6) + n] = held[rb][0][r] * e0;
+                            Gi[(size_t)row * b + (J << 6) + 32 + n] = held[rb][1][r] * e1;
+                            Gi[(size_t)((J << 6) + n) * b + row] = held[rb][0][r] * e0;
+                            Gi[(size_t)((J << 6) + 32 + n) * b + row] = held[rb][1][r] * e1;
                         }
-                    cs0 += __shfl_xor(cs0, 32);
-                    cs1 += __shfl_xor(cs1, 32);
-                    sigma[(J << 6) + lane] += h ? cs1 : cs0;
                 }
+                const float cs = Ops::signed_colsum(held, etaPack[I], h);
+                sigma[(J << 6) + lane] = fmaf(cs, fast_exp2(aterm[(J << 6) + lane] - row_const), sigma[(J << 6) + lane]);
+                __syncthreads();                               // sigma[I+1] is complete
             }
+            __syncthreads();                                   // last panel of the chunk: nothing to prepare
             __syncthreads();
+        } else if (wave == 1) {
+            for (int I = p0; I + 1 < p1; ++I) {
+                // ------------------------------------------------ diagonal tile of panel I+1, stored once the walker has read tile I
+                floatx16 dv[2][2];
+                {
+                    const char* ldsA = ldsK + (size_t)(((I + 1) << 6) - row0) * G::kLdsRow;
+                    Frag A[G::kGroups][2];
+                    Ops::load_frags(A, ldsA, G::kLdsRow, n, h);
+                    Ops::gram(dv, A, ldsA, n, h);
+                    Ops::weights(dv, aterm + ((I + 1) << 6), alpha, h);
+                }
+                __syncthreads();                               // eta_I is visible; the walker is done with the diagonal tile
+                const float e0 = fast_exp2(aterm[((I + 1) << 6) + n] - row_const), e1 = fast_exp2(aterm[((I + 1) << 6) + 32 + n] - row_const);
+                Ops::store_diag(diag, dv, e0, e1, n, h);
+                if (EMIT_G) {
+#pragma unroll
+                    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int row = 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+                            Gi[(size_t)(((I + 1) << 6) + row) * b + ((I + 1) << 6) + n] = dv[rb][0][r] * e0;
+                            Gi[(size_t)(((I + 1) << 6) + row) * b + ((I + 1) << 6) + 32 + n] = dv[rb][1][r] * e1;
+                        }
+                }
+                __syncthreads();                               // sigma[I+1] and the next diagonal tile are complete
+            }
+            __syncthreads();                                   // last panel of the chunk: nothing to prepare
+            __syncthreads();
+        } else {
+            for (int I = p0; I < p1; ++I) {
+                const bool has_next = I + 1 < p1;
+                const int nC = (I > p0 && has_next) ? p1 - I - 1 : 0;       // tiles (I-1, J), J = I+1 .. p1-1
+                // tiles (I-1, J): wave 3+k takes J = I+1+k, and again every fifth J after that
+                const int c_first = wave - 3, c_step = kWaves - 3;
+                if (c_first < nC) {
+                    const char* ldsA = ldsK + (size_t)(((I - 1) << 6) - row0) * G::kLdsRow;
+                    const uint2 em = etaPack[I - 1];
+                    Frag A[G::kGroups][2];
+                    Ops::load_frags(A, ldsA, G::kLdsRow, n, h);
+                    for (int cj = c_first; cj < nC; cj += c_step) {
+                        const int J = I + 1 + cj;
+                        const char* ldsB = ldsK + (size_t)((J << 6) - row0) * G::kLdsRow;
+                        floatx16 acc[2][2];
+                        Ops::gram(acc, A, ldsB, n, h);
+                        Ops::weights(acc, aterm + ((I - 1) << 6), alpha, h);
+                        if (EMIT_G) {
+                            const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
+#pragma unroll
+                            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                                for (int r = 0; r < 16; ++r) {
+                                    const int row = ((I - 1) << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+                                    Gi[(size_t)row * b + (J << 6) + n] = acc[rb][0][r] * e0;
+                                    Gi[(size_t)row * b + (J << 6) + 32 + n] = acc[rb][1][r] * e1;
+                                    Gi[(size_t)((J << 6) + n) * b + row] = acc[rb][0][r] * e0;
+                                    Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r] * e1;
+                                }
+                        }
+                        const float cs = Ops::signed_colsum(acc, em, h);
+                        sigma[(J << 6) + lane] = fmaf(cs, fast_exp2(aterm[(J << 6) + lane] - row_const), sigma[(J << 6) + lane]);
+                    }
+                }
+                __syncthreads();                               // eta_I is visible
+                __syncthreads();                               // sigma[I+1] is complete
+            }
         }
     }
 
     // ------------------------------------------------------------------ output step (Alg. 2 lines 12-16 + strict n/2)
     if (wave == 0) {
         int n_plus = 0;
-        for (int p = 0; p < nP; ++p) n_plus += __popcll(etaMask[p]);
+        for (int p = 0; p < nP; ++p) n_plus += __popc(etaPack[p].x) + __popc(etaPack[p].y);
         const bool plus_is_minority = n_plus <= b - n_plus;               // tie -> '+'
         const int n_min = plus_is_minority ? n_plus : b - n_plus;
         const int need = b / 2 - n_min;                                   // majority tokens to add, lowest index first
         int maj_before = 0, kept_before = 0;
         const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
         for (int p = 0; p < nP; ++p) {
-            const unsigned long long m = etaMask[p];
+            const uint2 pk = etaPack[p];
+            const unsigned long long m = Ops::unpack_signs(make_uint2(__builtin_amdgcn_readfirstlane(pk.x),
+                                                                      __builtin_amdgcn_readfirstlane(pk.y)));
             const unsigned long long minm = plus_is_minority ? m : ~m;
             const unsigned long long majm = ~minm;
             const int my_rank = maj_before + __popcll(majm & lt);
@@ -373,8 +557,13 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             if (keep) keptIdx[kept_before + __popcll(km & lt)] = (p << 6) + lane;
             maj_before += __popcll(majm);
             kept_before += __popcll(km);
-            if (a.signs_out) a.signs_out[(size_t)inst * b + (p << 6) + lane] = ((m >> lane) & 1ull) ? 1 : -1;
         }
+    }
+    __syncthreads();
+    if (wave == 0) {      // side outputs: issued after the barrier so that nobody waits for these stores
+        if (a.signs_out)
+            for (int p = 0; p < nP; ++p)
+                a.signs_out[(size_t)inst * b + (p << 6) + lane] = ((Ops::unpack_signs(etaPack[p]) >> lane) & 1ull) ? 1 : -1;
         min_margin = wave_min(min_margin);
         max_sigma = wave_max(max_sigma);
         if (lane == 0) {
@@ -394,27 +583,50 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             }
         }
     }
-    __syncthreads();
     const int half = b >> 1;
+    // survivors: rows of the ORIGINAL keys / values, ascending index (16-byte slices, several rows in flight)
+    auto src_token = [&](int r) -> int64_t {      // token of survivor r within its sequence, in the value tensor's frame
+        const int kept = keptIdx[r];
+        return a.idx_in ? (int64_t)a.idx_in[in_tok0 + kept] : (int64_t)blk * b + kept;
+    };
     if (a.K_out) {
         char* Ko = a.K_out + out_tok0 * G::kRowBytes;
-        for (int r = rg; r < half; r += RG)
-            *reinterpret_cast<uintx4*>(Ko + (size_t)r * G::kRowBytes + sl * 16) =
-                *reinterpret_cast<const uintx4*>(Kin + (size_t)keptIdx[r] * G::kRowBytes + sl * 16);
+        constexpr int U = 4;
+        for (int r0 = rg; r0 < half; r0 += RG * U) {
+            uintx4 raw[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int r = r0 + u * RG;
+                if (r < half) raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)keptIdx[r] * G::kRowBytes + sl * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int r = r0 + u * RG;
+                if (r < half) *reinterpret_cast<uintx4*>(Ko + (size_t)r * G::kRowBytes + sl * 16) = raw[u];
+            }
+        }
     }
     if (a.V_out && a.V) {
-        const char* Vin = a.V + in_tok0 * G::kRowBytes;
+        const char* Vseq = a.V + (size_t)seq * a.v_seq_stride * G::kRowBytes;
         char* Vo = a.V_out + out_tok0 * G::kRowBytes;
-        for (int r = rg; r < half; r += RG)
-            *reinterpret_cast<uintx4*>(Vo + (size_t)r * G::kRowBytes + sl * 16) =
-                *reinterpret_cast<const uintx4*>(Vin + (size_t)keptIdx[r] * G::kRowBytes + sl * 16);
+        constexpr int U = 4;
+        for (int r0 = rg; r0 < half; r0 += RG * U) {
+            uintx4 raw[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int r = r0 + u * RG;
+                if (r < half) raw[u] = *reinterpret_cast<const uintx4*>(Vseq + (size_t)src_token(r) * G::kRowBytes + sl * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int r = r0 + u * RG;
+                if (r < half) *reinterpret_cast<uintx4*>(Vo + (size_t)r * G::kRowBytes + sl * 16) = raw[u];
+            }
+        }
     }
     for (int r = tid; r < half; r += kThreads) {
         if (a.w_out) a.w_out[out_tok0 + r] = a.w_out_val;
-        if (a.idx_out) {
-            const int src = keptIdx[r];
-            a.idx_out[seq * a.idx_out_seq_stride + (int64_t)blk * half + r] = a.idx_in ? a.idx_in[in_tok0 + src] : blk * b + src;
-        }
+        if (a.idx_out) a.idx_out[seq * a.idx_out_seq_stride + (int64_t)blk * half + r] = (int32_t)src_token(r);
     }
 }
 
@@ -437,8 +649,7 @@ static hipError_t launch_one(const CompressArgs& a, int64_t n_inst, hipStream_t 
 
 hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64_t n_inst, hipStream_t st) {
     const int row_bytes = d * (dtype == BKV_BF16 ? 2 : 4);
-    const int chunk_max = row_bytes == 128 ? 1024 : (row_bytes == 256 ? 512 : 256);
-    a.chunk_rows = a.b < chunk_max ? a.b : chunk_max;
+    a.chunk_rows = chunk_rows_for(row_bytes, a.b);
     if (n_inst <= 0) return hipSuccess;
     // grids are one-dimensional; split very large launches
     const int64_t kMaxGrid = 1ll << 30;

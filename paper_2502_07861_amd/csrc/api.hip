@@ -375,9 +375,7 @@ int bkv_append_token(bkv_cache* c, const void* k, const void* v, int32_t* status
     }
     hipError_t e;
     // C^0 <- C^0 U {(k_j, v_j)}, weight 1
-    if ((e = bkv::launch_copy_rows(k, c->K + (size_t)c->count * rb, c->n_seq, 1, c->cap, 1, rb, st)) != hipSuccess) return hip_fail(e);
-    if ((e = bkv::launch_copy_rows(v, c->V + (size_t)c->count * rb, c->n_seq, 1, c->cap, 1, rb, st)) != hipSuccess) return hip_fail(e);
-    if ((e = bkv::launch_fill_w(c->w, c->n_seq, c->cap, c->count, 1, 1.f, st)) != hipSuccess) return hip_fail(e);
+    if ((e = bkv::launch_append(k, v, c->K, c->V, c->w, c->n_seq, c->cap, c->count, rb, st)) != hipSuccess) return hip_fail(e);
     c->count += 1;
     c->stream_j = j;
     if (halvings == 0) return 0;

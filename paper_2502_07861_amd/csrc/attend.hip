@@ -14,6 +14,7 @@ namespace bkv {
 constexpr int kQT = 4;           // query vectors per pass over the cache
 constexpr int kAttWaves = 4;
 constexpr int kUnroll = 4;       // rows in flight per lane group
+constexpr int kTargetWGs = 4096;   // workgroups of the streaming pass when the token range is split
 constexpr float kNeg = -1.0e30f; // "minus infinity" that stays finite under subtraction
 
 template <typename T, int D>
@@ -37,19 +38,14 @@ __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const At
     const char* Vb = a.V + (size_t)seq * a.stride_tokens * ROWB;
     const float* wb = a.w + (size_t)seq * a.stride_tokens;
 
-    float qf[kQT][EPL];
+    // queries of this pass: raw 16-byte slices (bf16 path: consumed by packed dot products) and, for
+    // fp32, the unpacked values; the logit scale log2(e)/sqrt(d) is applied to the reduced dot product
+    uintx4 qraw[kQT];
 #pragma unroll
     for (int qi = 0; qi < kQT; ++qi) {
         const int q = qg * kQT + qi;
-        if (q < a.n_q) {
-            uintx4 raw = *reinterpret_cast<const uintx4*>(a.Q + ((size_t)seq * a.n_q + q) * ROWB + sl * 16);
-            Elem<T>::unpack(raw, qf[qi]);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) qf[qi][e] *= a.scale_log2;
-        } else {
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) qf[qi][e] = 0.f;
-        }
+        qraw[qi] = (q < a.n_q) ? *reinterpret_cast<const uintx4*>(a.Q + ((size_t)seq * a.n_q + q) * ROWB + sl * 16)
+                               : uintx4{0u, 0u, 0u, 0u};
     }
     float m[kQT], l[kQT], o[kQT][EPL];
 #pragma unroll
@@ -59,36 +55,32 @@ __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const At
         for (int e = 0; e < EPL; ++e) o[qi][e] = 0.f;
     }
 
-    for (int64_t base = r_begin; base < r_end; base += ROWS_IT) {
-        uintx4 kraw[kUnroll], vraw[kUnroll];
-        float wv[kUnroll];
-        bool ok[kUnroll];
+    struct Batch { uintx4 k[kUnroll], v[kUnroll]; float w[kUnroll]; };
+    auto issue = [&](Batch& t, int64_t base) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int64_t row = base + (u * kAttWaves + wave) * RPW + lg;
-            ok[u] = row < r_end;
-            const int64_t rr = ok[u] ? row : r_end - 1;          // stay in bounds; masked below
-            kraw[u] = *reinterpret_cast<const uintx4*>(Kb + (size_t)rr * ROWB + sl * 16);
-            vraw[u] = *reinterpret_cast<const uintx4*>(Vb + (size_t)rr * ROWB + sl * 16);
-            wv[u] = wb[rr];
+            const int64_t rr = row < r_end ? row : r_end - 1;          // stay in bounds; masked in consume()
+            t.k[u] = *reinterpret_cast<const uintx4*>(Kb + (size_t)rr * ROWB + sl * 16);
+            t.v[u] = *reinterpret_cast<const uintx4*>(Vb + (size_t)rr * ROWB + sl * 16);
+            t.w[u] = wb[rr];
         }
+    };
+    auto consume = [&](const Batch& t, int64_t base) {
         float lg2[kUnroll][kQT];
         float mb[kQT];
 #pragma unroll
         for (int qi = 0; qi < kQT; ++qi) mb[qi] = kNeg;
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            float kf[EPL];
-            Elem<T>::unpack(kraw[u], kf);
-            const bool live = ok[u] && wv[u] > 0.f;
-            const float bias = live ? __builtin_amdgcn_logf(wv[u]) : 0.f;    // v_log_f32 = log2
+            const int64_t row = base + (u * kAttWaves + wave) * RPW + lg;
+            const bool live = row < r_end && t.w[u] > 0.f;
+            const float bias = live ? __builtin_amdgcn_logf(t.w[u]) : 0.f;    // v_log_f32 = log2
 #pragma unroll
             for (int qi = 0; qi < kQT; ++qi) {
-                float part = 0.f;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) part = fmaf(qf[qi][e], kf[e], part);
+                float part = Elem<T>::dot(qraw[qi], t.k[u]);
                 part = group_sum<SL>(part);
-                lg2[u][qi] = live ? part + bias : kNeg;
+                lg2[u][qi] = live ? fmaf(part, a.scale_log2, bias) : kNeg;
                 mb[qi] = fmaxf(mb[qi], lg2[u][qi]);
             }
         }
@@ -104,13 +96,27 @@ __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const At
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             float vf[EPL];
-            Elem<T>::unpack(vraw[u], vf);
+            Elem<T>::unpack(t.v[u], vf);
 #pragma unroll
             for (int qi = 0; qi < kQT; ++qi) {
                 const float p = (lg2[u][qi] > 0.5f * kNeg) ? fast_exp2(lg2[u][qi] - m[qi]) : 0.f;
                 l[qi] += p;
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) o[qi][e] = fmaf(p, vf[e], o[qi][e]);
+            }
+        }
+    };
+
+    // two batches of rows in flight: the loads of the next batch are issued before the current one is consumed
+    if (r_begin < r_end) {
+        Batch b0, b1;
+        issue(b0, r_begin);
+        for (int64_t base = r_begin; base < r_end; base += 2 * ROWS_IT) {
+            if (base + ROWS_IT < r_end) issue(b1, base + ROWS_IT);
+            consume(b0, base);
+            if (base + ROWS_IT < r_end) {
+                if (base + 2 * ROWS_IT < r_end) issue(b0, base + 2 * ROWS_IT);
+                consume(b1, base + ROWS_IT);
             }
         }
     }
@@ -157,33 +163,56 @@ __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const At
     }
 }
 
-// One workgroup per (sequence, query): merge the split partials, normalise, store.
+// One workgroup (2 wavefronts) per (sequence, query): merge the split partials, normalise, store.
+constexpr int kMergeThreads = 128;
+constexpr int kScaleCache = 512;
 template <typename T, int D>
-__global__ __launch_bounds__(64) void attend_merge_kernel(const AttendArgs a, int n_qgroups) {
+__global__ __launch_bounds__(kMergeThreads) void attend_merge_kernel(const AttendArgs a, int n_qgroups) {
+    __shared__ float red[4];
+    __shared__ float scale[kScaleCache];
     const int64_t seq = blockIdx.y;
-    const int q = blockIdx.x;
+    const int q = blockIdx.x, tid = threadIdx.x, ns = a.n_splits;
     const int qg = q / kQT, qi = q % kQT;
-    const float* src = a.partial + (((size_t)seq * n_qgroups + qg) * a.n_splits * kQT) * (D + 2);
-    float M = kNeg;
-    for (int s = 0; s < a.n_splits; ++s) M = fmaxf(M, src[((size_t)s * kQT + qi) * (D + 2) + D]);
-    float L = 0.f;
-    for (int s = 0; s < a.n_splits; ++s) {
-        const float* p = src + ((size_t)s * kQT + qi) * (D + 2);
-        L += p[D + 1] * fast_exp2(p[D] - M);
+    const float* src = a.partial + ((((size_t)seq * n_qgroups + qg) * ns) * kQT + qi) * (D + 2);
+    const size_t sstride = (size_t)kQT * (D + 2);                  // between consecutive splits
+    // largest running maximum over the splits
+    float m = kNeg;
+    for (int s = tid; s < ns; s += kMergeThreads) m = fmaxf(m, src[s * sstride + D]);
+    m = wave_max(m);
+    if ((tid & 63) == 0) red[tid >> 6] = m;
+    __syncthreads();
+    const float M = fmaxf(red[0], red[1]);
+    // denominators, rescaled; the per-split factors are kept for the numerator pass
+    float l = 0.f;
+    for (int s = tid; s < ns; s += kMergeThreads) {
+        const float sc = fast_exp2(src[s * sstride + D] - M);
+        l = fmaf(src[s * sstride + D + 1], sc, l);
+        if (s < kScaleCache) scale[s] = sc;
     }
+    l = wave_sum(l);
+    if ((tid & 63) == 0) red[2 + (tid >> 6)] = l;
+    __syncthreads();
+    const float L = red[2] + red[3];
     const float inv = L > 0.f ? 1.f / L : 0.f;
-    for (int c = threadIdx.x; c < D; c += 64) {
+    for (int c = tid; c < D; c += kMergeThreads) {
         float acc = 0.f;
-        for (int s = 0; s < a.n_splits; ++s) {
-            const float* p = src + ((size_t)s * kQT + qi) * (D + 2);
-            acc += p[c] * fast_exp2(p[D] - M);
+        int s = 0;
+        for (; s + 4 <= ns && s + 4 <= kScaleCache; s += 4) {      // four independent loads in flight
+            const float p0 = src[(s + 0) * sstride + c], p1 = src[(s + 1) * sstride + c];
+            const float p2 = src[(s + 2) * sstride + c], p3 = src[(s + 3) * sstride + c];
+            acc = fmaf(p0, scale[s], acc); acc = fmaf(p1, scale[s + 1], acc);
+            acc = fmaf(p2, scale[s + 2], acc); acc = fmaf(p3, scale[s + 3], acc);
+        }
+        for (; s < ns; ++s) {
+            const float sc = s < kScaleCache ? scale[s] : fast_exp2(src[s * sstride + D] - M);
+            acc = fmaf(src[s * sstride + c], sc, acc);
         }
         const float z = acc * inv;
         const size_t oi = ((size_t)seq * a.n_q + q) * D + c;
         if (sizeof(T) == 2) reinterpret_cast<unsigned short*>(a.out)[oi] = (unsigned short)f32_to_bf16_bits(z);
         else reinterpret_cast<float*>(a.out)[oi] = z;
     }
-    if (a.lse_out && threadIdx.x == 0)
+    if (a.lse_out && tid == 0)
         a.lse_out[(size_t)seq * a.n_q + q] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f : -INFINITY;
 }
 
@@ -193,8 +222,8 @@ static void attend_plan(int d, int dtype_bytes, int64_t n_seq, int64_t count, in
     const int rows_it = kAttWaves * (64 / sl) * kUnroll;
     *n_qg = (n_q + kQT - 1) / kQT;
     int64_t wgs = n_seq * (*n_qg);
-    int64_t want = wgs > 0 ? (2048 + wgs - 1) / wgs : 1;
-    int64_t max_splits = (count + 4 * rows_it - 1) / (4 * rows_it);
+    int64_t want = wgs > 0 ? (kTargetWGs + wgs - 1) / wgs : 1;
+    int64_t max_splits = (count + 2 * rows_it - 1) / (2 * rows_it);
     if (max_splits < 1) max_splits = 1;
     if (want > max_splits) want = max_splits;
     if (want < 1) want = 1;
@@ -208,10 +237,10 @@ static void attend_plan(int d, int dtype_bytes, int64_t n_seq, int64_t count, in
 }
 
 size_t attend_workspace_bytes(int d, int64_t n_seq, int n_q) {
-    // the split count never exceeds ceil(2048 / workgroups-without-splitting), whatever the token count
+    // the split count never exceeds ceil(kTargetWGs / workgroups-without-splitting), whatever the token count
     const int64_t n_qg = (n_q + kQT - 1) / kQT;
     const int64_t wgs = n_seq * n_qg;
-    const int64_t ns = wgs > 0 ? (2048 + wgs - 1) / wgs : 1;
+    const int64_t ns = wgs > 0 ? (kTargetWGs + wgs - 1) / wgs : 1;
     return (size_t)(wgs * ns) * kQT * (d + 2) * sizeof(float) + 256;
 }
 
@@ -225,7 +254,7 @@ static hipError_t launch_attend_t(AttendArgs& a, int64_t n_seq, int n_qg, hipStr
     }
     if (e != hipSuccess) return e;
     ProfScope prof(kProfAttendMerge, n_seq * a.n_q, st);
-    hipLaunchKernelGGL((attend_merge_kernel<T, D>), dim3(a.n_q, (unsigned)n_seq), dim3(64), 0, st, a, n_qg);
+    hipLaunchKernelGGL((attend_merge_kernel<T, D>), dim3(a.n_q, (unsigned)n_seq), dim3(kMergeThreads), 0, st, a, n_qg);
     return hipGetLastError();
 }
 

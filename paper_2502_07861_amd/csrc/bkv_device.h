@@ -55,6 +55,17 @@ template <> struct Elem<__bf16> {
             f[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
         }
     }
+    // dot product of two 16-byte slices (8 bf16 each), fp32 accumulation: v_dot2c_f32_bf16
+    static __device__ __forceinline__ float dot(const uintx4& a, const uintx4& b) {
+        typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+        float acc = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const unsigned int ai = a[i], bi = b[i];      // scalars first: bit-casting a vector element directly picks element 0
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, ai), __builtin_bit_cast(bf16x2_t, bi), acc, false);
+        }
+        return acc;
+    }
 };
 
 template <> struct Elem<float> {
@@ -67,6 +78,12 @@ template <> struct Elem<float> {
     static __device__ __forceinline__ void unpack(const uintx4& raw, float (&f)[4]) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(raw[i]);
+    }
+    static __device__ __forceinline__ float dot(const uintx4& a, const uintx4& b) {
+        float acc = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc = fmaf(__uint_as_float(a[i]), __uint_as_float(b[i]), acc);
+        return acc;
     }
 };
 

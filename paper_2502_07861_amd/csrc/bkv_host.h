@@ -48,6 +48,8 @@ hipError_t launch_gather_rows(const void* in, const int32_t* idx, void* out, int
 hipError_t launch_fill_u32(void* p, uint32_t v, int64_t n, hipStream_t st);
 hipError_t launch_copy_rows(const void* src, void* dst, int64_t n_seq, int64_t src_seq_stride,
                             int64_t dst_seq_stride, int64_t rows, int row_bytes, hipStream_t st);
+hipError_t launch_append(const void* k, const void* v, void* K, void* V, float* w, int64_t n_seq, int64_t seq_stride,
+                         int64_t pos, int row_bytes, hipStream_t st);
 hipError_t launch_copy_f32(const float* src, float* dst, int64_t n_seq, int64_t src_seq_stride,
                            int64_t dst_seq_stride, int64_t rows, hipStream_t st);
 hipError_t launch_fill_w(float* w, int64_t n_seq, int64_t seq_stride, int64_t off, int64_t rows, float val,

@@ -752,6 +752,31 @@ hipError_t launch_copy_f32(const float* src, float* dst, int64_t n_seq, int64_t 
     return hipGetLastError();
 }
 
+// One streamed token per sequence: K[seq, pos, :] = k[seq, :], V likewise, w[seq, pos] = 1 (Alg. 3: C^0 gets the new pair).
+__global__ void append_kernel(const char* k, const char* v, char* K, char* V, float* w, int64_t seq_stride, int64_t pos,
+                              int row_bytes, int64_t n_seq) {
+    const int slices = row_bytes >> 4;
+    const int64_t total = n_seq * slices;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t seq = t / slices;
+        const int s = (int)(t - seq * slices);
+        const size_t dst = (size_t)(seq * seq_stride + pos) * row_bytes + s * 16;
+        *reinterpret_cast<uintx4*>(K + dst) = *reinterpret_cast<const uintx4*>(k + (size_t)seq * row_bytes + s * 16);
+        *reinterpret_cast<uintx4*>(V + dst) = *reinterpret_cast<const uintx4*>(v + (size_t)seq * row_bytes + s * 16);
+        if (s == 0) w[seq * seq_stride + pos] = 1.f;
+    }
+}
+hipError_t launch_append(const void* k, const void* v, void* K, void* V, float* w, int64_t n_seq, int64_t seq_stride,
+                         int64_t pos, int row_bytes, hipStream_t st) {
+    const int64_t total = n_seq * (row_bytes >> 4);
+    if (total <= 0) return hipSuccess;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(append_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const char*)k, (const char*)v, (char*)K,
+                       (char*)V, w, seq_stride, pos, row_bytes, n_seq);
+    return hipGetLastError();
+}
+
 // w[seq, off + r] = val for r < rows
 __global__ void fill_w_kernel(float* w, int64_t seq_stride, int64_t off, int64_t rows, float val, int64_t total) {
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {

@@ -72,6 +72,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a plain 1 GiB device copy 5 times and exit (reference for FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus %d is not supported (the path shards over "
@@ -80,11 +82,22 @@ def main():
 
     import torch
 
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, device="cuda", dtype=torch.uint8).random_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read_per_launch": 1 << 30, "bytes_written_per_launch": 1 << 30,
+                                               "launches": 5, "kernel": "torch elementwise copy (uint8, 1 GiB)"}}))
+        return
+
     import paper_2502_07861_amd as bk
     from paper_2502_07861_amd import binding, synth
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
     bk.lib()
     cfg = dict(synth.WORKLOADS[args.workload])
     nq_bench = 1                       # one decode step: the GQA group of g queries per KV head

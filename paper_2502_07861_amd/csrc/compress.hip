@@ -42,22 +42,26 @@ template <typename T, int D> struct Geo {
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
-constexpr int kDiagFloats = 63 * 64;                        // rows 0..62 of a 64x64 diagonal tile (row 63 is never read)
+constexpr int kDiagStride = 68;                             // floats per column of the transposed diagonal tile (16-byte rows, conflict-free)
+constexpr int kDiagFloats = 64 * kDiagStride;
+constexpr int kLdsLimit = 160 * 1024;
 
+static inline size_t lds_fixed_bytes(int b) {
+    return (size_t)b * 4 * 2             // sigma, aterm
+           + 16 * 8                      // eta of each panel, packed for the accumulator layout
+           + kDiagFloats * 4             // diagonal tile (also: mean partials, survivor list)
+           + 64;                         // scalars
+}
+// rows of the block staged in LDS at a time: as many 64-row panels as fit, at most 8
 static inline int chunk_rows_for(int row_bytes, int b) {
-    const int chunk_max = row_bytes <= 256 ? 512 : 256;
-    return b < chunk_max ? b : chunk_max;
+    int rows = 512;
+    while (rows > 64 && (size_t)rows * (row_bytes + 16) + lds_fixed_bytes(b) > (size_t)kLdsLimit) rows -= 64;
+    return b < rows ? b : rows;
 }
 
 size_t compress_lds_bytes(int row_bytes, int b) {
-    size_t bytes = (size_t)chunk_rows_for(row_bytes, b) * (row_bytes + 16);
-    bytes += (size_t)b * 4 * 2;          // sigma, aterm
-    bytes += 16 * 8;                     // eta of each panel, packed for the accumulator layout
-    bytes += kDiagFloats * 4;            // diagonal tile (also: mean partials, survivor list)
-    bytes += 64;                         // scalars
-    return bytes;
+    return (size_t)chunk_rows_for(row_bytes, b) * (row_bytes + 16) + lds_fixed_bytes(b);
 }
-
 
 template <typename T, int D>
 struct TileOps {
@@ -125,19 +129,29 @@ struct TileOps {
         cs1 += __shfl_xor(cs1, 32);
         return h ? cs1 : cs0;
     }
-    // v (a diagonal tile, column factors e0/e1 applied here) -> LDS [row][col], rows 0..62
-    static __device__ __forceinline__ void store_diag(float* diag, const floatx16 (&v)[2][2], float e0, float e1, int n, int h) {
-        float* dst = diag + (4 * h) * 64 + n;
+    // Diagonal tile: apply the column factors and zero everything that is not strictly above the diagonal
+    // (the walk only ever adds eta_j * g_jl for l > j) ...
+    static __device__ __forceinline__ void mask_diag(floatx16 (&v)[2][2], float e0, float e1, int n, int h) {
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row0 = 32 * rb + 8 * (r >> 2) + (r & 3);            // + 4*h
-                if (row0 + 4 < 63 || h == 0) {                                // row 63 has no later column
-                    dst[row0 * 64] = v[rb][0][r] * e0;
-                    dst[row0 * 64 + 32] = v[rb][1][r] * e1;
-                }
+                const int row = 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+                v[rb][0][r] = (n > row) ? v[rb][0][r] * e0 : 0.f;
+                v[rb][1][r] = (32 + n > row) ? v[rb][1][r] * e1 : 0.f;
             }
+    }
+    // ... and store it transposed, diag[col * kDiagStride + row]: four consecutive rows per 16-byte store.
+    static __device__ __forceinline__ void store_diag(float* diag, const floatx16 (&v)[2][2], int n, int h) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    floatx4 t = {v[rb][cb][4 * q], v[rb][cb][4 * q + 1], v[rb][cb][4 * q + 2], v[rb][cb][4 * q + 3]};
+                    *reinterpret_cast<floatx4*>(diag + (32 * cb + n) * kDiagStride + 32 * rb + 8 * q + 4 * h) = t;
+                }
     }
     // eta mask of a panel (bit j = 1 iff eta_j = +1) -> the two packed words above
     static __device__ __forceinline__ uint2 pack_signs(unsigned long long m) {
@@ -160,20 +174,20 @@ struct TileOps {
     }
 };
 
-// One decision of the walk (Alg. 2 lines 5-9 for token j of the panel): every lane compares its sigma
-// with its threshold, lane j's outcome is picked out of the compare mask on the scalar unit and comes
+// One decision of the walk (Alg. 2 lines 5-9 for token j of the panel): every lane tests the sign of its
+// sigma (which carries the threshold, see the kernel), lane j's outcome is picked out of the compare mask on the scalar unit and comes
 // back as the scalar +1/-1 that multiplies row j of the diagonal tile.  Two vector instructions per
 // step; lanes <= j hold g[j] = 0, so their sigma stays at its decision-time value.
 template <int J>
-__device__ __forceinline__ void walk_step(float& sv, float tau, const float (&g)[64]) {
+__device__ __forceinline__ void walk_step(float& sv, const float (&g)[64]) {
     float sg;
-    asm volatile("v_cmp_lt_f32 vcc, %1, %2\n\ts_bitcmp1_b64 vcc, %3\n\ts_cselect_b32 %0, 1.0, -1.0"
-                 : "=s"(sg) : "v"(sv), "v"(tau), "n"(J) : "vcc", "scc");
+    asm volatile("v_cmp_gt_f32 vcc, 0, %1\n\ts_bitcmp1_b64 vcc, %2\n\ts_cselect_b32 %0, 1.0, -1.0"
+                 : "=s"(sg) : "v"(sv), "n"(J) : "vcc", "scc");
     sv = fmaf(sg, g[J], sv);
 }
 template <int... Js>
-__device__ __forceinline__ void walk_panel(float& sv, float tau, const float (&g)[64], std::integer_sequence<int, Js...>) {
-    (walk_step<Js>(sv, tau, g), ...);
+__device__ __forceinline__ void walk_panel(float& sv, const float (&g)[64], std::integer_sequence<int, Js...>) {
+    (walk_step<Js>(sv, g), ...);
 }
 
 template <typename T, int D, bool EMIT_G>
@@ -192,10 +206,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     float* sigma = reinterpret_cast<float*>(smem + (size_t)CH * G::kLdsRow);
     float* aterm = sigma + b;                                      // -alpha * a_i; column factor = exp2(aterm)
     uint2* etaPack = reinterpret_cast<uint2*>(aterm + b);          // signs of each panel, packed for the accumulator layout
-    float* diag = reinterpret_cast<float*>(etaPack + 16);          // [63][64]
+    float* diag = reinterpret_cast<float*>(etaPack + 16);          // [64 columns][kDiagStride], transposed
     float* scal = diag + kDiagFloats;                              // [0] |mu|^2, [1] A, [2..2+kWaves) partial maxima
-    float* mu = diag;                                              // [D]          (statistics phase only)
-    float* wpart = diag + 128;                                     // [kWaves][D]  (statistics phase only)
+    float* wpart = diag;                                           // [RG][D] <= 4096 floats (statistics phase only)
+    float* mu = diag + 4096;                                       // [D]                    (statistics phase only)
     int* keptIdx = reinterpret_cast<int*>(diag);                   // [b/2]        (output phase only)
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -220,15 +234,41 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     const uint64_t key = stream_key(a.seed, stream);
     const uint64_t ctr0 = a.tree_mode ? (uint64_t)(a.blk_base + blk) * (uint64_t)b : 0ull;
 
-    // walk statistics (wave 0)
-    int n_margin = 0, any_fail = 0;
-    float min_margin = 3.0e38f, max_sigma = 0.f;
+    // decision threshold of token i: eta_i = +1 <=> u_i < 1/2 - s_i/2 <=> s_i < 1 - 2 u_i (exact in fp32)
+    auto threshold = [&](int i) -> float {
+        float u;
+        if (a.uniforms) u = a.uniforms[(size_t)inst * b + i];
+        else u = (float)draw_bits_keyed(key, ctr0 + (uint64_t)i) * (1.0f / 16777216.0f);
+        return 1.f - 2.f * u;
+    };
 
     // 16-byte slice `sl` of row i: from the resident chunk (single-chunk blocks) or from global memory
     auto row_slice = [&](int i) -> uintx4 {
         if (single_chunk) return *reinterpret_cast<const uintx4*>(ldsK + (size_t)i * G::kLdsRow + sl * 16);
         return *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
     };
+
+    // column sums for the block mean, accumulated while rows pass through the registers
+    float part[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) part[e] = 0.f;
+    if (center && !single_chunk) {                       // blocks larger than a chunk: one streaming pass up front
+        constexpr int U = 8;
+        for (int i0 = rg; i0 < b; i0 += RG * U) {
+            uintx4 raw[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)min(i0 + u * RG, b - 1) * G::kRowBytes + sl * 16);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float f[EPL];
+                Elem<T>::unpack(raw[u], f);
+                if (i0 + u * RG < b)
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) part[e] += f[e];
+            }
+        }
+    }
 
     const int n_chunks = (b + CH - 1) / CH;
     for (int c = 0; c < n_chunks; ++c) {
@@ -238,6 +278,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         __syncthreads();                               // previous users of ldsK are done
         {
             constexpr int U = 8;
+            const bool acc_mean = center && single_chunk;
             for (int i0 = rg; i0 < rows_here; i0 += RG * U) {
                 uintx4 raw[U];
 #pragma unroll
@@ -248,60 +289,41 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int i = i0 + u * RG;
-                    if (i < rows_here) *reinterpret_cast<uintx4*>(ldsK + (size_t)i * G::kLdsRow + sl * 16) = raw[u];
+                    if (i < rows_here) {
+                        *reinterpret_cast<uintx4*>(ldsK + (size_t)i * G::kLdsRow + sl * 16) = raw[u];
+                        if (acc_mean) {
+                            float f[EPL];
+                            Elem<T>::unpack(raw[u], f);
+#pragma unroll
+                            for (int e = 0; e < EPL; ++e) part[e] += f[e];
+                        }
+                    }
                 }
             }
         }
+        if (c == 0 && center)                          // partial column sums of every row group -> LDS
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) wpart[rg * D + sl * EPL + e] = part[e];
         __syncthreads();
 
         if (c == 0) {
             // ---------------------------------------------------------- block statistics
             // mu = mean key (fp32), a_i = <k_i, mu>, A = largest centred squared norm (or r_key^2)
             if (center) {
-                float part[EPL];
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) part[e] = 0.f;
-                constexpr int U = 8;
-                for (int i0 = rg; i0 < b; i0 += RG * U) {
-                    uintx4 raw[U];
-#pragma unroll
-                    for (int u = 0; u < U; ++u) raw[u] = row_slice(min(i0 + u * RG, b - 1));
-#pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        float f[EPL];
-                        Elem<T>::unpack(raw[u], f);
-                        if (i0 + u * RG < b)
-#pragma unroll
-                            for (int e = 0; e < EPL; ++e) part[e] += f[e];
-                    }
-                }
-#pragma unroll
-                for (int o = SL; o < 64; o <<= 1)
-#pragma unroll
-                    for (int e = 0; e < EPL; ++e) part[e] += __shfl_xor(part[e], o);
-                if (lane < SL)
-#pragma unroll
-                    for (int e = 0; e < EPL; ++e) wpart[wave * D + sl * EPL + e] = part[e];
-                __syncthreads();
                 if (tid < D) {
-                    float s = 0.f;
-#pragma unroll
-                    for (int w = 0; w < kWaves; ++w) s += wpart[w * D + tid];
-                    mu[tid] = s / (float)b;
-                }
-                __syncthreads();
-                if (wave == 0) {
-                    float s = 0.f;
-                    for (int cc = lane; cc < D; cc += 64) s += mu[cc] * mu[cc];
-                    s = wave_sum(s);
-                    if (lane == 0) scal[0] = s;
+                    float s0 = 0.f;
+                    for (int r = 0; r < RG; ++r) s0 += wpart[r * D + tid];
+                    mu[tid] = s0 / (float)b;
                 }
             } else {
                 if (tid < D) mu[tid] = 0.f;
-                if (tid == 0) scal[0] = 0.f;
             }
             __syncthreads();
-            const float mumu = scal[0];
+            float mumu = 0.f;                             // every wavefront forms |mu|^2 for itself
+            if (center) {
+                for (int cc = lane; cc < D; cc += 64) mumu = fmaf(mu[cc], mu[cc], mumu);
+                mumu = wave_sum(mumu);
+            }
             if (center || need_norm) {
                 float mloc[EPL];
 #pragma unroll
@@ -342,7 +364,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     for (int w = 1; w < kWaves; ++w) A = fmaxf(A, scal[2 + w]);
                 }
                 const float rc = alpha * (mumu - A + a.cterm);       // row constant of the exponent
-                for (int i = tid; i < b; i += kThreads) { aterm[i] += rc; sigma[i] = 0.f; }
+                for (int i = tid; i < b; i += kThreads) {
+                    aterm[i] += rc;
+                    sigma[i] = -threshold(i);                        // the walk tests (sum - threshold) < 0
+                }
                 if (tid == 0) scal[1] = rc;
             }
             __syncthreads();
@@ -387,7 +412,6 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             Ops::gram(acc, A, ldsA, n, h);
             Ops::weights(acc, aterm + (p0 << 6), alpha, h);
             const float e0 = fast_exp2(aterm[(p0 << 6) + n] - row_const), e1 = fast_exp2(aterm[(p0 << 6) + 32 + n] - row_const);
-            Ops::store_diag(diag, acc, e0, e1, n, h);
             if (EMIT_G) {
 #pragma unroll
                 for (int rb = 0; rb < 2; ++rb)
@@ -398,6 +422,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                         Gi[(size_t)((p0 << 6) + row) * b + (p0 << 6) + 32 + n] = acc[rb][1][r] * e1;
                     }
             }
+            Ops::mask_diag(acc, e0, e1, n, h);
+            Ops::store_diag(diag, acc, n, h);
         }
         __syncthreads();
 
@@ -407,31 +433,21 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         if (wave == 0) {
             for (int I = p0; I < p1; ++I) {
                 // ------------------------------------------------ the walk over panel I (Alg. 2 lines 4-10)
-                int ln = lane;
-                asm volatile("" : "+v"(ln));                  // keep the 63 lane masks local to this panel
-                const float* src = diag + ln;
+                // this lane's column of the diagonal tile: g[j] = g_{j,lane} for j < lane, else 0
                 float g[64];
 #pragma unroll
-                for (int j = 0; j < 63; ++j) {
-                    const float v = src[j * 64];              // row j of the tile, this lane's column
-                    g[j] = (ln > j) ? v : 0.f;                // strictly earlier tokens only
+                for (int t = 0; t < 16; ++t) {
+                    const floatx4 v = *reinterpret_cast<const floatx4*>(diag + lane * kDiagStride + 4 * t);
+                    g[4 * t] = v[0]; g[4 * t + 1] = v[1]; g[4 * t + 2] = v[2]; g[4 * t + 3] = v[3];
                 }
-                g[63] = 0.f;
+                // sigma holds (sum of signed weights so far) - (1 - 2 u): eta = +1 <=> u < 1/2 - s/2 <=> sigma < 0
                 float sv = sigma[(I << 6) + lane];
-                float u;
-                if (a.uniforms) u = a.uniforms[(size_t)inst * b + (I << 6) + lane];
-                else u = (float)draw_bits_keyed(key, ctr0 + (uint64_t)((I << 6) + lane)) * (1.0f / 16777216.0f);
-                const float tau = 1.f - 2.f * u;              // eta = +1  <=>  u < 1/2 - sigma/2  <=>  sigma < tau
                 __builtin_amdgcn_s_setprio(3);                // the serial chain goes first on its SIMD
-                walk_panel(sv, tau, g, std::make_integer_sequence<int, 64>{});
+                walk_panel(sv, g, std::make_integer_sequence<int, 64>{});
                 __builtin_amdgcn_s_setprio(0);
-                const unsigned long long m = __ballot(sv < tau);
+                const unsigned long long m = __ballot(sv < 0.f);
                 if (lane == 0) etaPack[I] = Ops::pack_signs(m);
-                any_fail |= (__ballot(fabsf(sv) > 1.f) != 0ull);
-                const float margin = 0.5f * fabsf(fminf(fmaxf(sv, -1.f), 1.f) - tau);   // |u - clamp(p)|
-                n_margin += __popcll(__ballot(margin < 1e-4f));
-                min_margin = fminf(min_margin, margin);
-                max_sigma = fmaxf(max_sigma, fabsf(sv));
+                sigma[(I << 6) + lane] = sv;                  // decision-time values, read back for the statistics
                 __syncthreads();                               // eta_I is visible
                 __syncthreads();                               // sigma[I+1] is complete
             }
@@ -479,19 +495,22 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     Ops::gram(dv, A, ldsA, n, h);
                     Ops::weights(dv, aterm + ((I + 1) << 6), alpha, h);
                 }
-                __syncthreads();                               // eta_I is visible; the walker is done with the diagonal tile
-                const float e0 = fast_exp2(aterm[((I + 1) << 6) + n] - row_const), e1 = fast_exp2(aterm[((I + 1) << 6) + 32 + n] - row_const);
-                Ops::store_diag(diag, dv, e0, e1, n, h);
-                if (EMIT_G) {
+                {
+                    const float e0 = fast_exp2(aterm[((I + 1) << 6) + n] - row_const), e1 = fast_exp2(aterm[((I + 1) << 6) + 32 + n] - row_const);
+                    if (EMIT_G) {
 #pragma unroll
-                    for (int rb = 0; rb < 2; ++rb)
+                        for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int row = 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-                            Gi[(size_t)(((I + 1) << 6) + row) * b + ((I + 1) << 6) + n] = dv[rb][0][r] * e0;
-                            Gi[(size_t)(((I + 1) << 6) + row) * b + ((I + 1) << 6) + 32 + n] = dv[rb][1][r] * e1;
-                        }
+                            for (int r = 0; r < 16; ++r) {
+                                const int row = 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+                                Gi[(size_t)(((I + 1) << 6) + row) * b + ((I + 1) << 6) + n] = dv[rb][0][r] * e0;
+                                Gi[(size_t)(((I + 1) << 6) + row) * b + ((I + 1) << 6) + 32 + n] = dv[rb][1][r] * e1;
+                            }
+                    }
+                    Ops::mask_diag(dv, e0, e1, n, h);
                 }
+                __syncthreads();                               // eta_I is visible; the walker is done with the diagonal tile
+                Ops::store_diag(diag, dv, n, h);
                 __syncthreads();                               // sigma[I+1] and the next diagonal tile are complete
             }
             __syncthreads();                                   // last panel of the chunk: nothing to prepare
@@ -537,15 +556,28 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     }
 
     // ------------------------------------------------------------------ output step (Alg. 2 lines 12-16 + strict n/2)
-    if (wave == 0) {
+    // Every wavefront handles the panels p = wave, wave + 8, ...: minority sign ('+' on ties), then exactly
+    // b/2 survivors = the minority class plus the lowest-index majority tokens, ascending.
+    {
         int n_plus = 0;
-        for (int p = 0; p < nP; ++p) n_plus += __popc(etaPack[p].x) + __popc(etaPack[p].y);
+        for (int p = 0; p < nP; ++p) {
+            const uint2 pk = etaPack[p];
+            n_plus += __popc(__builtin_amdgcn_readfirstlane(pk.x)) + __popc(__builtin_amdgcn_readfirstlane(pk.y));
+        }
         const bool plus_is_minority = n_plus <= b - n_plus;               // tie -> '+'
         const int n_min = plus_is_minority ? n_plus : b - n_plus;
         const int need = b / 2 - n_min;                                   // majority tokens to add, lowest index first
-        int maj_before = 0, kept_before = 0;
         const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-        for (int p = 0; p < nP; ++p) {
+        for (int p = wave; p < nP; p += kWaves) {
+            int maj_before = 0, kept_before = 0;
+            for (int q = 0; q < p; ++q) {                                 // scalar prefix over the earlier panels
+                const uint2 pk = etaPack[q];
+                const int plus_q = __popc(__builtin_amdgcn_readfirstlane(pk.x)) + __popc(__builtin_amdgcn_readfirstlane(pk.y));
+                const int min_q = plus_is_minority ? plus_q : 64 - plus_q;
+                const int maj_q = 64 - min_q;
+                kept_before += min_q + max(0, min(maj_q, need - maj_before));
+                maj_before += maj_q;
+            }
             const uint2 pk = etaPack[p];
             const unsigned long long m = Ops::unpack_signs(make_uint2(__builtin_amdgcn_readfirstlane(pk.x),
                                                                       __builtin_amdgcn_readfirstlane(pk.y)));
@@ -555,8 +587,6 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             const bool keep = ((minm >> lane) & 1ull) || (my_rank < need);
             const unsigned long long km = __ballot(keep);
             if (keep) keptIdx[kept_before + __popcll(km & lt)] = (p << 6) + lane;
-            maj_before += __popcll(majm);
-            kept_before += __popcll(km);
         }
     }
     __syncthreads();
@@ -564,6 +594,19 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         if (a.signs_out)
             for (int p = 0; p < nP; ++p)
                 a.signs_out[(size_t)inst * b + (p << 6) + lane] = ((Ops::unpack_signs(etaPack[p]) >> lane) & 1ull) ? 1 : -1;
+    } else if (wave == 2 && (a.status_out || a.stats_out)) {
+        // walk statistics from the decision-time values: FAIL events (Alg. 2 line 6), near-tie decisions
+        int n_margin = 0, any_fail = 0;
+        float min_margin = 3.0e38f, max_sigma = 0.f;
+        for (int p = 0; p < nP; ++p) {
+            const float tau = threshold((p << 6) + lane);
+            const float sg = sigma[(p << 6) + lane] + tau;                        // y^T eta / (c R^2) at decision time
+            any_fail |= (__ballot(fabsf(sg) > 1.f) != 0ull);
+            const float margin = 0.5f * fabsf(fminf(fmaxf(sg, -1.f), 1.f) - tau);  // |u - clamp(p)|
+            n_margin += __popcll(__ballot(margin < 1e-4f));
+            min_margin = fminf(min_margin, margin);
+            max_sigma = fmaxf(max_sigma, fabsf(sg));
+        }
         min_margin = wave_min(min_margin);
         max_sigma = wave_max(max_sigma);
         if (lane == 0) {
@@ -591,25 +634,31 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     };
     if (a.K_out) {
         char* Ko = a.K_out + out_tok0 * G::kRowBytes;
-        constexpr int U = 4;
-        for (int r0 = rg; r0 < half; r0 += RG * U) {
-            uintx4 raw[U];
+        if (single_chunk) {                              // the whole block is still resident in LDS
+            for (int r = rg; r < half; r += RG)
+                *reinterpret_cast<uintx4*>(Ko + (size_t)r * G::kRowBytes + sl * 16) =
+                    *reinterpret_cast<const uintx4*>(ldsK + (size_t)keptIdx[r] * G::kLdsRow + sl * 16);
+        } else {
+            constexpr int U = 8;
+            for (int r0 = rg; r0 < half; r0 += RG * U) {
+                uintx4 raw[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int r = r0 + u * RG;
-                if (r < half) raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)keptIdx[r] * G::kRowBytes + sl * 16);
-            }
+                for (int u = 0; u < U; ++u) {
+                    const int r = r0 + u * RG;
+                    if (r < half) raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)keptIdx[r] * G::kRowBytes + sl * 16);
+                }
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int r = r0 + u * RG;
-                if (r < half) *reinterpret_cast<uintx4*>(Ko + (size_t)r * G::kRowBytes + sl * 16) = raw[u];
+                for (int u = 0; u < U; ++u) {
+                    const int r = r0 + u * RG;
+                    if (r < half) *reinterpret_cast<uintx4*>(Ko + (size_t)r * G::kRowBytes + sl * 16) = raw[u];
+                }
             }
         }
     }
     if (a.V_out && a.V) {
         const char* Vseq = a.V + (size_t)seq * a.v_seq_stride * G::kRowBytes;
         char* Vo = a.V_out + out_tok0 * G::kRowBytes;
-        constexpr int U = 4;
+        constexpr int U = 8;
         for (int r0 = rg; r0 < half; r0 += RG * U) {
             uintx4 raw[U];
 #pragma unroll

@@ -375,33 +375,57 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         const float row_const = scal[1];
 
         // ---------------------------------------------------------- rows of earlier chunks
+        // Every earlier row panel I (all signs known) meets every column panel J of the resident chunk.
+        // A wavefront takes row panels I = wave, wave + 8, ...: it loads them once from global memory (L2) as
+        // the A operand and sweeps all J of the chunk; per-wavefront column sums go through LDS and are added
+        // to sigma in a fixed order, so the result does not depend on timing.
         if (c > 0) {
-            for (int J = p0 + wave; J < p1; J += kWaves) {
-                const char* ldsB = ldsK + (size_t)((J << 6) - row0) * G::kLdsRow;
-                float csum = 0.f;
-                for (int I = 0; I < p0; ++I) {
-                    Frag A[G::kGroups][2];
-                    Ops::load_frags(A, Kin + (size_t)(I << 6) * G::kRowBytes, G::kRowBytes, n, h);
-                    floatx16 acc[2][2];
-                    Ops::gram(acc, A, ldsB, n, h);
-                    Ops::weights(acc, aterm + (I << 6), alpha, h);
-                    if (EMIT_G) {
-                        const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
+            const int nJ = p1 - p0;                       // <= 8
+            float* partial = diag;                        // [kWaves][8][64], the diagonal-tile buffer is idle here
+            float cs[8];
 #pragma unroll
-                        for (int rb = 0; rb < 2; ++rb)
+            for (int jj = 0; jj < 8; ++jj) cs[jj] = 0.f;
+            for (int I = wave; I < p0; I += kWaves) {
+                Frag A[G::kGroups][2];
+                Ops::load_frags(A, Kin + (size_t)(I << 6) * G::kRowBytes, G::kRowBytes, n, h);
+                const uint2 em = etaPack[I];
 #pragma unroll
-                            for (int r = 0; r < 16; ++r) {
-                                const int row = (I << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-                                Gi[(size_t)row * b + (J << 6) + n] = acc[rb][0][r] * e0;
-                                Gi[(size_t)row * b + (J << 6) + 32 + n] = acc[rb][1][r] * e1;
-                                Gi[(size_t)((J << 6) + n) * b + row] = acc[rb][0][r] * e0;
-                                Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r] * e1;
-                            }
+                for (int jj = 0; jj < 8; ++jj) {
+                    if (jj < nJ) {
+                        const int J = p0 + jj;
+                        const char* ldsB = ldsK + (size_t)(jj << 6) * G::kLdsRow;
+                        floatx16 acc[2][2];
+                        Ops::gram(acc, A, ldsB, n, h);
+                        Ops::weights(acc, aterm + (I << 6), alpha, h);
+                        if (EMIT_G) {
+                            const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
+#pragma unroll
+                            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                                for (int r = 0; r < 16; ++r) {
+                                    const int row = (I << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+                                    Gi[(size_t)row * b + (J << 6) + n] = acc[rb][0][r] * e0;
+                                    Gi[(size_t)row * b + (J << 6) + 32 + n] = acc[rb][1][r] * e1;
+                                    Gi[(size_t)((J << 6) + n) * b + row] = acc[rb][0][r] * e0;
+                                    Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r] * e1;
+                                }
+                        }
+                        cs[jj] += Ops::signed_colsum(acc, em, h);
                     }
-                    csum += Ops::signed_colsum(acc, etaPack[I], h);
                 }
-                sigma[(J << 6) + lane] = fmaf(csum, fast_exp2(aterm[(J << 6) + lane] - row_const), sigma[(J << 6) + lane]);
             }
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj)
+                if (jj < nJ) partial[(wave * 8 + jj) * 64 + lane] = cs[jj];
+            __syncthreads();
+            if (wave < nJ) {
+                const int J = p0 + wave;
+                float tot = 0.f;
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) tot += partial[(w * 8 + wave) * 64 + lane];
+                sigma[(J << 6) + lane] = fmaf(tot, fast_exp2(aterm[(J << 6) + lane] - row_const), sigma[(J << 6) + lane]);
+            }
+            __syncthreads();                              // the buffer goes back to the diagonal tile
         }
         // diagonal tile of the chunk's first panel
         if (wave == 1) {

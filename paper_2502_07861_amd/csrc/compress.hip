@@ -48,7 +48,8 @@ constexpr int kLdsLimit = 160 * 1024;
 
 static inline size_t lds_fixed_bytes(int b) {
     return (size_t)b * 4 * 2             // sigma, aterm
-           + 16 * 8                      // eta of each panel, packed for the accumulator layout
+           + 16 * 8                      // eta of each panel as a 64-bit mask (bit j = 1 iff eta_j = +1)
+           + 2 * 64 * 4                  // eta of the two most recent panels as +-1 floats, same layout
            + kDiagFloats * 4             // diagonal tile (also: mean partials, survivor list)
            + 64;                         // scalars
 }
@@ -113,18 +114,129 @@ struct TileOps {
     // sum over the 64 rows of eta_row * weight, per column; returns this lane's column 32*h + n
     // (before the column factor).  The signs of a row panel come packed for this register layout:
     // word h holds, at bit 16*rb + r, the sign of row 32*rb + 8*(r/4) + 4*h + r%4 (1 = '+').
-    static __device__ __forceinline__ float signed_colsum(const floatx16 (&v)[2][2], uint2 packed, int h) {
-        const unsigned int nb = ~(h ? packed.y : packed.x);          // bit set = '-'
+    // Signs of a row panel for the accumulator layout: entry 16*rb + r of lane half h belongs to row
+    // 32*rb + 8*(r/4) + 4*h + r%4.  From the panel's mask (bit j = 1 iff eta_j = +1) ...
+    static __device__ __forceinline__ void signs_from_mask(float (&sg)[32], unsigned long long m, int h) {
+        const unsigned long long mh = ~m >> (4 * h);                  // bit set = '-'
+        const unsigned int w[2] = {(unsigned int)mh, (unsigned int)(mh >> 32)};
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            const int bit = 8 * ((k & 15) >> 2) + (k & 3);
+            sg[k] = __uint_as_float(((w[k >> 4] << (31 - bit)) & 0x80000000u) | 0x3f800000u);   // +1 or -1
+        }
+    }
+    // ... or as +-1 floats from LDS: this lane's 32 entries start at sgn_h = base + 32*h
+    static __device__ __forceinline__ void signs_from_lds(float (&sg)[32], const float* sgn_h) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const floatx4 t = *reinterpret_cast<const floatx4*>(sgn_h + 4 * q);
+            sg[4 * q] = t[0]; sg[4 * q + 1] = t[1]; sg[4 * q + 2] = t[2]; sg[4 * q + 3] = t[3];
+        }
+    }
+    static __device__ __forceinline__ float signed_colsum(const floatx16 (&v)[2][2], const float (&sg)[32], int h) {
         float cs0 = 0.f, cs1 = 0.f;
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int k = 16 * rb + r;
-                const float sg = __uint_as_float(((nb << (31 - k)) & 0x80000000u) | 0x3f800000u);   // +1 or -1
-                cs0 = fmaf(sg, v[rb][0][r], cs0);
-                cs1 = fmaf(sg, v[rb][1][r], cs1);
+            for (int r = 0; r < 16; ++r) cs0 = fmaf(sg[16 * rb + r], v[rb][0][r], cs0);
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) cs1 = fmaf(sg[16 * rb + r], v[rb][1][r], cs1);
+        cs0 += __shfl_xor(cs0, 32);
+        cs1 += __shfl_xor(cs1, 32);
+        return h ? cs1 : cs0;
+    }
+    // One 64x64 tile in two row halves: Gram of rows 0..31, then the Gram of rows 32..63 while the vector unit
+    // turns the first half into kernel weights (acc <- exp2(alpha * acc + rterm[row])) and, with SUM, adds them up
+    // per column with the row signs; then the same for the second half.  Per MFMA (32 cycles in the matrix pipe)
+    // the vector unit gets two elements: 2 FMA + 2 exp2 (+ 2 FMA); the order is written out and fenced, B fragments
+    // are requested one k-group ahead.  A fragments come from registers (AREG: the caller's A, reused over several
+    // tiles) or from LDS rows ldsA[0..63], one half at a time; signs come from registers (sg) or, if sg is null,
+    // from LDS (sgn_h: this lane half's 32 floats).  Returns this lane's column 32*h + n of the signed column sums
+    // (before the column factor).
+    template <bool SUM, bool AREG>
+    static __device__ __forceinline__ float tile(floatx16 (&acc)[2][2], const Frag (*A)[2], const char* ldsA, const char* ldsB,
+                                                 const float* aterm_panel, float alpha, const float* sg, const float* sgn_h,
+                                                 int n, int h) {
+        constexpr int KG = G::kGroups;
+        constexpr int RPI = 16 / KG;                       // accumulator registers (per column half) finished per k-group
+        static_assert(RPI >= 1, "at most 16 k-groups per row");
+        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        float cs0 = 0.f, cs1 = 0.f;
+        const char* bp0 = ldsB + (size_t)n * G::kLdsRow + 16 * h;
+        const char* bp1 = bp0 + (size_t)32 * G::kLdsRow;
+        Frag Ah[KG];
+        floatx4 at[4], sq[4];
+        auto load_a = [&](int rb) {
+#pragma unroll
+            for (int g = 0; g < KG; ++g)
+                Ah[g] = AREG ? A[g][rb] : *reinterpret_cast<const Frag*>(ldsA + (size_t)(32 * rb + n) * G::kLdsRow + 32 * g + 16 * h);
+        };
+        auto load_rowterms = [&](int rb) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                at[q] = *reinterpret_cast<const floatx4*>(aterm_panel + 32 * rb + 8 * q + 4 * h);
+                if (SUM) {
+                    if (sg) { sq[q][0] = sg[16 * rb + 4 * q]; sq[q][1] = sg[16 * rb + 4 * q + 1]; sq[q][2] = sg[16 * rb + 4 * q + 2]; sq[q][3] = sg[16 * rb + 4 * q + 3]; }
+                    else sq[q] = *reinterpret_cast<const floatx4*>(sgn_h + 16 * rb + 4 * q);
+                }
             }
+        };
+        auto finish = [&](int rb, int r) {
+            acc[rb][0][r] = fast_exp2(fmaf(acc[rb][0][r], alpha, at[r >> 2][r & 3]));
+            acc[rb][1][r] = fast_exp2(fmaf(acc[rb][1][r], alpha, at[r >> 2][r & 3]));
+            if (SUM) {
+                cs0 = fmaf(sq[r >> 2][r & 3], acc[rb][0][r], cs0);
+                cs1 = fmaf(sq[r >> 2][r & 3], acc[rb][1][r], cs1);
+            }
+        };
+        // rows 0..31
+        load_a(0);
+        acc[0][0] = zero; acc[0][1] = zero;
+        {
+            Frag b0 = *reinterpret_cast<const Frag*>(bp0), b1 = *reinterpret_cast<const Frag*>(bp1);
+#pragma unroll
+            for (int g = 0; g < KG; ++g) {
+                Frag nb0 = b0, nb1 = b1;
+                if (g + 1 < KG) {
+                    nb0 = *reinterpret_cast<const Frag*>(bp0 + 32 * (g + 1));
+                    nb1 = *reinterpret_cast<const Frag*>(bp1 + 32 * (g + 1));
+                }
+                Elem<T>::mma(acc[0][0], Ah[g], b0);
+                Elem<T>::mma(acc[0][1], Ah[g], b1);
+                b0 = nb0; b1 = nb1;
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // rows 32..63 on the matrix pipe, rows 0..31 on the vector unit
+        load_rowterms(0);
+        load_a(1);
+        acc[1][0] = zero; acc[1][1] = zero;
+        {
+            Frag b0 = *reinterpret_cast<const Frag*>(bp0), b1 = *reinterpret_cast<const Frag*>(bp1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int g = 0; g < KG; ++g) {
+                Frag nb0 = b0, nb1 = b1;
+                if (g + 1 < KG) {
+                    nb0 = *reinterpret_cast<const Frag*>(bp0 + 32 * (g + 1));
+                    nb1 = *reinterpret_cast<const Frag*>(bp1 + 32 * (g + 1));
+                }
+                Elem<T>::mma(acc[1][0], Ah[g], b0);
+#pragma unroll
+                for (int r = g * RPI; r < g * RPI + (RPI + 1) / 2; ++r) finish(0, r);
+                Elem<T>::mma(acc[1][1], Ah[g], b1);
+#pragma unroll
+                for (int r = g * RPI + (RPI + 1) / 2; r < (g + 1) * RPI; ++r) finish(0, r);
+                b0 = nb0; b1 = nb1;
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        load_rowterms(1);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) finish(1, r);
+        if (!SUM) return 0.f;
         cs0 += __shfl_xor(cs0, 32);
         cs1 += __shfl_xor(cs1, 32);
         return h ? cs1 : cs0;
@@ -153,26 +265,13 @@ struct TileOps {
                     *reinterpret_cast<floatx4*>(diag + (32 * cb + n) * kDiagStride + 32 * rb + 8 * q + 4 * h) = t;
                 }
     }
-    // eta mask of a panel (bit j = 1 iff eta_j = +1) -> the two packed words above
-    static __device__ __forceinline__ uint2 pack_signs(unsigned long long m) {
-        unsigned int lo = 0, hi = 0;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            lo |= (unsigned int)((m >> (8 * t)) & 0xFull) << (4 * t);
-            hi |= (unsigned int)((m >> (8 * t + 4)) & 0xFull) << (4 * t);
-        }
-        return make_uint2(lo, hi);
-    }
-    static __device__ __forceinline__ unsigned long long unpack_signs(uint2 pk) {
-        unsigned long long m = 0;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            m |= (unsigned long long)((pk.x >> (4 * t)) & 0xFu) << (8 * t);
-            m |= (unsigned long long)((pk.y >> (4 * t)) & 0xFu) << (8 * t + 4);
-        }
-        return m;
-    }
 };
+
+// The tile must be complete at this point of the program: the compiler may otherwise sink register-only
+// work (MFMAs, exponentials) past a barrier into the stretch every wavefront waits on.
+__device__ __forceinline__ void settle(floatx16 (&v)[2][2]) {
+    asm volatile("" : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[1][0]), "+v"(v[1][1]));
+}
 
 // One decision of the walk (Alg. 2 lines 5-9 for token j of the panel): every lane tests the sign of its
 // sigma (which carries the threshold, see the kernel), lane j's outcome is picked out of the compare mask on the scalar unit and comes
@@ -205,11 +304,11 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     char* ldsK = smem;
     float* sigma = reinterpret_cast<float*>(smem + (size_t)CH * G::kLdsRow);
     float* aterm = sigma + b;                                      // -alpha * a_i; column factor = exp2(aterm)
-    uint2* etaPack = reinterpret_cast<uint2*>(aterm + b);          // signs of each panel, packed for the accumulator layout
-    float* diag = reinterpret_cast<float*>(etaPack + 16);          // [64 columns][kDiagStride], transposed
+    unsigned long long* etaMask = reinterpret_cast<unsigned long long*>(aterm + b);   // bit j of entry I: eta of token 64 I + j is +1
+    float* etaF = reinterpret_cast<float*>(etaMask + 16);          // [2][2][32]: +-1 of panel I at slot I&1, entry h*32 + 16*rb + r
+    float* diag = etaF + 128;                                      // [64 columns][kDiagStride], transposed
     float* scal = diag + kDiagFloats;                              // [0] |mu|^2, [1] A, [2..2+kWaves) partial maxima
-    float* wpart = diag;                                           // [RG][D] <= 4096 floats (statistics phase only)
-    float* mu = diag + 4096;                                       // [D]                    (statistics phase only)
+    float* wpart = diag;                                           // [kWaves][D] column sums (statistics phase only)
     int* keptIdx = reinterpret_cast<int*>(diag);                   // [b/2]        (output phase only)
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -248,6 +347,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         return *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
     };
 
+    // sigma starts at minus the threshold: the walk tests (sum of signed weights - threshold) < 0.  Integer work,
+    // done first so that it overlaps the latency of the loads below.
+    for (int i = tid; i < b; i += kThreads) sigma[i] = -threshold(i);
+
     // column sums for the block mean, accumulated while rows pass through the registers
     float part[EPL];
 #pragma unroll
@@ -271,105 +374,121 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     }
 
     const int n_chunks = (b + CH - 1) / CH;
-    for (int c = 0; c < n_chunks; ++c) {
-        const int row0 = c * CH;                       // first row of the chunk
-        const int rows_here = min(CH, b - row0);
-        const int p0 = row0 >> 6, p1 = (row0 + rows_here) >> 6;
-        __syncthreads();                               // previous users of ldsK are done
-        {
-            constexpr int U = 8;
-            const bool acc_mean = center && single_chunk;
-            for (int i0 = rg; i0 < rows_here; i0 += RG * U) {
-                uintx4 raw[U];
+    // rows [row0, row0 + rows_here) of the block -> LDS (several rows in flight per thread)
+    auto stage_chunk = [&](int row0, int rows_here, bool acc_mean) {
+        constexpr int U = 8;
+        for (int i0 = rg; i0 < rows_here; i0 += RG * U) {
+            uintx4 raw[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int i = i0 + u * RG;
-                    if (i < rows_here) raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)(row0 + i) * G::kRowBytes + sl * 16);
-                }
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * RG;
+                if (i < rows_here) raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)(row0 + i) * G::kRowBytes + sl * 16);
+            }
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int i = i0 + u * RG;
-                    if (i < rows_here) {
-                        *reinterpret_cast<uintx4*>(ldsK + (size_t)i * G::kLdsRow + sl * 16) = raw[u];
-                        if (acc_mean) {
-                            float f[EPL];
-                            Elem<T>::unpack(raw[u], f);
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * RG;
+                if (i < rows_here) {
+                    *reinterpret_cast<uintx4*>(ldsK + (size_t)i * G::kLdsRow + sl * 16) = raw[u];
+                    if (acc_mean) {
+                        float f[EPL];
+                        Elem<T>::unpack(raw[u], f);
 #pragma unroll
-                            for (int e = 0; e < EPL; ++e) part[e] += f[e];
-                        }
+                        for (int e = 0; e < EPL; ++e) part[e] += f[e];
                     }
                 }
             }
         }
-        if (c == 0 && center)                          // partial column sums of every row group -> LDS
+    };
+    stage_chunk(0, min(CH, b), center && single_chunk);
+    if (center) {                        // column sums of every wavefront -> LDS
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) wpart[rg * D + sl * EPL + e] = part[e];
-        __syncthreads();
-
-        if (c == 0) {
-            // ---------------------------------------------------------- block statistics
-            // mu = mean key (fp32), a_i = <k_i, mu>, A = largest centred squared norm (or r_key^2)
-            if (center) {
-                if (tid < D) {
-                    float s0 = 0.f;
-                    for (int r = 0; r < RG; ++r) s0 += wpart[r * D + tid];
-                    mu[tid] = s0 / (float)b;
-                }
-            } else {
-                if (tid < D) mu[tid] = 0.f;
+        for (int o = SL; o < 64; o <<= 1)
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) part[e] += __shfl_xor(part[e], o);
+        if (lane < SL)
+#pragma unroll
+            for (int q = 0; q < EPL / 4; ++q) {
+                const floatx4 t = {part[4 * q], part[4 * q + 1], part[4 * q + 2], part[4 * q + 3]};
+                *reinterpret_cast<floatx4*>(wpart + wave * D + sl * EPL + 4 * q) = t;
             }
-            __syncthreads();
-            float mumu = 0.f;                             // every wavefront forms |mu|^2 for itself
-            if (center) {
-                for (int cc = lane; cc < D; cc += 64) mumu = fmaf(mu[cc], mu[cc], mumu);
-                mumu = wave_sum(mumu);
+    }
+    __syncthreads();
+    {
+        // ---------------------------------------------------------- block statistics
+        // mu = mean key (fp32), a_i = <k_i, mu>, A = largest centred squared norm (or r_key^2)
+        // every thread forms its own 16-byte slice of mu and |mu|^2 (the same value in all threads)
+        float mloc[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) mloc[e] = 0.f;
+        float mumu = 0.f;
+        if (center) {
+            floatx4 wp[kWaves][EPL / 4];
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+                for (int q = 0; q < EPL / 4; ++q)
+                    wp[w][q] = *reinterpret_cast<const floatx4*>(wpart + w * D + sl * EPL + 4 * q);
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) mloc[e] += wp[w][e >> 2][e & 3];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                mloc[e] *= 1.f / (float)b;
+                mumu = fmaf(mloc[e], mloc[e], mumu);
             }
-            if (center || need_norm) {
-                float mloc[EPL];
+            mumu = group_sum<SL>(mumu);
+        }
+        if (center || need_norm) {
+            float amax = -3.0e38f;
+            constexpr int U = 4;
+            for (int i0 = rg; i0 < b; i0 += RG * U) {          // b is a multiple of 64 >= RG; rows past b are skipped
+                uintx4 raw[U];
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) mloc[e] = mu[sl * EPL + e];
-                float amax = -3.0e38f;
-                constexpr int U = 4;
-                for (int i0 = rg; i0 < b; i0 += RG * U) {          // b is a multiple of 64 >= RG; rows past b are skipped
-                    uintx4 raw[U];
+                for (int u = 0; u < U; ++u) raw[u] = row_slice(min(i0 + u * RG, b - 1));
 #pragma unroll
-                    for (int u = 0; u < U; ++u) raw[u] = row_slice(min(i0 + u * RG, b - 1));
+                for (int u = 0; u < U; ++u) {
+                    const int i = i0 + u * RG;
+                    float f[EPL];
+                    Elem<T>::unpack(raw[u], f);
+                    float pa = 0.f, pn = 0.f;
 #pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        const int i = i0 + u * RG;
-                        float f[EPL];
-                        Elem<T>::unpack(raw[u], f);
-                        float pa = 0.f, pn = 0.f;
-#pragma unroll
-                        for (int e = 0; e < EPL; ++e) { pa = fmaf(f[e], mloc[e], pa); pn = fmaf(f[e], f[e], pn); }
-                        pa = group_sum<SL>(pa);
-                        pn = group_sum<SL>(pn);
-                        if (i < b) {
-                            if (sl == 0) aterm[i] = -alpha * pa;
-                            amax = fmaxf(amax, pn - 2.f * pa + mumu);
-                        }
+                    for (int e = 0; e < EPL; ++e) { pa = fmaf(f[e], mloc[e], pa); pn = fmaf(f[e], f[e], pn); }
+                    pa = group_sum<SL>(pa);
+                    pn = group_sum<SL>(pn);
+                    if (i < b) {
+                        if (sl == 0) aterm[i] = -alpha * pa;
+                        amax = fmaxf(amax, pn - 2.f * pa + mumu);
                     }
                 }
-                amax = wave_max(amax);
-                if (lane == 0) scal[2 + wave] = amax;
-            } else {
-                for (int i = tid; i < b; i += kThreads) aterm[i] = 0.f;
             }
-            __syncthreads();                                        // mu / wpart (aliasing diag) are dead from here
-            {
-                float A = a.rkey2;
-                if (need_norm) {
-                    A = scal[2];
+            amax = wave_max(amax);
+            if (lane == 0) scal[2 + wave] = amax;
+        } else {
+            for (int i = tid; i < b; i += kThreads) aterm[i] = 0.f;
+        }
+        __syncthreads();                                        // mu / wpart (aliasing diag) are dead from here
+        {
+            float A = a.rkey2;
+            if (need_norm) {
+                A = scal[2];
 #pragma unroll
-                    for (int w = 1; w < kWaves; ++w) A = fmaxf(A, scal[2 + w]);
-                }
-                const float rc = alpha * (mumu - A + a.cterm);       // row constant of the exponent
-                for (int i = tid; i < b; i += kThreads) {
-                    aterm[i] += rc;
-                    sigma[i] = -threshold(i);                        // the walk tests (sum - threshold) < 0
-                }
-                if (tid == 0) scal[1] = rc;
+                for (int w = 1; w < kWaves; ++w) A = fmaxf(A, scal[2 + w]);
             }
+            const float rc = alpha * (mumu - A + a.cterm);       // row constant of the exponent
+            for (int i = tid; i < b; i += kThreads) aterm[i] += rc;
+            if (tid == 0) scal[1] = rc;
+        }
+        __syncthreads();
+    }
+
+    for (int c = 0; c < n_chunks; ++c) {
+        const int row0 = c * CH;                       // first row of the chunk
+        const int rows_here = min(CH, b - row0);
+        const int p0 = row0 >> 6, p1 = (row0 + rows_here) >> 6;
+        if (c > 0) {
+            __syncthreads();                           // previous users of ldsK are done
+            stage_chunk(row0, rows_here, false);
             __syncthreads();
         }
         const float row_const = scal[1];
@@ -382,41 +501,38 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         if (c > 0) {
             const int nJ = p1 - p0;                       // <= 8
             float* partial = diag;                        // [kWaves][8][64], the diagonal-tile buffer is idle here
-            float cs[8];
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj) cs[jj] = 0.f;
+            bool first = true;
             for (int I = wave; I < p0; I += kWaves) {
                 Frag A[G::kGroups][2];
                 Ops::load_frags(A, Kin + (size_t)(I << 6) * G::kRowBytes, G::kRowBytes, n, h);
-                const uint2 em = etaPack[I];
+                float sg[32];
+                Ops::signs_from_mask(sg, etaMask[I], h);
+#pragma unroll 1
+                for (int jj = 0; jj < nJ; ++jj) {
+                    const int J = p0 + jj;
+                    const char* ldsB = ldsK + (size_t)(jj << 6) * G::kLdsRow;
+                    floatx16 acc[2][2];
+                    const float cs = Ops::template tile<true, true>(acc, A, nullptr, ldsB, aterm + (I << 6), alpha, sg, nullptr, n, h);
+                    if (EMIT_G) {
+                        const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
 #pragma unroll
-                for (int jj = 0; jj < 8; ++jj) {
-                    if (jj < nJ) {
-                        const int J = p0 + jj;
-                        const char* ldsB = ldsK + (size_t)(jj << 6) * G::kLdsRow;
-                        floatx16 acc[2][2];
-                        Ops::gram(acc, A, ldsB, n, h);
-                        Ops::weights(acc, aterm + (I << 6), alpha, h);
-                        if (EMIT_G) {
-                            const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
+                        for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-                            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                                for (int r = 0; r < 16; ++r) {
-                                    const int row = (I << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-                                    Gi[(size_t)row * b + (J << 6) + n] = acc[rb][0][r] * e0;
-                                    Gi[(size_t)row * b + (J << 6) + 32 + n] = acc[rb][1][r] * e1;
-                                    Gi[(size_t)((J << 6) + n) * b + row] = acc[rb][0][r] * e0;
-                                    Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r] * e1;
-                                }
-                        }
-                        cs[jj] += Ops::signed_colsum(acc, em, h);
+                            for (int r = 0; r < 16; ++r) {
+                                const int row = (I << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+                                Gi[(size_t)row * b + (J << 6) + n] = acc[rb][0][r] * e0;
+                                Gi[(size_t)row * b + (J << 6) + 32 + n] = acc[rb][1][r] * e1;
+                                Gi[(size_t)((J << 6) + n) * b + row] = acc[rb][0][r] * e0;
+                                Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r] * e1;
+                            }
                     }
+                    float* slot = partial + (wave * 8 + jj) * 64 + lane;      // this wavefront's own slot
+                    *slot = first ? cs : *slot + cs;
                 }
+                first = false;
             }
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj)
-                if (jj < nJ) partial[(wave * 8 + jj) * 64 + lane] = cs[jj];
+            if (first)                                    // no row panel for this wavefront
+                for (int jj = 0; jj < nJ; ++jj) partial[(wave * 8 + jj) * 64 + lane] = 0.f;
             __syncthreads();
             if (wave < nJ) {
                 const int J = p0 + wave;
@@ -430,11 +546,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         // diagonal tile of the chunk's first panel
         if (wave == 1) {
             const char* ldsA = ldsK + (size_t)((p0 << 6) - row0) * G::kLdsRow;
-            Frag A[G::kGroups][2];
-            Ops::load_frags(A, ldsA, G::kLdsRow, n, h);
             floatx16 acc[2][2];
-            Ops::gram(acc, A, ldsA, n, h);
-            Ops::weights(acc, aterm + (p0 << 6), alpha, h);
+            Ops::template tile<false, false>(acc, nullptr, ldsA, ldsA, aterm + (p0 << 6), alpha, nullptr, nullptr, n, h);
             const float e0 = fast_exp2(aterm[(p0 << 6) + n] - row_const), e1 = fast_exp2(aterm[(p0 << 6) + 32 + n] - row_const);
             if (EMIT_G) {
 #pragma unroll
@@ -470,7 +583,12 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 walk_panel(sv, g, std::make_integer_sequence<int, 64>{});
                 __builtin_amdgcn_s_setprio(0);
                 const unsigned long long m = __ballot(sv < 0.f);
-                if (lane == 0) etaPack[I] = Ops::pack_signs(m);
+                if (lane == 0) etaMask[I] = m;
+                {
+                    const int k = lane & 31;
+                    const int row = 32 * (k >> 4) + 8 * ((k & 15) >> 2) + 4 * h + (k & 3);
+                    etaF[((I & 1) << 6) + lane] = ((m >> row) & 1ull) ? 1.f : -1.f;
+                }
                 sigma[(I << 6) + lane] = sv;                  // decision-time values, read back for the statistics
                 __syncthreads();                               // eta_I is visible
                 __syncthreads();                               // sigma[I+1] is complete
@@ -483,11 +601,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 {
                     const char* ldsA = ldsK + (size_t)((I << 6) - row0) * G::kLdsRow;
                     const char* ldsB = ldsK + (size_t)((J << 6) - row0) * G::kLdsRow;
-                    Frag A[G::kGroups][2];
-                    Ops::load_frags(A, ldsA, G::kLdsRow, n, h);
-                    Ops::gram(held, A, ldsB, n, h);
-                    Ops::weights(held, aterm + (I << 6), alpha, h);
+                    Ops::template tile<false, false>(held, nullptr, ldsA, ldsB, aterm + (I << 6), alpha, nullptr, nullptr, n, h);
                 }
+                settle(held);
                 __syncthreads();                               // eta_I is visible
                 if (EMIT_G) {
                     const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
@@ -502,7 +618,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                             Gi[(size_t)((J << 6) + 32 + n) * b + row] = held[rb][1][r] * e1;
                         }
                 }
-                const float cs = Ops::signed_colsum(held, etaPack[I], h);
+                float sg[32];
+                Ops::signs_from_lds(sg, etaF + ((I & 1) << 6) + 32 * h);
+                const float cs = Ops::signed_colsum(held, sg, h);
                 sigma[(J << 6) + lane] = fmaf(cs, fast_exp2(aterm[(J << 6) + lane] - row_const), sigma[(J << 6) + lane]);
                 __syncthreads();                               // sigma[I+1] is complete
             }
@@ -514,10 +632,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 floatx16 dv[2][2];
                 {
                     const char* ldsA = ldsK + (size_t)(((I + 1) << 6) - row0) * G::kLdsRow;
-                    Frag A[G::kGroups][2];
-                    Ops::load_frags(A, ldsA, G::kLdsRow, n, h);
-                    Ops::gram(dv, A, ldsA, n, h);
-                    Ops::weights(dv, aterm + ((I + 1) << 6), alpha, h);
+                    Ops::template tile<false, false>(dv, nullptr, ldsA, ldsA, aterm + ((I + 1) << 6), alpha, nullptr, nullptr, n, h);
                 }
                 {
                     const float e0 = fast_exp2(aterm[((I + 1) << 6) + n] - row_const), e1 = fast_exp2(aterm[((I + 1) << 6) + 32 + n] - row_const);
@@ -533,6 +648,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     }
                     Ops::mask_diag(dv, e0, e1, n, h);
                 }
+                settle(dv);
                 __syncthreads();                               // eta_I is visible; the walker is done with the diagonal tile
                 Ops::store_diag(diag, dv, n, h);
                 __syncthreads();                               // sigma[I+1] and the next diagonal tile are complete
@@ -547,15 +663,12 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 const int c_first = wave - 3, c_step = kWaves - 3;
                 if (c_first < nC) {
                     const char* ldsA = ldsK + (size_t)(((I - 1) << 6) - row0) * G::kLdsRow;
-                    const uint2 em = etaPack[I - 1];
-                    Frag A[G::kGroups][2];
-                    Ops::load_frags(A, ldsA, G::kLdsRow, n, h);
+                    const float* sgn_h = etaF + (((I - 1) & 1) << 6) + 32 * h;
                     for (int cj = c_first; cj < nC; cj += c_step) {
                         const int J = I + 1 + cj;
                         const char* ldsB = ldsK + (size_t)((J << 6) - row0) * G::kLdsRow;
                         floatx16 acc[2][2];
-                        Ops::gram(acc, A, ldsB, n, h);
-                        Ops::weights(acc, aterm + ((I - 1) << 6), alpha, h);
+                        const float cs = Ops::template tile<true, false>(acc, nullptr, ldsA, ldsB, aterm + ((I - 1) << 6), alpha, nullptr, sgn_h, n, h);
                         if (EMIT_G) {
                             const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
 #pragma unroll
@@ -569,7 +682,6 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                                     Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r] * e1;
                                 }
                         }
-                        const float cs = Ops::signed_colsum(acc, em, h);
                         sigma[(J << 6) + lane] = fmaf(cs, fast_exp2(aterm[(J << 6) + lane] - row_const), sigma[(J << 6) + lane]);
                     }
                 }
@@ -583,28 +695,32 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     // Every wavefront handles the panels p = wave, wave + 8, ...: minority sign ('+' on ties), then exactly
     // b/2 survivors = the minority class plus the lowest-index majority tokens, ascending.
     {
-        int n_plus = 0;
-        for (int p = 0; p < nP; ++p) {
-            const uint2 pk = etaPack[p];
-            n_plus += __popc(__builtin_amdgcn_readfirstlane(pk.x)) + __popc(__builtin_amdgcn_readfirstlane(pk.y));
-        }
+        // lane q < nP (nP <= 16) carries the counts of panel q; prefix sums run over the first row of 16 lanes
+        auto row_scan = [](int x) -> int {                                // inclusive prefix sum inside a row of 16 lanes
+            x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, true);   // row_shr:1, zero fill
+            x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, true);   // row_shr:2
+            x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, true);   // row_shr:4
+            x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, true);   // row_shr:8
+            return x;
+        };
+        int plus_q = 0;
+        if (lane < nP) plus_q = __popcll(etaMask[lane]);
+        const int n_plus = __builtin_amdgcn_readlane(row_scan(plus_q), 15);
         const bool plus_is_minority = n_plus <= b - n_plus;               // tie -> '+'
         const int n_min = plus_is_minority ? n_plus : b - n_plus;
         const int need = b / 2 - n_min;                                   // majority tokens to add, lowest index first
+        const int min_q = (lane < nP) ? (plus_is_minority ? plus_q : 64 - plus_q) : 0;
+        const int maj_q = (lane < nP) ? 64 - min_q : 0;
+        const int maj_before_q = row_scan(maj_q) - maj_q;
+        const int kept_q = min_q + max(0, min(maj_q, need - maj_before_q));
+        const int kept_before_q = row_scan(kept_q) - kept_q;
         const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
         for (int p = wave; p < nP; p += kWaves) {
-            int maj_before = 0, kept_before = 0;
-            for (int q = 0; q < p; ++q) {                                 // scalar prefix over the earlier panels
-                const uint2 pk = etaPack[q];
-                const int plus_q = __popc(__builtin_amdgcn_readfirstlane(pk.x)) + __popc(__builtin_amdgcn_readfirstlane(pk.y));
-                const int min_q = plus_is_minority ? plus_q : 64 - plus_q;
-                const int maj_q = 64 - min_q;
-                kept_before += min_q + max(0, min(maj_q, need - maj_before));
-                maj_before += maj_q;
-            }
-            const uint2 pk = etaPack[p];
-            const unsigned long long m = Ops::unpack_signs(make_uint2(__builtin_amdgcn_readfirstlane(pk.x),
-                                                                      __builtin_amdgcn_readfirstlane(pk.y)));
+            const int maj_before = __builtin_amdgcn_readlane(maj_before_q, p);
+            const int kept_before = __builtin_amdgcn_readlane(kept_before_q, p);
+            const unsigned long long mv = etaMask[p];
+            const unsigned long long m = ((unsigned long long)__builtin_amdgcn_readfirstlane((unsigned int)(mv >> 32)) << 32) |
+                                         (unsigned int)__builtin_amdgcn_readfirstlane((unsigned int)mv);
             const unsigned long long minm = plus_is_minority ? m : ~m;
             const unsigned long long majm = ~minm;
             const int my_rank = maj_before + __popcll(majm & lt);
@@ -617,7 +733,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     if (wave == 0) {      // side outputs: issued after the barrier so that nobody waits for these stores
         if (a.signs_out)
             for (int p = 0; p < nP; ++p)
-                a.signs_out[(size_t)inst * b + (p << 6) + lane] = ((Ops::unpack_signs(etaPack[p]) >> lane) & 1ull) ? 1 : -1;
+                a.signs_out[(size_t)inst * b + (p << 6) + lane] = ((etaMask[p] >> lane) & 1ull) ? 1 : -1;
     } else if (wave == 2 && (a.status_out || a.stats_out)) {
         // walk statistics from the decision-time values: FAIL events (Alg. 2 line 6), near-tie decisions
         int n_margin = 0, any_fail = 0;
@@ -656,44 +772,50 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         const int kept = keptIdx[r];
         return a.idx_in ? (int64_t)a.idx_in[in_tok0 + kept] : (int64_t)blk * b + kept;
     };
-    if (a.K_out) {
-        char* Ko = a.K_out + out_tok0 * G::kRowBytes;
-        if (single_chunk) {                              // the whole block is still resident in LDS
-            for (int r = rg; r < half; r += RG)
-                *reinterpret_cast<uintx4*>(Ko + (size_t)r * G::kRowBytes + sl * 16) =
-                    *reinterpret_cast<const uintx4*>(ldsK + (size_t)keptIdx[r] * G::kLdsRow + sl * 16);
-        } else {
-            constexpr int U = 8;
-            for (int r0 = rg; r0 < half; r0 += RG * U) {
-                uintx4 raw[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int r = r0 + u * RG;
-                    if (r < half) raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)keptIdx[r] * G::kRowBytes + sl * 16);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int r = r0 + u * RG;
-                    if (r < half) *reinterpret_cast<uintx4*>(Ko + (size_t)r * G::kRowBytes + sl * 16) = raw[u];
-                }
-            }
-        }
-    }
-    if (a.V_out && a.V) {
-        const char* Vseq = a.V + (size_t)seq * a.v_seq_stride * G::kRowBytes;
-        char* Vo = a.V_out + out_tok0 * G::kRowBytes;
+    {
+        // Keys come from LDS when the whole block is still resident, else from global memory (L2); value rows
+        // always come from global memory.  All loads of a pass are issued before its first store.
+        char* Ko = a.K_out ? a.K_out + out_tok0 * G::kRowBytes : nullptr;
+        const bool do_v = a.V_out && a.V;
+        const char* Vseq = do_v ? a.V + (size_t)seq * a.v_seq_stride * G::kRowBytes : nullptr;
+        char* Vo = do_v ? a.V_out + out_tok0 * G::kRowBytes : nullptr;
+        const bool k_global = Ko && !single_chunk;
         constexpr int U = 8;
         for (int r0 = rg; r0 < half; r0 += RG * U) {
-            uintx4 raw[U];
+            uintx4 kraw[U], vraw[U];
+            if (do_v) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int r = r0 + u * RG;
-                if (r < half) raw[u] = *reinterpret_cast<const uintx4*>(Vseq + (size_t)src_token(r) * G::kRowBytes + sl * 16);
+                for (int u = 0; u < U; ++u) {
+                    const int r = r0 + u * RG;
+                    if (r < half) vraw[u] = *reinterpret_cast<const uintx4*>(Vseq + (size_t)src_token(r) * G::kRowBytes + sl * 16);
+                }
             }
+            if (k_global) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int r = r0 + u * RG;
-                if (r < half) *reinterpret_cast<uintx4*>(Vo + (size_t)r * G::kRowBytes + sl * 16) = raw[u];
+                for (int u = 0; u < U; ++u) {
+                    const int r = r0 + u * RG;
+                    if (r < half) kraw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)keptIdx[r] * G::kRowBytes + sl * 16);
+                }
+            } else if (Ko) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int r = r0 + u * RG;
+                    if (r < half) kraw[u] = *reinterpret_cast<const uintx4*>(ldsK + (size_t)keptIdx[r] * G::kLdsRow + sl * 16);
+                }
+            }
+            if (Ko) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int r = r0 + u * RG;
+                    if (r < half) *reinterpret_cast<uintx4*>(Ko + (size_t)r * G::kRowBytes + sl * 16) = kraw[u];
+                }
+            }
+            if (do_v) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int r = r0 + u * RG;
+                    if (r < half) *reinterpret_cast<uintx4*>(Vo + (size_t)r * G::kRowBytes + sl * 16) = vraw[u];
+                }
             }
         }
     }

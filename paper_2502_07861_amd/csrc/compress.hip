@@ -161,79 +161,73 @@ struct TileOps {
                                                  int n, int h) {
         constexpr int KG = G::kGroups;
         constexpr int RPI = 16 / KG;                       // accumulator registers (per column half) finished per k-group
-        static_assert(RPI >= 1, "at most 16 k-groups per row");
+        constexpr int kAhead = 2;                          // k-groups between the request of a B fragment and its use
+        static_assert(RPI >= 1 && KG >= 4, "4 to 16 k-groups per row");
         const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         float cs0 = 0.f, cs1 = 0.f;
         const char* bp0 = ldsB + (size_t)n * G::kLdsRow + 16 * h;
         const char* bp1 = bp0 + (size_t)32 * G::kLdsRow;
-        Frag Ah[KG];
-        floatx4 at[4], sq[4];
-        auto load_a = [&](int rb) {
-#pragma unroll
-            for (int g = 0; g < KG; ++g)
-                Ah[g] = AREG ? A[g][rb] : *reinterpret_cast<const Frag*>(ldsA + (size_t)(32 * rb + n) * G::kLdsRow + 32 * g + 16 * h);
+        const char* ap = AREG ? nullptr : ldsA + (size_t)n * G::kLdsRow + 16 * h;
+        Frag Ah[2][KG], B0[KG], B1[KG];
+        floatx4 at[2][4], sq[2][4];
+        auto load_a = [&](int rb, int g) {
+            Ah[rb][g] = AREG ? A[g][rb] : *reinterpret_cast<const Frag*>(ap + (size_t)(32 * rb) * G::kLdsRow + 32 * g);
         };
-        auto load_rowterms = [&](int rb) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                at[q] = *reinterpret_cast<const floatx4*>(aterm_panel + 32 * rb + 8 * q + 4 * h);
-                if (SUM) {
-                    if (sg) { sq[q][0] = sg[16 * rb + 4 * q]; sq[q][1] = sg[16 * rb + 4 * q + 1]; sq[q][2] = sg[16 * rb + 4 * q + 2]; sq[q][3] = sg[16 * rb + 4 * q + 3]; }
-                    else sq[q] = *reinterpret_cast<const floatx4*>(sgn_h + 16 * rb + 4 * q);
-                }
+        auto load_b = [&](int g) {
+            B0[g] = *reinterpret_cast<const Frag*>(bp0 + 32 * g);
+            B1[g] = *reinterpret_cast<const Frag*>(bp1 + 32 * g);
+        };
+        auto load_rowterm = [&](int rb, int q) {
+            at[rb][q] = *reinterpret_cast<const floatx4*>(aterm_panel + 32 * rb + 8 * q + 4 * h);
+            if (SUM) {
+                if (sg) { sq[rb][q][0] = sg[16 * rb + 4 * q]; sq[rb][q][1] = sg[16 * rb + 4 * q + 1]; sq[rb][q][2] = sg[16 * rb + 4 * q + 2]; sq[rb][q][3] = sg[16 * rb + 4 * q + 3]; }
+                else sq[rb][q] = *reinterpret_cast<const floatx4*>(sgn_h + 16 * rb + 4 * q);
             }
         };
         auto finish = [&](int rb, int r) {
-            acc[rb][0][r] = fast_exp2(fmaf(acc[rb][0][r], alpha, at[r >> 2][r & 3]));
-            acc[rb][1][r] = fast_exp2(fmaf(acc[rb][1][r], alpha, at[r >> 2][r & 3]));
+            acc[rb][0][r] = fast_exp2(fmaf(acc[rb][0][r], alpha, at[rb][r >> 2][r & 3]));
+            acc[rb][1][r] = fast_exp2(fmaf(acc[rb][1][r], alpha, at[rb][r >> 2][r & 3]));
             if (SUM) {
-                cs0 = fmaf(sq[r >> 2][r & 3], acc[rb][0][r], cs0);
-                cs1 = fmaf(sq[r >> 2][r & 3], acc[rb][1][r], cs1);
+                cs0 = fmaf(sq[rb][r >> 2][r & 3], acc[rb][0][r], cs0);
+                cs1 = fmaf(sq[rb][r >> 2][r & 3], acc[rb][1][r], cs1);
             }
         };
-        // rows 0..31
-        load_a(0);
-        acc[0][0] = zero; acc[0][1] = zero;
-        {
-            Frag b0 = *reinterpret_cast<const Frag*>(bp0), b1 = *reinterpret_cast<const Frag*>(bp1);
+        // rows 0..31 on the matrix pipe; requests for what the next stage needs ride along
 #pragma unroll
-            for (int g = 0; g < KG; ++g) {
-                Frag nb0 = b0, nb1 = b1;
-                if (g + 1 < KG) {
-                    nb0 = *reinterpret_cast<const Frag*>(bp0 + 32 * (g + 1));
-                    nb1 = *reinterpret_cast<const Frag*>(bp1 + 32 * (g + 1));
-                }
-                Elem<T>::mma(acc[0][0], Ah[g], b0);
-                Elem<T>::mma(acc[0][1], Ah[g], b1);
-                b0 = nb0; b1 = nb1;
-                __builtin_amdgcn_sched_barrier(0);
-            }
+        for (int g = 0; g < KG; ++g) load_a(0, g);
+#pragma unroll
+        for (int g = 0; g < kAhead; ++g) load_b(g);
+        acc[0][0] = zero; acc[0][1] = zero;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < KG; ++g) {
+            if (g + kAhead < KG) load_b(g + kAhead);
+            if (g < 4) load_rowterm(0, g);
+            if (!AREG) load_a(1, g);
+            Elem<T>::mma(acc[0][0], Ah[0][g], B0[g]);
+            Elem<T>::mma(acc[0][1], Ah[0][g], B1[g]);
+            __builtin_amdgcn_sched_barrier(0);
         }
         // rows 32..63 on the matrix pipe, rows 0..31 on the vector unit
-        load_rowterms(0);
-        load_a(1);
+        if (AREG)
+#pragma unroll
+            for (int g = 0; g < KG; ++g) load_a(1, g);
+#pragma unroll
+        for (int g = 0; g < kAhead; ++g) load_b(g);
         acc[1][0] = zero; acc[1][1] = zero;
-        {
-            Frag b0 = *reinterpret_cast<const Frag*>(bp0), b1 = *reinterpret_cast<const Frag*>(bp1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < KG; ++g) {
+            if (g + kAhead < KG) load_b(g + kAhead);
+            if (g >= KG - 4) load_rowterm(1, g - (KG - 4));
+            Elem<T>::mma(acc[1][0], Ah[1][g], B0[g]);
+#pragma unroll
+            for (int r = g * RPI; r < g * RPI + (RPI + 1) / 2; ++r) finish(0, r);
+            Elem<T>::mma(acc[1][1], Ah[1][g], B1[g]);
+#pragma unroll
+            for (int r = g * RPI + (RPI + 1) / 2; r < (g + 1) * RPI; ++r) finish(0, r);
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int g = 0; g < KG; ++g) {
-                Frag nb0 = b0, nb1 = b1;
-                if (g + 1 < KG) {
-                    nb0 = *reinterpret_cast<const Frag*>(bp0 + 32 * (g + 1));
-                    nb1 = *reinterpret_cast<const Frag*>(bp1 + 32 * (g + 1));
-                }
-                Elem<T>::mma(acc[1][0], Ah[g], b0);
-#pragma unroll
-                for (int r = g * RPI; r < g * RPI + (RPI + 1) / 2; ++r) finish(0, r);
-                Elem<T>::mma(acc[1][1], Ah[g], b1);
-#pragma unroll
-                for (int r = g * RPI + (RPI + 1) / 2; r < (g + 1) * RPI; ++r) finish(0, r);
-                b0 = nb0; b1 = nb1;
-                __builtin_amdgcn_sched_barrier(0);
-            }
         }
-        load_rowterms(1);
 #pragma unroll
         for (int r = 0; r < 16; ++r) finish(1, r);
         if (!SUM) return 0.f;
@@ -273,20 +267,47 @@ __device__ __forceinline__ void settle(floatx16 (&v)[2][2]) {
     asm volatile("" : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[1][0]), "+v"(v[1][1]));
 }
 
-// One decision of the walk (Alg. 2 lines 5-9 for token j of the panel): every lane tests the sign of its
-// sigma (which carries the threshold, see the kernel), lane j's outcome is picked out of the compare mask on the scalar unit and comes
-// back as the scalar +1/-1 that multiplies row j of the diagonal tile.  Two vector instructions per
-// step; lanes <= j hold g[j] = 0, so their sigma stays at its decision-time value.
-template <int J>
-__device__ __forceinline__ void walk_step(float& sv, const float (&g)[64]) {
-    float sg;
-    asm volatile("v_cmp_gt_f32 vcc, 0, %1\n\ts_bitcmp1_b64 vcc, %2\n\ts_cselect_b32 %0, 1.0, -1.0"
-                 : "=s"(sg) : "v"(sv), "n"(J) : "vcc", "scc");
-    sv = fmaf(sg, g[J], sv);
+// One decision of the walk (Alg. 2 lines 5-9 for token j of the panel).  Every lane tests the sign of its sigma
+// (which carries the threshold, see the kernel); the compare mask is then read back as data by the vector unit:
+// bit j of it, sign-extended, becomes the -1/+1 that multiplies row j of the diagonal tile.  No scalar-unit hop
+// on the chain: four dependent vector instructions per step.  A vector instruction that reads a scalar register
+// written by the vector instruction just before it needs two wait states on this hardware, hence the s_nop.
+// Lanes <= j hold g[j] = 0, so their sigma stays at its decision-time value.
+// Eight consecutive steps per asm statement, so that nothing is scheduled into the chain.
+template <int B>
+__device__ __forceinline__ void walk_steps8(float& sv, const float (&g)[64], unsigned int sign_bit) {
+    int t;
+    if constexpr (B < 32)
+        asm volatile("v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_lo, %11, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %3\n\t"
+                     "v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_lo, %12, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %4\n\t"
+                     "v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_lo, %13, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %5\n\t"
+                     "v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_lo, %14, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %6\n\t"
+                     "v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_lo, %15, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %7\n\t"
+                     "v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_lo, %16, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %8\n\t"
+                     "v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_lo, %17, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %9\n\t"
+                     "v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_lo, %18, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %10"
+                     : "+v"(sv), "=&v"(t)
+                     : "s"(sign_bit), "v"(g[B]), "v"(g[B + 1]), "v"(g[B + 2]), "v"(g[B + 3]), "v"(g[B + 4]), "v"(g[B + 5]), "v"(g[B + 6]), "v"(g[B + 7]),
+                       "n"(B), "n"(B + 1), "n"(B + 2), "n"(B + 3), "n"(B + 4), "n"(B + 5), "n"(B + 6), "n"(B + 7)
+                     : "vcc");
+    else
+        asm volatile("v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_hi, %11, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %3\n\t"
+                     "v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_hi, %12, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %4\n\t"
+                     "v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_hi, %13, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %5\n\t"
+                     "v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_hi, %14, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %6\n\t"
+                     "v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_hi, %15, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %7\n\t"
+                     "v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_hi, %16, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %8\n\t"
+                     "v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_hi, %17, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %9\n\t"
+                     "v_cmp_le_f32 vcc, 0, %0\n\ts_nop 1\n\tv_bfe_i32 %1, vcc_hi, %18, 1\n\tv_and_or_b32 %1, %1, %2, 1.0\n\tv_fmac_f32 %0, %1, %10"
+                     : "+v"(sv), "=&v"(t)
+                     : "s"(sign_bit), "v"(g[B]), "v"(g[B + 1]), "v"(g[B + 2]), "v"(g[B + 3]), "v"(g[B + 4]), "v"(g[B + 5]), "v"(g[B + 6]), "v"(g[B + 7]),
+                       "n"(B - 32), "n"(B - 31), "n"(B - 30), "n"(B - 29), "n"(B - 28), "n"(B - 27), "n"(B - 26), "n"(B - 25)
+                     : "vcc");
+    // per step: sigma >= 0 -> bit set, factor -1 (eta = -1); sigma < 0 -> factor +1
 }
-template <int... Js>
-__device__ __forceinline__ void walk_panel(float& sv, const float (&g)[64], std::integer_sequence<int, Js...>) {
-    (walk_step<Js>(sv, g), ...);
+__device__ __forceinline__ void walk_panel(float& sv, const float (&g)[64], unsigned int sign_bit) {
+    walk_steps8<0>(sv, g, sign_bit);  walk_steps8<8>(sv, g, sign_bit);  walk_steps8<16>(sv, g, sign_bit); walk_steps8<24>(sv, g, sign_bit);
+    walk_steps8<32>(sv, g, sign_bit); walk_steps8<40>(sv, g, sign_bit); walk_steps8<48>(sv, g, sign_bit); walk_steps8<56>(sv, g, sign_bit);
 }
 
 template <typename T, int D, bool EMIT_G>
@@ -349,57 +370,40 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
 
     // sigma starts at minus the threshold: the walk tests (sum of signed weights - threshold) < 0.  Integer work,
     // done first so that it overlaps the latency of the loads below.
-    for (int i = tid; i < b; i += kThreads) sigma[i] = -threshold(i);
+    for (int i = tid; i < b; i += kThreads) sigma[i] = 0.f - threshold(i);      // never -0: the sign bit alone decides
 
     // column sums for the block mean, accumulated while rows pass through the registers
     float part[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) part[e] = 0.f;
-    if (center && !single_chunk) {                       // blocks larger than a chunk: one streaming pass up front
-        constexpr int U = 8;
-        for (int i0 = rg; i0 < b; i0 += RG * U) {
-            uintx4 raw[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)min(i0 + u * RG, b - 1) * G::kRowBytes + sl * 16);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                float f[EPL];
-                Elem<T>::unpack(raw[u], f);
-                if (i0 + u * RG < b)
-#pragma unroll
-                    for (int e = 0; e < EPL; ++e) part[e] += f[e];
-            }
-        }
-    }
 
     const int n_chunks = (b + CH - 1) / CH;
-    // rows [row0, row0 + rows_here) of the block -> LDS (several rows in flight per thread)
-    auto stage_chunk = [&](int row0, int rows_here, bool acc_mean) {
-        constexpr int U = 8;
-        for (int i0 = rg; i0 < rows_here; i0 += RG * U) {
+    // Rows [row0, row0 + rows_here) of the block -> LDS, many rows in flight per thread; the first rows_sum rows
+    // from row0 (possibly more than are staged) also enter the column sums of the mean.
+    auto stage_chunk = [&](int row0, int rows_here, int rows_sum) {
+        constexpr int U = 16;
+        const int rows_all = max(rows_here, rows_sum);
+        for (int i0 = rg; i0 < rows_all; i0 += RG * U) {
             uintx4 raw[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int i = i0 + u * RG;
-                if (i < rows_here) raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)(row0 + i) * G::kRowBytes + sl * 16);
+                if (i < rows_all) raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)(row0 + i) * G::kRowBytes + sl * 16);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int i = i0 + u * RG;
-                if (i < rows_here) {
-                    *reinterpret_cast<uintx4*>(ldsK + (size_t)i * G::kLdsRow + sl * 16) = raw[u];
-                    if (acc_mean) {
-                        float f[EPL];
-                        Elem<T>::unpack(raw[u], f);
+                if (i < rows_here) *reinterpret_cast<uintx4*>(ldsK + (size_t)i * G::kLdsRow + sl * 16) = raw[u];
+                if (i < rows_sum) {
+                    float f[EPL];
+                    Elem<T>::unpack(raw[u], f);
 #pragma unroll
-                        for (int e = 0; e < EPL; ++e) part[e] += f[e];
-                    }
+                    for (int e = 0; e < EPL; ++e) part[e] += f[e];
                 }
             }
         }
     };
-    stage_chunk(0, min(CH, b), center && single_chunk);
+    stage_chunk(0, min(CH, b), center ? b : 0);
     if (center) {                        // column sums of every wavefront -> LDS
 #pragma unroll
         for (int o = SL; o < 64; o <<= 1)
@@ -488,7 +492,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         const int p0 = row0 >> 6, p1 = (row0 + rows_here) >> 6;
         if (c > 0) {
             __syncthreads();                           // previous users of ldsK are done
-            stage_chunk(row0, rows_here, false);
+            stage_chunk(row0, rows_here, 0);
             __syncthreads();
         }
         const float row_const = scal[1];
@@ -568,6 +572,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         // Every wavefront passes exactly two barriers per superstep; the three roles keep their
         // registers apart by living in separate branches.
         if (wave == 0) {
+            unsigned int sign_bit = 0x80000000u;
+            asm volatile("" : "+s"(sign_bit));             // stays in a scalar register
             for (int I = p0; I < p1; ++I) {
                 // ------------------------------------------------ the walk over panel I (Alg. 2 lines 4-10)
                 // this lane's column of the diagonal tile: g[j] = g_{j,lane} for j < lane, else 0
@@ -580,7 +586,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 // sigma holds (sum of signed weights so far) - (1 - 2 u): eta = +1 <=> u < 1/2 - s/2 <=> sigma < 0
                 float sv = sigma[(I << 6) + lane];
                 __builtin_amdgcn_s_setprio(3);                // the serial chain goes first on its SIMD
-                walk_panel(sv, g, std::make_integer_sequence<int, 64>{});
+                walk_panel(sv, g, sign_bit);
                 __builtin_amdgcn_s_setprio(0);
                 const unsigned long long m = __ballot(sv < 0.f);
                 if (lane == 0) etaMask[I] = m;
@@ -780,7 +786,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         const char* Vseq = do_v ? a.V + (size_t)seq * a.v_seq_stride * G::kRowBytes : nullptr;
         char* Vo = do_v ? a.V_out + out_tok0 * G::kRowBytes : nullptr;
         const bool k_global = Ko && !single_chunk;
-        constexpr int U = 8;
+        constexpr int U = 16;
         for (int r0 = rg; r0 < half; r0 += RG * U) {
             uintx4 kraw[U], vraw[U];
             if (do_v) {

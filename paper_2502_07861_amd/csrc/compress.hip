@@ -161,7 +161,7 @@ struct TileOps {
                                                  int n, int h) {
         constexpr int KG = G::kGroups;
         constexpr int RPI = 16 / KG;                       // accumulator registers (per column half) finished per k-group
-        constexpr int kAhead = 2;                          // k-groups between the request of a B fragment and its use
+        constexpr int kAhead = KG < 4 ? KG : 4;              // k-groups between the request of a B fragment and its use
         static_assert(RPI >= 1 && KG >= 4, "4 to 16 k-groups per row");
         const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         float cs0 = 0.f, cs1 = 0.f;
@@ -192,6 +192,23 @@ struct TileOps {
                 cs1 = fmaf(sq[rb][r >> 2][r & 3], acc[rb][1][r], cs1);
             }
         };
+        // the same for registers r0 .. r0+RPI-1, one kind of instruction at a time (dependent instructions kept apart)
+        auto finish_group = [&](int rb, int r0, int step) {
+#pragma unroll
+            for (int r = r0; r < r0 + RPI; ++r) {
+                if (step == 0) {
+                    acc[rb][0][r] = fmaf(acc[rb][0][r], alpha, at[rb][r >> 2][r & 3]);
+                    acc[rb][1][r] = fmaf(acc[rb][1][r], alpha, at[rb][r >> 2][r & 3]);
+                } else if (step == 1) {
+                    acc[rb][0][r] = fast_exp2(acc[rb][0][r]);
+                    acc[rb][1][r] = fast_exp2(acc[rb][1][r]);
+                } else if (SUM) {
+                    cs0 = fmaf(sq[rb][r >> 2][r & 3], acc[rb][0][r], cs0);
+                    cs1 = fmaf(sq[rb][r >> 2][r & 3], acc[rb][1][r], cs1);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
         // rows 0..31 on the matrix pipe; requests for what the next stage needs ride along
 #pragma unroll
         for (int g = 0; g < KG; ++g) load_a(0, g);
@@ -221,11 +238,10 @@ struct TileOps {
             if (g + kAhead < KG) load_b(g + kAhead);
             if (g >= KG - 4) load_rowterm(1, g - (KG - 4));
             Elem<T>::mma(acc[1][0], Ah[1][g], B0[g]);
-#pragma unroll
-            for (int r = g * RPI; r < g * RPI + (RPI + 1) / 2; ++r) finish(0, r);
+            finish_group(0, g * RPI, 0);                   // scale-and-shift of this k-group's share of rows 0..31 ...
             Elem<T>::mma(acc[1][1], Ah[1][g], B1[g]);
-#pragma unroll
-            for (int r = g * RPI + (RPI + 1) / 2; r < (g + 1) * RPI; ++r) finish(0, r);
+            finish_group(0, g * RPI, 1);                   // ... their exponentials ...
+            finish_group(0, g * RPI, 2);                   // ... and the signed sums
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
@@ -234,6 +250,90 @@ struct TileOps {
         cs0 += __shfl_xor(cs0, 32);
         cs1 += __shfl_xor(cs1, 32);
         return h ? cs1 : cs0;
+    }
+    // One row panel (A in registers, signs in registers) against nJ consecutive 64-row column panels in LDS,
+    // software-pipelined over half tiles: while the matrix pipe forms rows 0..31 of the next tile the vector unit
+    // finishes rows 32..63 of the current one, and vice versa, so that neither unit waits for the other even when
+    // two wavefronts share a SIMD.  emit(jj, cs) receives this lane's column 32*h + n of tile jj's signed column sums.
+    template <typename Emit>
+    static __device__ __forceinline__ void row_sweep(const Frag (&A)[G::kGroups][2], const char* ldsB, int nJ,
+                                                     const float* aterm_panel, float alpha, const float (&sg)[32],
+                                                     int n, int h, Emit emit) {
+        constexpr int KG = G::kGroups;
+        constexpr int RPI = 16 / KG;
+        constexpr int kAhead = KG < 3 ? KG : 3;
+        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        floatx16 acc[2][2];
+        float cs0 = 0.f, cs1 = 0.f;
+        const char* bp0 = ldsB + (size_t)n * G::kLdsRow + 16 * h;
+        Frag B0[KG], B1[KG];
+        floatx4 at[4];
+        auto load_b = [&](int g) {
+            B0[g] = *reinterpret_cast<const Frag*>(bp0 + 32 * g);
+            B1[g] = *reinterpret_cast<const Frag*>(bp0 + (size_t)32 * G::kLdsRow + 32 * g);
+        };
+        auto load_at = [&](int rb) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) at[q] = *reinterpret_cast<const floatx4*>(aterm_panel + 32 * rb + 8 * q + 4 * h);
+        };
+        auto finish = [&](int rb, int r) {
+            acc[rb][0][r] = fast_exp2(fmaf(acc[rb][0][r], alpha, at[r >> 2][r & 3]));
+            acc[rb][1][r] = fast_exp2(fmaf(acc[rb][1][r], alpha, at[r >> 2][r & 3]));
+            cs0 = fmaf(sg[16 * rb + r], acc[rb][0][r], cs0);
+            cs1 = fmaf(sg[16 * rb + r], acc[rb][1][r], cs1);
+        };
+        auto finish_group = [&](int rb, int r0, int step) {
+#pragma unroll
+            for (int r = r0; r < r0 + RPI; ++r) {
+                if (step == 0) {
+                    acc[rb][0][r] = fmaf(acc[rb][0][r], alpha, at[r >> 2][r & 3]);
+                    acc[rb][1][r] = fmaf(acc[rb][1][r], alpha, at[r >> 2][r & 3]);
+                } else if (step == 1) {
+                    acc[rb][0][r] = fast_exp2(acc[rb][0][r]);
+                    acc[rb][1][r] = fast_exp2(acc[rb][1][r]);
+                } else {
+                    cs0 = fmaf(sg[16 * rb + r], acc[rb][0][r], cs0);
+                    cs1 = fmaf(sg[16 * rb + r], acc[rb][1][r], cs1);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // the MFMAs of row half RBM of the tile at bp0; with FIN, the other half (of the previous product) is finished alongside
+        auto stage = [&](auto rbm_c, auto fin_c) {
+            constexpr int RBM = decltype(rbm_c)::value;
+            constexpr bool FIN = decltype(fin_c)::value;
+#pragma unroll
+            for (int g = 0; g < kAhead; ++g) load_b(g);
+            if (FIN) load_at(1 - RBM);
+            acc[RBM][0] = zero; acc[RBM][1] = zero;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int g = 0; g < KG; ++g) {
+                if (g + kAhead < KG) load_b(g + kAhead);
+                Elem<T>::mma(acc[RBM][0], A[g][RBM], B0[g]);
+                if (FIN) finish_group(1 - RBM, g * RPI, 0);
+                Elem<T>::mma(acc[RBM][1], A[g][RBM], B1[g]);
+                if (FIN) { finish_group(1 - RBM, g * RPI, 1); finish_group(1 - RBM, g * RPI, 2); }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        stage(std::integral_constant<int, 0>{}, std::false_type{});
+#pragma unroll 1
+        for (int jj = 0; jj < nJ; ++jj) {
+            cs0 = 0.f; cs1 = 0.f;
+            stage(std::integral_constant<int, 1>{}, std::true_type{});         // rows 32..63 of tile jj | finish rows 0..31
+            if (jj + 1 < nJ) {
+                bp0 += (size_t)64 * G::kLdsRow;
+                stage(std::integral_constant<int, 0>{}, std::true_type{});     // rows 0..31 of tile jj+1 | finish rows 32..63
+            } else {
+                load_at(1);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) finish(1, r);
+            }
+            cs0 += __shfl_xor(cs0, 32);
+            cs1 += __shfl_xor(cs1, 32);
+            emit(jj, h ? cs1 : cs0);
+        }
     }
     // Diagonal tile: apply the column factors and zero everything that is not strictly above the diagonal
     // (the walk only ever adds eta_j * g_jl for l > j) ...
@@ -445,7 +545,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         }
         if (center || need_norm) {
             float amax = -3.0e38f;
-            constexpr int U = 4;
+            constexpr int U = 8;
             for (int i0 = rg; i0 < b; i0 += RG * U) {          // b is a multiple of 64 >= RG; rows past b are skipped
                 uintx4 raw[U];
 #pragma unroll
@@ -455,9 +555,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     const int i = i0 + u * RG;
                     float f[EPL];
                     Elem<T>::unpack(raw[u], f);
-                    float pa = 0.f, pn = 0.f;
+                    float pa = 0.f;
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) { pa = fmaf(f[e], mloc[e], pa); pn = fmaf(f[e], f[e], pn); }
+                    for (int e = 0; e < EPL; ++e) pa = fmaf(f[e], mloc[e], pa);
+                    float pn = Elem<T>::dot(raw[u], raw[u]);          // exact products, fp32 accumulation
                     pa = group_sum<SL>(pa);
                     pn = group_sum<SL>(pn);
                     if (i < b) {
@@ -511,13 +612,20 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 Ops::load_frags(A, Kin + (size_t)(I << 6) * G::kRowBytes, G::kRowBytes, n, h);
                 float sg[32];
                 Ops::signs_from_mask(sg, etaMask[I], h);
+                if constexpr (!EMIT_G) {
+                    const bool first_panel = first;
+                    Ops::row_sweep(A, ldsK, nJ, aterm + (I << 6), alpha, sg, n, h, [&](int jj, float cs) {
+                        float* slot = partial + (wave * 8 + jj) * 64 + lane;          // this wavefront's own slot
+                        *slot = first_panel ? cs : *slot + cs;
+                    });
+                } else
 #pragma unroll 1
                 for (int jj = 0; jj < nJ; ++jj) {
                     const int J = p0 + jj;
                     const char* ldsB = ldsK + (size_t)(jj << 6) * G::kLdsRow;
                     floatx16 acc[2][2];
                     const float cs = Ops::template tile<true, true>(acc, A, nullptr, ldsB, aterm + (I << 6), alpha, sg, nullptr, n, h);
-                    if (EMIT_G) {
+                    {
                         const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
 #pragma unroll
                         for (int rb = 0; rb < 2; ++rb)

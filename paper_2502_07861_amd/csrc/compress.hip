@@ -35,9 +35,14 @@ namespace bkv {
 
 template <typename T, int D> struct Geo {
     static constexpr int kRowBytes = D * (int)sizeof(T);
-    static constexpr int kLdsRow = kRowBytes + 16;          // +16 B: conflict-free 16-byte reads
+    static constexpr int kLdsRow = kRowBytes;               // rows are packed; 16-byte slices are permuted per row instead
     static constexpr int kGroups = kRowBytes / 32;          // k-groups of 32 bytes per row
     static constexpr int kSlices = kRowBytes / 16;          // 16-byte slices per row
+    // Slice s of LDS row r is stored at slice position s ^ key(r).  Sixteen consecutive rows reading the same
+    // logical slice (an MFMA operand fetch) then touch sixteen different groups of four banks, and so do the
+    // slices of one row (staging, gathers): no padding bytes, no bank conflicts.  key(r) = key(r + 16).
+    static __device__ __forceinline__ int key(int row) { return kRowBytes >= 256 ? (row & 15) : ((row >> 1) & (kSlices - 1)); }
+    static __device__ __forceinline__ int slice_off(int row, int slice) { return (slice ^ key(row)) << 4; }
 };
 
 constexpr int kWaves = 8;
@@ -56,12 +61,12 @@ static inline size_t lds_fixed_bytes(int b) {
 // rows of the block staged in LDS at a time: as many 64-row panels as fit, at most 8
 static inline int chunk_rows_for(int row_bytes, int b) {
     int rows = 512;
-    while (rows > 64 && (size_t)rows * (row_bytes + 16) + lds_fixed_bytes(b) > (size_t)kLdsLimit) rows -= 64;
+    while (rows > 64 && (size_t)rows * row_bytes + lds_fixed_bytes(b) > (size_t)kLdsLimit) rows -= 64;
     return b < rows ? b : rows;
 }
 
 size_t compress_lds_bytes(int row_bytes, int b) {
-    return (size_t)chunk_rows_for(row_bytes, b) * (row_bytes + 16) + lds_fixed_bytes(b);
+    return (size_t)chunk_rows_for(row_bytes, b) * row_bytes + lds_fixed_bytes(b);
 }
 
 template <typename T, int D>
@@ -79,41 +84,8 @@ struct TileOps {
                 F[g][rb] = *reinterpret_cast<const Frag*>(base + (size_t)(32 * rb + n) * row_stride + 32 * g + 16 * h);
     }
 
-    // acc = A_I * B_J^T with B read from LDS rows ldsB[0..63].
     // Accumulator layout (32x32 MFMA): register r of lane (n,h) is row 8*(r/4) + 4*h + r%4, column n.
-    static __device__ __forceinline__ void gram(floatx16 (&acc)[2][2], const Frag (&A)[G::kGroups][2],
-                                                const char* ldsB, int n, int h) {
-        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        acc[0][0] = zero; acc[0][1] = zero; acc[1][0] = zero; acc[1][1] = zero;    // folds into the first MFMA's C operand
-#pragma unroll
-        for (int g = 0; g < G::kGroups; ++g) {
-            Frag b0 = *reinterpret_cast<const Frag*>(ldsB + (size_t)n * G::kLdsRow + 32 * g + 16 * h);
-            Frag b1 = *reinterpret_cast<const Frag*>(ldsB + (size_t)(32 + n) * G::kLdsRow + 32 * g + 16 * h);
-            Elem<T>::mma(acc[0][0], A[g][0], b0);
-            Elem<T>::mma(acc[0][1], A[g][0], b1);
-            Elem<T>::mma(acc[1][0], A[g][1], b0);
-            Elem<T>::mma(acc[1][1], A[g][1], b1);
-        }
-    }
 
-    // acc <- exp2(alpha * acc + rterm[row])  (kernel weight without the column factor)
-    static __device__ __forceinline__ void weights(floatx16 (&acc)[2][2], const float* aterm_panel, float alpha, int h) {
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const floatx4 at = *reinterpret_cast<const floatx4*>(aterm_panel + 32 * rb + 8 * q + 4 * h);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    acc[rb][0][4 * q + e] = fast_exp2(fmaf(acc[rb][0][4 * q + e], alpha, at[e]));
-                    acc[rb][1][4 * q + e] = fast_exp2(fmaf(acc[rb][1][4 * q + e], alpha, at[e]));
-                }
-            }
-    }
-
-    // sum over the 64 rows of eta_row * weight, per column; returns this lane's column 32*h + n
-    // (before the column factor).  The signs of a row panel come packed for this register layout:
-    // word h holds, at bit 16*rb + r, the sign of row 32*rb + 8*(r/4) + 4*h + r%4 (1 = '+').
     // Signs of a row panel for the accumulator layout: entry 16*rb + r of lane half h belongs to row
     // 32*rb + 8*(r/4) + 4*h + r%4.  From the panel's mask (bit j = 1 iff eta_j = +1) ...
     static __device__ __forceinline__ void signs_from_mask(float (&sg)[32], unsigned long long m, int h) {
@@ -133,6 +105,7 @@ struct TileOps {
             sg[4 * q] = t[0]; sg[4 * q + 1] = t[1]; sg[4 * q + 2] = t[2]; sg[4 * q + 3] = t[3];
         }
     }
+    // sum over the 64 rows of sign * weight, per column; returns this lane's column 32*h + n (before the column factor)
     static __device__ __forceinline__ float signed_colsum(const floatx16 (&v)[2][2], const float (&sg)[32], int h) {
         float cs0 = 0.f, cs1 = 0.f;
 #pragma unroll
@@ -158,24 +131,24 @@ struct TileOps {
     template <bool SUM, bool AREG>
     static __device__ __forceinline__ float tile(floatx16 (&acc)[2][2], const Frag (*A)[2], const char* ldsA, const char* ldsB,
                                                  const float* aterm_panel, float alpha, const float* sg, const float* sgn_h,
-                                                 int n, int h) {
+                                                 const int (&foff)[G::kGroups], int n, int h) {
         constexpr int KG = G::kGroups;
         constexpr int RPI = 16 / KG;                       // accumulator registers (per column half) finished per k-group
         constexpr int kAhead = KG < 4 ? KG : 4;              // k-groups between the request of a B fragment and its use
         static_assert(RPI >= 1 && KG >= 4, "4 to 16 k-groups per row");
         const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         float cs0 = 0.f, cs1 = 0.f;
-        const char* bp0 = ldsB + (size_t)n * G::kLdsRow + 16 * h;
+        const char* bp0 = ldsB + (size_t)n * G::kLdsRow;
         const char* bp1 = bp0 + (size_t)32 * G::kLdsRow;
-        const char* ap = AREG ? nullptr : ldsA + (size_t)n * G::kLdsRow + 16 * h;
+        const char* ap = AREG ? nullptr : ldsA + (size_t)n * G::kLdsRow;
         Frag Ah[2][KG], B0[KG], B1[KG];
         floatx4 at[2][4], sq[2][4];
         auto load_a = [&](int rb, int g) {
-            Ah[rb][g] = AREG ? A[g][rb] : *reinterpret_cast<const Frag*>(ap + (size_t)(32 * rb) * G::kLdsRow + 32 * g);
+            Ah[rb][g] = AREG ? A[g][rb] : *reinterpret_cast<const Frag*>(ap + (size_t)(32 * rb) * G::kLdsRow + foff[g]);
         };
         auto load_b = [&](int g) {
-            B0[g] = *reinterpret_cast<const Frag*>(bp0 + 32 * g);
-            B1[g] = *reinterpret_cast<const Frag*>(bp1 + 32 * g);
+            B0[g] = *reinterpret_cast<const Frag*>(bp0 + foff[g]);
+            B1[g] = *reinterpret_cast<const Frag*>(bp1 + foff[g]);
         };
         auto load_rowterm = [&](int rb, int q) {
             at[rb][q] = *reinterpret_cast<const floatx4*>(aterm_panel + 32 * rb + 8 * q + 4 * h);
@@ -257,20 +230,27 @@ struct TileOps {
     // two wavefronts share a SIMD.  emit(jj, cs) receives this lane's column 32*h + n of tile jj's signed column sums.
     template <typename Emit>
     static __device__ __forceinline__ void row_sweep(const Frag (&A)[G::kGroups][2], const char* ldsB, int nJ,
-                                                     const float* aterm_panel, float alpha, const float (&sg)[32],
-                                                     int n, int h, Emit emit) {
+                                                     const float* aterm_panel, float alpha, unsigned long long eta_mask,
+                                                     const int (&foff)[G::kGroups], int n, int h, Emit emit) {
         constexpr int KG = G::kGroups;
         constexpr int RPI = 16 / KG;
         constexpr int kAhead = KG < 3 ? KG : 3;
         const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         floatx16 acc[2][2];
         float cs0 = 0.f, cs1 = 0.f;
-        const char* bp0 = ldsB + (size_t)n * G::kLdsRow + 16 * h;
+        // signs are formed where they are used (two cheap instructions per row) rather than held in 32 registers:
+        // bit 8*(r/4) + r%4 of word rb is set iff the row of accumulator register r, row half rb, has eta = -1
+        const unsigned long long mh = ~eta_mask >> (4 * h);
+        const unsigned int nbw[2] = {(unsigned int)mh, (unsigned int)(mh >> 32)};
+        auto sign_of = [&](int rb, int r) -> float {
+            return __uint_as_float(((nbw[rb] << (31 - (8 * (r >> 2) + (r & 3)))) & 0x80000000u) | 0x3f800000u);
+        };
+        const char* bp0 = ldsB + (size_t)n * G::kLdsRow;
         Frag B0[KG], B1[KG];
         floatx4 at[4];
         auto load_b = [&](int g) {
-            B0[g] = *reinterpret_cast<const Frag*>(bp0 + 32 * g);
-            B1[g] = *reinterpret_cast<const Frag*>(bp0 + (size_t)32 * G::kLdsRow + 32 * g);
+            B0[g] = *reinterpret_cast<const Frag*>(bp0 + foff[g]);
+            B1[g] = *reinterpret_cast<const Frag*>(bp0 + (size_t)32 * G::kLdsRow + foff[g]);
         };
         auto load_at = [&](int rb) {
 #pragma unroll
@@ -279,8 +259,9 @@ struct TileOps {
         auto finish = [&](int rb, int r) {
             acc[rb][0][r] = fast_exp2(fmaf(acc[rb][0][r], alpha, at[r >> 2][r & 3]));
             acc[rb][1][r] = fast_exp2(fmaf(acc[rb][1][r], alpha, at[r >> 2][r & 3]));
-            cs0 = fmaf(sg[16 * rb + r], acc[rb][0][r], cs0);
-            cs1 = fmaf(sg[16 * rb + r], acc[rb][1][r], cs1);
+            const float sr = sign_of(rb, r);
+            cs0 = fmaf(sr, acc[rb][0][r], cs0);
+            cs1 = fmaf(sr, acc[rb][1][r], cs1);
         };
         auto finish_group = [&](int rb, int r0, int step) {
 #pragma unroll
@@ -292,8 +273,9 @@ struct TileOps {
                     acc[rb][0][r] = fast_exp2(acc[rb][0][r]);
                     acc[rb][1][r] = fast_exp2(acc[rb][1][r]);
                 } else {
-                    cs0 = fmaf(sg[16 * rb + r], acc[rb][0][r], cs0);
-                    cs1 = fmaf(sg[16 * rb + r], acc[rb][1][r], cs1);
+                    const float sr = sign_of(rb, r);
+                    cs0 = fmaf(sr, acc[rb][0][r], cs0);
+                    cs1 = fmaf(sr, acc[rb][1][r], cs1);
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -435,6 +417,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: roles branch on scalars
     const int n = lane & 31, h = lane >> 5;
+    int foff[G::kGroups];                      // byte offset, inside an LDS row, of this lane's fragment of k-group g
+#pragma unroll
+    for (int g = 0; g < G::kGroups; ++g) foff[g] = G::slice_off(n, 2 * g + h);
     const int64_t inst = blockIdx.x;
     const int64_t seq = inst / a.blocks_per_seq;
     const int blk = (int)(inst - seq * a.blocks_per_seq);
@@ -462,9 +447,17 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         return 1.f - 2.f * u;
     };
 
+    // First byte of LDS row `r` of the resident chunk.  The row number passes through an empty asm so that the
+    // compiler forms tile addresses where they are used (scalar base + per-lane fragment offset) instead of
+    // carrying one induction register per fragment across the panel loops.
+    auto lds_rows = [&](int r) -> const char* {
+        asm volatile("" : "+s"(r));
+        return ldsK + (size_t)r * G::kLdsRow;
+    };
+
     // 16-byte slice `sl` of row i: from the resident chunk (single-chunk blocks) or from global memory
     auto row_slice = [&](int i) -> uintx4 {
-        if (single_chunk) return *reinterpret_cast<const uintx4*>(ldsK + (size_t)i * G::kLdsRow + sl * 16);
+        if (single_chunk) return *reinterpret_cast<const uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, sl));
         return *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
     };
 
@@ -493,7 +486,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int i = i0 + u * RG;
-                if (i < rows_here) *reinterpret_cast<uintx4*>(ldsK + (size_t)i * G::kLdsRow + sl * 16) = raw[u];
+                if (i < rows_here) *reinterpret_cast<uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, sl)) = raw[u];
                 if (i < rows_sum) {
                     float f[EPL];
                     Elem<T>::unpack(raw[u], f);
@@ -610,21 +603,21 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             for (int I = wave; I < p0; I += kWaves) {
                 Frag A[G::kGroups][2];
                 Ops::load_frags(A, Kin + (size_t)(I << 6) * G::kRowBytes, G::kRowBytes, n, h);
-                float sg[32];
-                Ops::signs_from_mask(sg, etaMask[I], h);
                 if constexpr (!EMIT_G) {
                     const bool first_panel = first;
-                    Ops::row_sweep(A, ldsK, nJ, aterm + (I << 6), alpha, sg, n, h, [&](int jj, float cs) {
+                    Ops::row_sweep(A, ldsK, nJ, aterm + (I << 6), alpha, etaMask[I], foff, n, h, [&](int jj, float cs) {
                         float* slot = partial + (wave * 8 + jj) * 64 + lane;          // this wavefront's own slot
                         *slot = first_panel ? cs : *slot + cs;
                     });
-                } else
+                } else {
+                float sg[32];
+                Ops::signs_from_mask(sg, etaMask[I], h);
 #pragma unroll 1
                 for (int jj = 0; jj < nJ; ++jj) {
                     const int J = p0 + jj;
-                    const char* ldsB = ldsK + (size_t)(jj << 6) * G::kLdsRow;
+                    const char* ldsB = lds_rows(jj << 6);
                     floatx16 acc[2][2];
-                    const float cs = Ops::template tile<true, true>(acc, A, nullptr, ldsB, aterm + (I << 6), alpha, sg, nullptr, n, h);
+                    const float cs = Ops::template tile<true, true>(acc, A, nullptr, ldsB, aterm + (I << 6), alpha, sg, nullptr, foff, n, h);
                     {
                         const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
 #pragma unroll
@@ -640,6 +633,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     }
                     float* slot = partial + (wave * 8 + jj) * 64 + lane;      // this wavefront's own slot
                     *slot = first ? cs : *slot + cs;
+                }
                 }
                 first = false;
             }
@@ -657,9 +651,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         }
         // diagonal tile of the chunk's first panel
         if (wave == 1) {
-            const char* ldsA = ldsK + (size_t)((p0 << 6) - row0) * G::kLdsRow;
+            const char* ldsA = lds_rows((p0 << 6) - row0);
             floatx16 acc[2][2];
-            Ops::template tile<false, false>(acc, nullptr, ldsA, ldsA, aterm + (p0 << 6), alpha, nullptr, nullptr, n, h);
+            Ops::template tile<false, false>(acc, nullptr, ldsA, ldsA, aterm + (p0 << 6), alpha, nullptr, nullptr, foff, n, h);
             const float e0 = fast_exp2(aterm[(p0 << 6) + n] - row_const), e1 = fast_exp2(aterm[(p0 << 6) + 32 + n] - row_const);
             if (EMIT_G) {
 #pragma unroll
@@ -713,9 +707,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 const int J = I + 1;
                 floatx16 held[2][2];
                 {
-                    const char* ldsA = ldsK + (size_t)((I << 6) - row0) * G::kLdsRow;
-                    const char* ldsB = ldsK + (size_t)((J << 6) - row0) * G::kLdsRow;
-                    Ops::template tile<false, false>(held, nullptr, ldsA, ldsB, aterm + (I << 6), alpha, nullptr, nullptr, n, h);
+                    const char* ldsA = lds_rows((I << 6) - row0);
+                    const char* ldsB = lds_rows((J << 6) - row0);
+                    Ops::template tile<false, false>(held, nullptr, ldsA, ldsB, aterm + (I << 6), alpha, nullptr, nullptr, foff, n, h);
                 }
                 settle(held);
                 __syncthreads();                               // eta_I is visible
@@ -745,8 +739,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 // ------------------------------------------------ diagonal tile of panel I+1, stored once the walker has read tile I
                 floatx16 dv[2][2];
                 {
-                    const char* ldsA = ldsK + (size_t)(((I + 1) << 6) - row0) * G::kLdsRow;
-                    Ops::template tile<false, false>(dv, nullptr, ldsA, ldsA, aterm + ((I + 1) << 6), alpha, nullptr, nullptr, n, h);
+                    const char* ldsA = lds_rows(((I + 1) << 6) - row0);
+                    Ops::template tile<false, false>(dv, nullptr, ldsA, ldsA, aterm + ((I + 1) << 6), alpha, nullptr, nullptr, foff, n, h);
                 }
                 {
                     const float e0 = fast_exp2(aterm[((I + 1) << 6) + n] - row_const), e1 = fast_exp2(aterm[((I + 1) << 6) + 32 + n] - row_const);
@@ -776,13 +770,13 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 // tiles (I-1, J): wave 3+k takes J = I+1+k, and again every fifth J after that
                 const int c_first = wave - 3, c_step = kWaves - 3;
                 if (c_first < nC) {
-                    const char* ldsA = ldsK + (size_t)(((I - 1) << 6) - row0) * G::kLdsRow;
+                    const char* ldsA = lds_rows(((I - 1) << 6) - row0);
                     const float* sgn_h = etaF + (((I - 1) & 1) << 6) + 32 * h;
                     for (int cj = c_first; cj < nC; cj += c_step) {
                         const int J = I + 1 + cj;
-                        const char* ldsB = ldsK + (size_t)((J << 6) - row0) * G::kLdsRow;
+                        const char* ldsB = lds_rows((J << 6) - row0);
                         floatx16 acc[2][2];
-                        const float cs = Ops::template tile<true, false>(acc, nullptr, ldsA, ldsB, aterm + ((I - 1) << 6), alpha, nullptr, sgn_h, n, h);
+                        const float cs = Ops::template tile<true, false>(acc, nullptr, ldsA, ldsB, aterm + ((I - 1) << 6), alpha, nullptr, sgn_h, foff, n, h);
                         if (EMIT_G) {
                             const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
 #pragma unroll
@@ -914,7 +908,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int r = r0 + u * RG;
-                    if (r < half) kraw[u] = *reinterpret_cast<const uintx4*>(ldsK + (size_t)keptIdx[r] * G::kLdsRow + sl * 16);
+                    if (r < half) {
+                        const int kr = keptIdx[r];
+                        kraw[u] = *reinterpret_cast<const uintx4*>(ldsK + (size_t)kr * G::kLdsRow + G::slice_off(kr, sl));
+                    }
                 }
             }
             if (Ko) {

@@ -39,6 +39,9 @@ struct CompressArgs {
     float cterm;              // -sqrt(d) * ln c
     float rkey2;              // r_key^2, <= 0: measure
     uint32_t flags;
+    int32_t stagger_blocks;   // the first stagger_blocks workgroups (one per compute unit) start stagger_step clock
+    int32_t stagger_step;     // ticks apart, so that the memory-bound phases of successive blocks do not coincide chip-wide
+    int32_t prefetch_ahead;   // > 0: while walking, touch the keys of block (this + prefetch_ahead) so that they sit in L2 / MALL
 };
 
 size_t compress_lds_bytes(int row_bytes, int b);

@@ -433,6 +433,15 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     const float alpha = a.alpha;
     float* Gi = EMIT_G ? a.G_out + (size_t)inst * b * b : nullptr;
 
+    // Every block of a launch takes the same time, so compute units that start together stay in lockstep and
+    // would all hit HBM in the same phases.  The first wave of workgroups therefore starts spread over one
+    // block duration (a bounded wait on the clock); later workgroups inherit the offsets.
+    if (a.stagger_step > 0 && (int)blockIdx.x < a.stagger_blocks) {
+        const long long wait = (long long)a.stagger_step * (long long)blockIdx.x;
+        const long long t0 = __builtin_amdgcn_s_memtime();
+        while (__builtin_amdgcn_s_memtime() - t0 < wait) __builtin_amdgcn_s_sleep(32);
+    }
+
     // generator stream of this instance
     uint64_t stream = a.tree_mode ? (uint64_t)(64 * (a.seq_base + seq) + a.round) : (uint64_t)inst;
     if (a.inst_ids) stream = a.inst_ids[inst];
@@ -764,7 +773,29 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             __syncthreads();                                   // last panel of the chunk: nothing to prepare
             __syncthreads();
         } else {
+            // While the walk is busy on chip, four of these wavefronts touch the keys of the block that this compute
+            // unit is likely to receive next (one dword per 16 bytes: every cache line of panel I of that block),
+            // so that its staging pass finds them in L2 / MALL.  The values are only consumed one superstep later.
+            constexpr int PF = G::kRowBytes / 64;                               // loads per wavefront and superstep
+            const int64_t inst_pf = inst + a.prefetch_ahead;
+            const bool do_pf = a.prefetch_ahead > 0 && inst_pf < (int64_t)gridDim.x && wave < 7;
+            const char* Kpf = nullptr;
+            if (do_pf) {
+                const int64_t seq_pf = inst_pf / a.blocks_per_seq;
+                const int64_t blk_pf = inst_pf - seq_pf * a.blocks_per_seq;
+                Kpf = a.K + (seq_pf * a.in_seq_stride + blk_pf * b) * G::kRowBytes + ((wave - 3) * PF) * 1024 + lane * 16;
+            }
+            int pfv[PF], pfacc = 0;
+#pragma unroll
+            for (int j = 0; j < PF; ++j) pfv[j] = 0;
             for (int I = p0; I < p1; ++I) {
+                if (do_pf) {
+#pragma unroll
+                    for (int j = 0; j < PF; ++j) {
+                        pfacc ^= pfv[j];
+                        pfv[j] = *reinterpret_cast<const int*>(Kpf + (size_t)(I << 6) * G::kRowBytes + j * 1024);
+                    }
+                }
                 const bool has_next = I + 1 < p1;
                 const int nC = (I > p0 && has_next) ? p1 - I - 1 : 0;       // tiles (I-1, J), J = I+1 .. p1-1
                 // tiles (I-1, J): wave 3+k takes J = I+1+k, and again every fifth J after that
@@ -796,6 +827,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 __syncthreads();                               // eta_I is visible
                 __syncthreads();                               // sigma[I+1] is complete
             }
+#pragma unroll
+            for (int j = 0; j < PF; ++j) pfacc ^= pfv[j];
+            asm volatile("" :: "v"(pfacc));                   // the touches must not be optimised away
         }
     }
 
@@ -957,6 +991,24 @@ hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64
     const int row_bytes = d * (dtype == BKV_BF16 ? 2 : 4);
     a.chunk_rows = chunk_rows_for(row_bytes, a.b);
     if (n_inst <= 0) return hipSuccess;
+    {
+        // one workgroup per compute unit is resident (LDS); with at least two rounds of workgroups, spread the first
+        static thread_local int n_cu = 0;
+        if (n_cu == 0) {
+            int dev = 0;
+            hipDeviceProp_t prop;
+            if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
+            n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+        }
+        a.stagger_blocks = 0; a.stagger_step = 0; a.prefetch_ahead = 0;
+        if (n_inst >= 2 * (int64_t)n_cu) {
+            // rough duration of one block in clock ticks (measured: about 75k for 512 bf16 tokens, 200k for 1024)
+            const double ticks = (40.0e3 + 0.15 * (double)a.b * (double)a.b) * (dtype == BKV_BF16 ? 1.0 : 1.5);
+            a.stagger_blocks = n_cu;
+            a.stagger_step = (int)(ticks / n_cu);
+            a.prefetch_ahead = n_cu;
+        }
+    }
     // grids are one-dimensional; split very large launches
     const int64_t kMaxGrid = 1ll << 30;
     if (n_inst > kMaxGrid) return hipErrorInvalidValue;

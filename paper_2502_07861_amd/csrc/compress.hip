@@ -464,9 +464,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         return ldsK + (size_t)r * G::kLdsRow;
     };
 
-    // 16-byte slice `sl` of row i: from the resident chunk (single-chunk blocks) or from global memory
-    auto row_slice = [&](int i) -> uintx4 {
-        if (single_chunk) return *reinterpret_cast<const uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, sl));
+    // 16-byte slice `sl` of row i: from the resident first chunk or, for later rows, from global memory
+    auto row_slice = [&](int i) -> uintx4 {       // only used while the first chunk (rows 0 .. CH-1) is resident
+        if (i < CH) return *reinterpret_cast<const uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, sl));
         return *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
     };
 
@@ -933,10 +933,17 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 }
             }
             if (k_global) {
+                const int res0 = (n_chunks - 1) * CH;          // rows from here on are still resident (last chunk)
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int r = r0 + u * RG;
-                    if (r < half) kraw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)keptIdx[r] * G::kRowBytes + sl * 16);
+                    if (r < half) {
+                        const int kr = keptIdx[r];
+                        if (kr >= res0)
+                            kraw[u] = *reinterpret_cast<const uintx4*>(ldsK + (size_t)(kr - res0) * G::kLdsRow + G::slice_off(kr - res0, sl));
+                        else
+                            kraw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)kr * G::kRowBytes + sl * 16);
+                    }
                 }
             } else if (Ko) {
 #pragma unroll

@@ -1,24 +1,23 @@
 // SoftmaxBalance (Alg. 2 of arXiv 2502.07861) on gfx950: Gram tiles on MFMA, kernel weights and
 // the self-balancing walk on chip, strict halving, gather of the survivors.
 //
-// One workgroup (8 wavefronts) owns one block of b tokens; its keys are staged in LDS in chunks of
-// up to kChunkRows rows.  The walk is organised over 64-token panels.  sigma[l] (LDS) accumulates
-// sum_{i signed so far} eta_i g_il for every column l.  Wavefront 0 is the walker: for panel I it
-// reads the strictly-upper part of the 64x64 diagonal tile of kernel weights as "one column per
-// lane" registers and takes the 64 sequential decisions of Alg. 2 (lane j compares sigma_j with
-// 1 - 2 u_j; its outcome is broadcast with a readlane and every later lane adds eta_j g_jl).
-// Wavefronts 1..7 form tiles on MFMA while the walker walks, in a static schedule:
+// One workgroup (8 wavefronts) owns one block of b tokens; its keys are staged in LDS in chunks of as many 64-row
+// panels as fit.  The walk is organised over 64-token panels.  sigma[l] (LDS) starts at minus the decision threshold
+// of token l and accumulates sum_{i signed so far} eta_i g_il.  Wavefront 0 is the walker: for panel I it holds the
+// strictly-upper part of the 64x64 diagonal tile of kernel weights as "one column per lane" registers and takes the 64
+// sequential decisions of Alg. 2 (lane j tests the sign of its sigma; bit j of the compare mask becomes the +-1 that
+// every later lane multiplies g_jl with).  Wavefronts 1..7 form tiles on MFMA while the walker walks, in a static
+// schedule:
 //
 //   superstep I:   walker            walk(I)
-//                  wave 1            diagonal tile of panel I+1  -> LDS (double buffered)
+//                  wave 1            diagonal tile of panel I+1 (stored to LDS between the two barriers)
 //                  wave 2            tile (I, I+1) without signs, kept in registers
-//                  waves 3..7 (,1)   tiles (I-1, J), J > I: multiply row i by eta_i, sum over rows,
-//                                    add the column sums into sigma[J]          (eta_{I-1} is known)
+//                  waves 3..7        tiles (I-1, J), J > I: weights, times eta of row panel I-1, summed over rows,
+//                                    added into sigma[J]                              (eta_{I-1} is known)
 //                  barrier; wave 2 applies eta_I to its tile -> sigma[I+1]; barrier
 //
-// so the only work between two walks is one signed column sum.  Rows of earlier chunks (b larger
-// than one chunk) are streamed from global memory as the A operand against the resident chunk
-// before its own panels are walked.
+// so the only work between two walks is one signed column sum.  Rows of earlier chunks (b larger than one chunk)
+// come back from global memory (L2) as the A operand against the resident chunk before its own panels are walked.
 //
 // Kernel weight: g_ij = exp((<k_i,k_j> - a_i - a_j + |mu|^2 - A)/sqrt(d) - ln c), a_i = <k_i,mu>
 // (mu = block mean when keys are centred, else 0), A = r_key^2 or the largest centred squared norm:

@@ -58,6 +58,7 @@ extern "C" {
 
 /* status word written per instance (bkv_compress_block) */
 #define BKV_STATUS_FAIL 1   /* bit 0: |y^T eta| > c R^2 happened (Alg. 2 line 6); p was clamped */
+#define BKV_STATUS_INTERNAL 2 /* bit 1: the kernel's internal pipeline timed out; the instance's outputs are invalid (never expected) */
 /* bits 8..31: number of decisions whose margin |u_j - p_j| was below 1e-4 */
 
 typedef struct bkv_params {

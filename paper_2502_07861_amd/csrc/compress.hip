@@ -53,9 +53,10 @@ constexpr int kLdsLimit = 160 * 1024;
 static inline size_t lds_fixed_bytes(int b) {
     return (size_t)b * 4 * 2             // sigma, aterm
            + 16 * 8                      // eta of each panel as a 64-bit mask (bit j = 1 iff eta_j = +1)
-           + 2 * 64 * 4                  // eta of the two most recent panels as +-1 floats, same layout
+           + 8 * 64 * 4                  // eta of the resident chunk's panels as +-1 floats, accumulator order
            + kDiagFloats * 4             // diagonal tile (also: mean partials, survivor list)
-           + 64;                         // scalars
+           + 64                          // scalars
+           + 128;                        // progress counters of the panel pipeline
 }
 // rows of the block staged in LDS at a time: as many 64-row panels as fit, at most 8
 static inline int chunk_rows_for(int row_bytes, int b) {
@@ -342,12 +343,6 @@ struct TileOps {
     }
 };
 
-// The tile must be complete at this point of the program: the compiler may otherwise sink register-only
-// work (MFMAs, exponentials) past a barrier into the stretch every wavefront waits on.
-__device__ __forceinline__ void settle(floatx16 (&v)[2][2]) {
-    asm volatile("" : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[1][0]), "+v"(v[1][1]));
-}
-
 // One decision of the walk (Alg. 2 lines 5-9 for token j of the panel).  Every lane tests the sign of its sigma
 // (which carries the threshold, see the kernel); the compare mask is then read back as data by the vector unit:
 // bit j of it, sign-extended, becomes the -1/+1 that multiplies row j of the diagonal tile.  No scalar-unit hop
@@ -391,6 +386,23 @@ __device__ __forceinline__ void walk_panel(float& sv, const float (&g)[64], unsi
     walk_steps8<32>(sv, g, sign_bit); walk_steps8<40>(sv, g, sign_bit); walk_steps8<48>(sv, g, sign_bit); walk_steps8<56>(sv, g, sign_bit);
 }
 
+// Progress counters in LDS (one writer each, values only grow): a wavefront publishes with a release store and
+// waits with a bounded poll.  Every wait is for an event that only depends on earlier events of the same block, and
+// all eight wavefronts are resident, so the polls end; the bound turns a logic error into a status bit instead of
+// a hang.
+constexpr int kSpinLimit = 1 << 16;
+__device__ __forceinline__ void publish(int* counter, int value) {
+    __hip_atomic_store(counter, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ void await(int* counter, int value, int* err) {
+    for (int it = 0; it < kSpinLimit; ++it) {
+        const int seen = __builtin_amdgcn_readfirstlane(__hip_atomic_load(counter, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
+        if (seen >= value) return;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
 template <typename T, int D, bool EMIT_G>
 __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a) {
     typedef Geo<T, D> G;
@@ -407,9 +419,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     float* sigma = reinterpret_cast<float*>(smem + (size_t)CH * G::kLdsRow);
     float* aterm = sigma + b;                                      // -alpha * a_i; column factor = exp2(aterm)
     unsigned long long* etaMask = reinterpret_cast<unsigned long long*>(aterm + b);   // bit j of entry I: eta of token 64 I + j is +1
-    float* etaF = reinterpret_cast<float*>(etaMask + 16);          // [2][2][32]: +-1 of panel I at slot I&1, entry h*32 + 16*rb + r
-    float* diag = etaF + 128;                                      // [64 columns][kDiagStride], transposed
+    float* etaF = reinterpret_cast<float*>(etaMask + 16);          // [8][2][32]: +-1 of the chunk's panel l, entry h*32 + 16*rb + r
+    float* diag = etaF + 512;                                      // [64 columns][kDiagStride], transposed
     float* scal = diag + kDiagFloats;                              // [0] |mu|^2, [1] A, [2..2+kWaves) partial maxima
+    int* prog = reinterpret_cast<int*>(scal + 16);                 // progress counters, see the panel pipeline below
     float* wpart = diag;                                           // [kWaves][D] column sums (statistics phase only)
     int* keptIdx = reinterpret_cast<int*>(diag);                   // [b/2]        (output phase only)
 
@@ -461,12 +474,6 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     auto lds_rows = [&](int r) -> const char* {
         asm volatile("" : "+s"(r));
         return ldsK + (size_t)r * G::kLdsRow;
-    };
-
-    // 16-byte slice `sl` of row i: from the resident first chunk or, for later rows, from global memory
-    auto row_slice = [&](int i) -> uintx4 {       // only used while the first chunk (rows 0 .. CH-1) is resident
-        if (i < CH) return *reinterpret_cast<const uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, sl));
-        return *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
     };
 
     // sigma starts at minus the threshold: the walk tests (sum of signed weights - threshold) < 0.  Integer work,
@@ -547,13 +554,18 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         if (center || need_norm) {
             float amax = -3.0e38f;
             constexpr int U = 8;
-            for (int i0 = rg; i0 < b; i0 += RG * U) {          // b is a multiple of 64 >= RG; rows past b are skipped
+            for (int ib0 = 0; ib0 < b; ib0 += RG * U) {        // b is a multiple of 64 and of RG; whole row groups are skipped past b
                 uintx4 raw[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) raw[u] = row_slice(min(i0 + u * RG, b - 1));
+                for (int u = 0; u < U; ++u) {
+                    const int ib = ib0 + u * RG;                // first row of this group: the same in every thread
+                    const int i = min(ib + rg, b - 1);
+                    if (ib < CH) raw[u] = *reinterpret_cast<const uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, sl));
+                    else raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
+                }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const int i = i0 + u * RG;
+                    const int i = ib0 + u * RG + rg;
                     float f[EPL];
                     Elem<T>::unpack(raw[u], f);
                     float pa = 0.f;
@@ -657,42 +669,70 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             }
             __syncthreads();                              // the buffer goes back to the diagonal tile
         }
-        // diagonal tile of the chunk's first panel
-        if (wave == 1) {
-            const char* ldsA = lds_rows((p0 << 6) - row0);
-            floatx16 acc[2][2];
-            Ops::template tile<false, false>(acc, nullptr, ldsA, ldsA, aterm + (p0 << 6), alpha, nullptr, nullptr, foff, n, h);
-            const float e0 = fast_exp2(aterm[(p0 << 6) + n] - row_const), e1 = fast_exp2(aterm[(p0 << 6) + 32 + n] - row_const);
+        // ---------------------------------------------------------- panels of this chunk: a dataflow pipeline
+        // No barriers in here.  Counters (all start at 0, local panel index l = I - p0):
+        //   eta_done      panels walked so far (the walker publishes after writing the signs of panel l)
+        //   diag_ready    diagonal tiles stored so far        diag_taken   diagonal tiles the walker has loaded so far
+        //   col[l]        row panels of this chunk already added into sigma of column panel l, in ascending order
+        // Tile (i, l), i < l, needs nothing for its weights; its signed column sum needs eta_done > i and is added
+        // when col[l] == i, so every sigma receives its contributions in the same order on every run.  The walker
+        // starts panel l when col[l] == l.  Wavefront 1 forms the diagonal tiles, wavefront 2 the tiles (l-1, l) that
+        // the walker waits for, wavefronts 3..7 all others in order of need (by column, then by row).
+        int* eta_done = prog;
+        int* diag_ready = prog + 1;
+        int* diag_taken = prog + 2;
+        int* sync_err = prog + 3;
+        int* col = prog + 8;
+        if (tid < 32 && tid != 3) prog[tid] = 0;
+        if (c == 0 && tid == 3) prog[3] = 0;
+        __syncthreads();
+        const int nPc = p1 - p0;
+        // weights of tile (li, lj) -> acc, and with EMIT_G both mirror images of it to the dump
+        auto off_diag_weights = [&](floatx16 (&acc)[2][2], int li, int lj) {
+            const int I = p0 + li, J = p0 + lj;
+            Ops::template tile<false, false>(acc, nullptr, lds_rows(li << 6), lds_rows(lj << 6), aterm + (I << 6), alpha, nullptr, nullptr, foff, n, h);
             if (EMIT_G) {
+                const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
 #pragma unroll
                 for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const int row = 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-                        Gi[(size_t)((p0 << 6) + row) * b + (p0 << 6) + n] = acc[rb][0][r] * e0;
-                        Gi[(size_t)((p0 << 6) + row) * b + (p0 << 6) + 32 + n] = acc[rb][1][r] * e1;
+                        const int row = (I << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+                        Gi[(size_t)row * b + (J << 6) + n] = acc[rb][0][r] * e0;
+                        Gi[(size_t)row * b + (J << 6) + 32 + n] = acc[rb][1][r] * e1;
+                        Gi[(size_t)((J << 6) + n) * b + row] = acc[rb][0][r] * e0;
+                        Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r] * e1;
                     }
             }
-            Ops::mask_diag(acc, e0, e1, n, h);
-            Ops::store_diag(diag, acc, n, h);
-        }
-        __syncthreads();
-
-        // ---------------------------------------------------------- panels of this chunk
-        // Every wavefront passes exactly two barriers per superstep; the three roles keep their
-        // registers apart by living in separate branches.
+        };
+        // signs of row panel li (once the walker has published them), column sums, then sigma of column panel lj in turn
+        auto sign_and_add = [&](const floatx16 (&acc)[2][2], int li, int lj) {
+            const int J = p0 + lj;
+            const float ecol = fast_exp2(aterm[(J << 6) + lane] - row_const);
+            await(eta_done, li + 1, sync_err);
+            float sg[32];
+            Ops::signs_from_lds(sg, etaF + (li << 6) + 32 * h);
+            const float cs = Ops::signed_colsum(acc, sg, h);
+            await(col + lj, li, sync_err);
+            sigma[(J << 6) + lane] = fmaf(cs, ecol, sigma[(J << 6) + lane]);
+            publish(col + lj, li + 1);
+        };
         if (wave == 0) {
             unsigned int sign_bit = 0x80000000u;
             asm volatile("" : "+s"(sign_bit));             // stays in a scalar register
-            for (int I = p0; I < p1; ++I) {
+            for (int l = 0; l < nPc; ++l) {
+                const int I = p0 + l;
                 // ------------------------------------------------ the walk over panel I (Alg. 2 lines 4-10)
                 // this lane's column of the diagonal tile: g[j] = g_{j,lane} for j < lane, else 0
+                await(diag_ready, l + 1, sync_err);
                 float g[64];
 #pragma unroll
                 for (int t = 0; t < 16; ++t) {
                     const floatx4 v = *reinterpret_cast<const floatx4*>(diag + lane * kDiagStride + 4 * t);
                     g[4 * t] = v[0]; g[4 * t + 1] = v[1]; g[4 * t + 2] = v[2]; g[4 * t + 3] = v[3];
                 }
+                publish(diag_taken, l + 1);                   // the tile is in registers: the buffer may be overwritten
+                await(col + l, l, sync_err);                   // sigma of this panel is complete
                 // sigma holds (sum of signed weights so far) - (1 - 2 u): eta = +1 <=> u < 1/2 - s/2 <=> sigma < 0
                 float sv = sigma[(I << 6) + lane];
                 __builtin_amdgcn_s_setprio(3);                // the serial chain goes first on its SIMD
@@ -703,91 +743,29 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 {
                     const int k = lane & 31;
                     const int row = 32 * (k >> 4) + 8 * ((k & 15) >> 2) + 4 * h + (k & 3);
-                    etaF[((I & 1) << 6) + lane] = ((m >> row) & 1ull) ? 1.f : -1.f;
+                    etaF[(l << 6) + lane] = ((m >> row) & 1ull) ? 1.f : -1.f;
                 }
                 sigma[(I << 6) + lane] = sv;                  // decision-time values, read back for the statistics
-                __syncthreads();                               // eta_I is visible
-                __syncthreads();                               // sigma[I+1] is complete
+                publish(eta_done, l + 1);
             }
-        } else if (wave == 2) {
-            for (int I = p0; I + 1 < p1; ++I) {
-                // ------------------------------------------------ tile (I, I+1): weights now, signs after the walk
-                const int J = I + 1;
-                floatx16 held[2][2];
-                {
-                    const char* ldsA = lds_rows((I << 6) - row0);
-                    const char* ldsB = lds_rows((J << 6) - row0);
-                    Ops::template tile<false, false>(held, nullptr, ldsA, ldsB, aterm + (I << 6), alpha, nullptr, nullptr, foff, n, h);
-                }
-                settle(held);
-                __syncthreads();                               // eta_I is visible
-                if (EMIT_G) {
-                    const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
-#pragma unroll
-                    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int row = (I << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-                            Gi[(size_t)row * b + (J << 6) + n] = held[rb][0][r] * e0;
-                            Gi[(size_t)row * b + (J << 6) + 32 + n] = held[rb][1][r] * e1;
-                            Gi[(size_t)((J << 6) + n) * b + row] = held[rb][0][r] * e0;
-                            Gi[(size_t)((J << 6) + 32 + n) * b + row] = held[rb][1][r] * e1;
-                        }
-                }
-                float sg[32];
-                Ops::signs_from_lds(sg, etaF + ((I & 1) << 6) + 32 * h);
-                const float cs = Ops::signed_colsum(held, sg, h);
-                sigma[(J << 6) + lane] = fmaf(cs, fast_exp2(aterm[(J << 6) + lane] - row_const), sigma[(J << 6) + lane]);
-                __syncthreads();                               // sigma[I+1] is complete
-            }
-            __syncthreads();                                   // last panel of the chunk: nothing to prepare
-            __syncthreads();
         } else if (wave == 1) {
-            for (int I = p0; I + 1 < p1; ++I) {
-                // ------------------------------------------------ diagonal tile of panel I+1, stored once the walker has read tile I
-                floatx16 dv[2][2];
-                {
-                    const char* ldsA = lds_rows(((I + 1) << 6) - row0);
-                    Ops::template tile<false, false>(dv, nullptr, ldsA, ldsA, aterm + ((I + 1) << 6), alpha, nullptr, nullptr, foff, n, h);
-                }
-                {
-                    const float e0 = fast_exp2(aterm[((I + 1) << 6) + n] - row_const), e1 = fast_exp2(aterm[((I + 1) << 6) + 32 + n] - row_const);
-                    if (EMIT_G) {
-#pragma unroll
-                        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) {
-                                const int row = 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-                                Gi[(size_t)(((I + 1) << 6) + row) * b + ((I + 1) << 6) + n] = dv[rb][0][r] * e0;
-                                Gi[(size_t)(((I + 1) << 6) + row) * b + ((I + 1) << 6) + 32 + n] = dv[rb][1][r] * e1;
-                            }
-                    }
-                    Ops::mask_diag(dv, e0, e1, n, h);
-                }
-                settle(dv);
-                __syncthreads();                               // eta_I is visible; the walker is done with the diagonal tile
-                Ops::store_diag(diag, dv, n, h);
-                __syncthreads();                               // sigma[I+1] and the next diagonal tile are complete
-            }
-            __syncthreads();                                   // last panel of the chunk: nothing to prepare
-            __syncthreads();
-        } else {
-            // While the walk is busy on chip, four of these wavefronts touch the keys of the block that this compute
-            // unit is likely to receive next (one dword per 16 bytes: every cache line of panel I of that block),
-            // so that its staging pass finds them in L2 / MALL.  The values are only consumed one superstep later.
-            constexpr int PF = G::kRowBytes / 64;                               // loads per wavefront and superstep
+            // While the walk is busy on chip, this wavefront also touches the keys of the block that this compute
+            // unit is likely to receive next (one dword per 16 bytes: every cache line of one panel per tile), so that
+            // its staging pass finds them in L2 / MALL.  The values are only consumed one tile later.
+            constexpr int PF = G::kRowBytes / 16;                               // loads per panel
             const int64_t inst_pf = inst + a.prefetch_ahead;
-            const bool do_pf = a.prefetch_ahead > 0 && inst_pf < (int64_t)gridDim.x && wave < 7;
+            const bool do_pf = a.prefetch_ahead > 0 && inst_pf < (int64_t)gridDim.x;
             const char* Kpf = nullptr;
             if (do_pf) {
                 const int64_t seq_pf = inst_pf / a.blocks_per_seq;
                 const int64_t blk_pf = inst_pf - seq_pf * a.blocks_per_seq;
-                Kpf = a.K + (seq_pf * a.in_seq_stride + blk_pf * b) * G::kRowBytes + ((wave - 3) * PF) * 1024 + lane * 16;
+                Kpf = a.K + (seq_pf * a.in_seq_stride + blk_pf * b) * G::kRowBytes + lane * 16;
             }
             int pfv[PF], pfacc = 0;
 #pragma unroll
             for (int j = 0; j < PF; ++j) pfv[j] = 0;
-            for (int I = p0; I < p1; ++I) {
+            for (int l = 0; l < nPc; ++l) {
+                const int I = p0 + l;
                 if (do_pf) {
 #pragma unroll
                     for (int j = 0; j < PF; ++j) {
@@ -795,41 +773,45 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                         pfv[j] = *reinterpret_cast<const int*>(Kpf + (size_t)(I << 6) * G::kRowBytes + j * 1024);
                     }
                 }
-                const bool has_next = I + 1 < p1;
-                const int nC = (I > p0 && has_next) ? p1 - I - 1 : 0;       // tiles (I-1, J), J = I+1 .. p1-1
-                // tiles (I-1, J): wave 3+k takes J = I+1+k, and again every fifth J after that
-                const int c_first = wave - 3, c_step = kWaves - 3;
-                if (c_first < nC) {
-                    const char* ldsA = lds_rows(((I - 1) << 6) - row0);
-                    const float* sgn_h = etaF + (((I - 1) & 1) << 6) + 32 * h;
-                    for (int cj = c_first; cj < nC; cj += c_step) {
-                        const int J = I + 1 + cj;
-                        const char* ldsB = lds_rows((J << 6) - row0);
-                        floatx16 acc[2][2];
-                        const float cs = Ops::template tile<true, false>(acc, nullptr, ldsA, ldsB, aterm + ((I - 1) << 6), alpha, nullptr, sgn_h, foff, n, h);
-                        if (EMIT_G) {
-                            const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
+                // ------------------------------------------------ diagonal tile of panel I, stored once the walker has taken tile I-1
+                floatx16 dv[2][2];
+                Ops::template tile<false, false>(dv, nullptr, lds_rows(l << 6), lds_rows(l << 6), aterm + (I << 6), alpha, nullptr, nullptr, foff, n, h);
+                const float e0 = fast_exp2(aterm[(I << 6) + n] - row_const), e1 = fast_exp2(aterm[(I << 6) + 32 + n] - row_const);
+                if (EMIT_G) {
 #pragma unroll
-                            for (int rb = 0; rb < 2; ++rb)
+                    for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-                                for (int r = 0; r < 16; ++r) {
-                                    const int row = ((I - 1) << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-                                    Gi[(size_t)row * b + (J << 6) + n] = acc[rb][0][r] * e0;
-                                    Gi[(size_t)row * b + (J << 6) + 32 + n] = acc[rb][1][r] * e1;
-                                    Gi[(size_t)((J << 6) + n) * b + row] = acc[rb][0][r] * e0;
-                                    Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r] * e1;
-                                }
+                        for (int r = 0; r < 16; ++r) {
+                            const int row = 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+                            Gi[(size_t)((I << 6) + row) * b + (I << 6) + n] = dv[rb][0][r] * e0;
+                            Gi[(size_t)((I << 6) + row) * b + (I << 6) + 32 + n] = dv[rb][1][r] * e1;
                         }
-                        sigma[(J << 6) + lane] = fmaf(cs, fast_exp2(aterm[(J << 6) + lane] - row_const), sigma[(J << 6) + lane]);
-                    }
                 }
-                __syncthreads();                               // eta_I is visible
-                __syncthreads();                               // sigma[I+1] is complete
+                Ops::mask_diag(dv, e0, e1, n, h);
+                await(diag_taken, l, sync_err);
+                Ops::store_diag(diag, dv, n, h);
+                publish(diag_ready, l + 1);
             }
 #pragma unroll
             for (int j = 0; j < PF; ++j) pfacc ^= pfv[j];
             asm volatile("" :: "v"(pfacc));                   // the touches must not be optimised away
+        } else if (wave == 2) {
+            for (int l = 1; l < nPc; ++l) {
+                floatx16 held[2][2];
+                off_diag_weights(held, l - 1, l);              // weights before the walk of panel l-1 ends, signs after
+                sign_and_add(held, l - 1, l);
+            }
+        } else {
+            int t = 0;
+            for (int lj = 2; lj < nPc; ++lj)
+                for (int li = 0; li + 1 < lj; ++li, ++t) {
+                    if (t % (kWaves - 3) != wave - 3) continue;
+                    floatx16 acc[2][2];
+                    off_diag_weights(acc, li, lj);
+                    sign_and_add(acc, li, lj);
+                }
         }
+        __syncthreads();                                   // the chunk is done: LDS rows, counters and tile buffer are free
     }
 
     // ------------------------------------------------------------------ output step (Alg. 2 lines 12-16 + strict n/2)
@@ -891,11 +873,13 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         min_margin = wave_min(min_margin);
         max_sigma = wave_max(max_sigma);
         if (lane == 0) {
-            const int word = (any_fail ? BKV_STATUS_FAIL : 0) | (n_margin << 8);
+            const int sync_failed = prog[3];
+            const int word = (any_fail ? BKV_STATUS_FAIL : 0) | (sync_failed ? BKV_STATUS_INTERNAL : 0) | (n_margin << 8);
             if (a.status_out) {
                 if (a.tree_mode) {
                     int* dst = a.status_out + seq * a.status_stride + a.round;
                     if (any_fail) atomicOr(dst, BKV_STATUS_FAIL);
+                    if (sync_failed) atomicOr(dst, BKV_STATUS_INTERNAL);
                     if (n_margin) atomicAdd(dst, n_margin << 8);
                 } else {
                     a.status_out[inst] = word;

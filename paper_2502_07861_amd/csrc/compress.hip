@@ -97,6 +97,12 @@ struct TileOps {
             sg[k] = __uint_as_float(((w[k >> 4] << (31 - bit)) & 0x80000000u) | 0x3f800000u);   // +1 or -1
         }
     }
+    // cs0 / cs1: per-lane partial sums for columns n / 32+n over this lane half's rows.  Returns, in lane (n, h), the
+    // full sum of column 32*h + n: one half-wave swap (lanes 32..63 of cs0 <-> lanes 0..31 of cs1) and one add.
+    static __device__ __forceinline__ float halves_sum(float cs0, float cs1) {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(cs0), __float_as_uint(cs1), false, false);
+        return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
     // ... or as +-1 floats from LDS: this lane's 32 entries start at sgn_h = base + 32*h
     static __device__ __forceinline__ void signs_from_lds(float (&sg)[32], const float* sgn_h) {
 #pragma unroll
@@ -116,9 +122,7 @@ struct TileOps {
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) cs1 = fmaf(sg[16 * rb + r], v[rb][1][r], cs1);
-        cs0 += __shfl_xor(cs0, 32);
-        cs1 += __shfl_xor(cs1, 32);
-        return h ? cs1 : cs0;
+        return halves_sum(cs0, cs1);
     }
     // One 64x64 tile in two row halves: Gram of rows 0..31, then the Gram of rows 32..63 while the vector unit
     // turns the first half into kernel weights (acc <- exp2(alpha * acc + rterm[row])) and, with SUM, adds them up
@@ -202,13 +206,15 @@ struct TileOps {
         if (AREG)
 #pragma unroll
             for (int g = 0; g < KG; ++g) load_a(1, g);
+        constexpr bool kKeepB = KG <= 8;                   // up to 64 registers: the B fragments of the first half stay
+        if (!kKeepB)
 #pragma unroll
-        for (int g = 0; g < kAhead; ++g) load_b(g);
+            for (int g = 0; g < kAhead; ++g) load_b(g);
         acc[1][0] = zero; acc[1][1] = zero;
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int g = 0; g < KG; ++g) {
-            if (g + kAhead < KG) load_b(g + kAhead);
+            if (!kKeepB && g + kAhead < KG) load_b(g + kAhead);
             if (g >= KG - 4) load_rowterm(1, g - (KG - 4));
             Elem<T>::mma(acc[1][0], Ah[1][g], B0[g]);
             finish_group(0, g * RPI, 0);                   // scale-and-shift of this k-group's share of rows 0..31 ...
@@ -220,9 +226,7 @@ struct TileOps {
 #pragma unroll
         for (int r = 0; r < 16; ++r) finish(1, r);
         if (!SUM) return 0.f;
-        cs0 += __shfl_xor(cs0, 32);
-        cs1 += __shfl_xor(cs1, 32);
-        return h ? cs1 : cs0;
+        return halves_sum(cs0, cs1);
     }
     // One row panel (A in registers, signs in registers) against nJ consecutive 64-row column panels in LDS,
     // software-pipelined over half tiles: while the matrix pipe forms rows 0..31 of the next tile the vector unit
@@ -312,9 +316,7 @@ struct TileOps {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) finish(1, r);
             }
-            cs0 += __shfl_xor(cs0, 32);
-            cs1 += __shfl_xor(cs1, 32);
-            emit(jj, h ? cs1 : cs0);
+            emit(jj, halves_sum(cs0, cs1));
         }
     }
     // Diagonal tile: apply the column factors and zero everything that is not strictly above the diagonal
@@ -394,11 +396,12 @@ constexpr int kSpinLimit = 1 << 16;
 __device__ __forceinline__ void publish(int* counter, int value) {
     __hip_atomic_store(counter, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
+template <bool EAGER = false>
 __device__ __forceinline__ void await(int* counter, int value, int* err) {
     for (int it = 0; it < kSpinLimit; ++it) {
         const int seen = __builtin_amdgcn_readfirstlane(__hip_atomic_load(counter, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
         if (seen >= value) return;
-        __builtin_amdgcn_s_sleep(1);
+        if (!EAGER) __builtin_amdgcn_s_sleep(1);          // waits on the walk's critical path poll back to back
     }
     __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
@@ -709,17 +712,21 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         auto sign_and_add = [&](const floatx16 (&acc)[2][2], int li, int lj) {
             const int J = p0 + lj;
             const float ecol = fast_exp2(aterm[(J << 6) + lane] - row_const);
-            await(eta_done, li + 1, sync_err);
+            const bool urgent = li + 1 == lj;                  // the walker is waiting for this one: go first on the SIMD and in LDS
+            if (urgent) { __builtin_amdgcn_s_setprio(3); await<true>(eta_done, li + 1, sync_err); }
+            else await(eta_done, li + 1, sync_err);
             float sg[32];
             Ops::signs_from_lds(sg, etaF + (li << 6) + 32 * h);
             const float cs = Ops::signed_colsum(acc, sg, h);
             await(col + lj, li, sync_err);
             sigma[(J << 6) + lane] = fmaf(cs, ecol, sigma[(J << 6) + lane]);
             publish(col + lj, li + 1);
+            if (urgent) __builtin_amdgcn_s_setprio(0);
         };
         if (wave == 0) {
             unsigned int sign_bit = 0x80000000u;
             asm volatile("" : "+s"(sign_bit));             // stays in a scalar register
+            __builtin_amdgcn_s_setprio(3);                    // the serial chain goes first on its SIMD and in LDS
             for (int l = 0; l < nPc; ++l) {
                 const int I = p0 + l;
                 // ------------------------------------------------ the walk over panel I (Alg. 2 lines 4-10)
@@ -732,12 +739,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     g[4 * t] = v[0]; g[4 * t + 1] = v[1]; g[4 * t + 2] = v[2]; g[4 * t + 3] = v[3];
                 }
                 publish(diag_taken, l + 1);                   // the tile is in registers: the buffer may be overwritten
-                await(col + l, l, sync_err);                   // sigma of this panel is complete
+                await<true>(col + l, l, sync_err);             // sigma of this panel is complete
                 // sigma holds (sum of signed weights so far) - (1 - 2 u): eta = +1 <=> u < 1/2 - s/2 <=> sigma < 0
                 float sv = sigma[(I << 6) + lane];
-                __builtin_amdgcn_s_setprio(3);                // the serial chain goes first on its SIMD
                 walk_panel(sv, g, sign_bit);
-                __builtin_amdgcn_s_setprio(0);
                 const unsigned long long m = __ballot(sv < 0.f);
                 if (lane == 0) etaMask[I] = m;
                 {
@@ -748,6 +753,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 sigma[(I << 6) + lane] = sv;                  // decision-time values, read back for the statistics
                 publish(eta_done, l + 1);
             }
+            __builtin_amdgcn_s_setprio(0);
         } else if (wave == 1) {
             // While the walk is busy on chip, this wavefront also touches the keys of the block that this compute
             // unit is likely to receive next (one dword per 16 bytes: every cache line of one panel per tile), so that

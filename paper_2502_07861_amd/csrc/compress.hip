@@ -84,6 +84,15 @@ struct TileOps {
                 F[g][rb] = *reinterpret_cast<const Frag*>(base + (size_t)(32 * rb + n) * row_stride + 32 * g + 16 * h);
     }
 
+    // The same from 64 LDS rows (packed rows, permuted slices: foff[g] is this lane's byte offset of k-group g).
+    static __device__ __forceinline__ void load_panel(Frag (&F)[G::kGroups][2], const char* lds_panel,
+                                                      const int (&foff)[G::kGroups], int n) {
+#pragma unroll
+        for (int g = 0; g < G::kGroups; ++g)
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+                F[g][rb] = *reinterpret_cast<const Frag*>(lds_panel + (size_t)(32 * rb + n) * G::kLdsRow + foff[g]);
+    }
     // Accumulator layout (32x32 MFMA): register r of lane (n,h) is row 8*(r/4) + 4*h + r%4, column n.
 
     // Signs of a row panel for the accumulator layout: entry 16*rb + r of lane half h belongs to row
@@ -132,18 +141,20 @@ struct TileOps {
     // tiles) or from LDS rows ldsA[0..63], one half at a time; signs come from registers (sg) or, if sg is null,
     // from LDS (sgn_h: this lane half's 32 floats).  Returns this lane's column 32*h + n of the signed column sums
     // (before the column factor).
-    template <bool SUM, bool AREG>
+    // With BREG the column panel's fragments come from the caller's registers too (Bq), e.g. a panel that a
+    // wavefront keeps for all tiles of its column.
+    template <bool SUM, bool AREG, bool BREG = false>
     static __device__ __forceinline__ float tile(floatx16 (&acc)[2][2], const Frag (*A)[2], const char* ldsA, const char* ldsB,
                                                  const float* aterm_panel, float alpha, const float* sg, const float* sgn_h,
-                                                 const int (&foff)[G::kGroups], int n, int h) {
+                                                 const int (&foff)[G::kGroups], int n, int h, const Frag (*Bq)[2] = nullptr) {
         constexpr int KG = G::kGroups;
         constexpr int RPI = 16 / KG;                       // accumulator registers (per column half) finished per k-group
         constexpr int kAhead = KG < 4 ? KG : 4;              // k-groups between the request of a B fragment and its use
         static_assert(RPI >= 1 && KG >= 4, "4 to 16 k-groups per row");
         const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         float cs0 = 0.f, cs1 = 0.f;
-        const char* bp0 = ldsB + (size_t)n * G::kLdsRow;
-        const char* bp1 = bp0 + (size_t)32 * G::kLdsRow;
+        const char* bp0 = BREG ? nullptr : ldsB + (size_t)n * G::kLdsRow;
+        const char* bp1 = BREG ? nullptr : bp0 + (size_t)32 * G::kLdsRow;
         const char* ap = AREG ? nullptr : ldsA + (size_t)n * G::kLdsRow;
         Frag Ah[2][KG], B0[KG], B1[KG];
         floatx4 at[2][4], sq[2][4];
@@ -151,6 +162,7 @@ struct TileOps {
             Ah[rb][g] = AREG ? A[g][rb] : *reinterpret_cast<const Frag*>(ap + (size_t)(32 * rb) * G::kLdsRow + foff[g]);
         };
         auto load_b = [&](int g) {
+            if (BREG) { B0[g] = Bq[g][0]; B1[g] = Bq[g][1]; return; }
             B0[g] = *reinterpret_cast<const Frag*>(bp0 + foff[g]);
             B1[g] = *reinterpret_cast<const Frag*>(bp1 + foff[g]);
         };
@@ -206,7 +218,7 @@ struct TileOps {
         if (AREG)
 #pragma unroll
             for (int g = 0; g < KG; ++g) load_a(1, g);
-        constexpr bool kKeepB = KG <= 8;                   // up to 64 registers: the B fragments of the first half stay
+        constexpr bool kKeepB = BREG || KG <= 8;           // up to 64 registers: the B fragments of the first half stay
         if (!kKeepB)
 #pragma unroll
             for (int g = 0; g < kAhead; ++g) load_b(g);
@@ -393,14 +405,20 @@ __device__ __forceinline__ void walk_panel(float& sv, const float (&g)[64], unsi
 // all eight wavefronts are resident, so the polls end; the bound turns a logic error into a status bit instead of
 // a hang.
 constexpr int kSpinLimit = 1 << 16;
+// The fences name LDS only: a wavefront with global loads or stores in flight (look-ahead touches, dumps) must
+// not wait for them here.
 __device__ __forceinline__ void publish(int* counter, int value) {
-    __hip_atomic_store(counter, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __hip_atomic_store(counter, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 template <bool EAGER = false>
 __device__ __forceinline__ void await(int* counter, int value, int* err) {
     for (int it = 0; it < kSpinLimit; ++it) {
-        const int seen = __builtin_amdgcn_readfirstlane(__hip_atomic_load(counter, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
-        if (seen >= value) return;
+        const int seen = __builtin_amdgcn_readfirstlane(__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+        if (seen >= value) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+            return;
+        }
         if (!EAGER) __builtin_amdgcn_s_sleep(1);          // waits on the walk's critical path poll back to back
     }
     __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -676,11 +694,14 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         // No barriers in here.  Counters (all start at 0, local panel index l = I - p0):
         //   eta_done      panels walked so far (the walker publishes after writing the signs of panel l)
         //   diag_ready    diagonal tiles stored so far        diag_taken   diagonal tiles the walker has loaded so far
-        //   col[l]        row panels of this chunk already added into sigma of column panel l, in ascending order
-        // Tile (i, l), i < l, needs nothing for its weights; its signed column sum needs eta_done > i and is added
-        // when col[l] == i, so every sigma receives its contributions in the same order on every run.  The walker
-        // starts panel l when col[l] == l.  Wavefront 1 forms the diagonal tiles, wavefront 2 the tiles (l-1, l) that
-        // the walker waits for, wavefronts 3..7 all others in order of need (by column, then by row).
+        //   col[l]        set to l by the owner of column panel l once sigma of that panel holds every earlier row panel
+        // Wavefront w = 1..7 owns column panel w of the chunk: it keeps the panel's fragments in registers as the B
+        // operand and forms, in row order, the tiles (i, w), i < w (weights need nothing; the signed column sum needs
+        // eta_done > i and goes into a register copy of sigma); then, its column being complete just as the walk of
+        // panel w starts, the diagonal tile of panel w+2, which it stores when the walker has taken the previous one
+        // (the tiles of panels 0, 1, 2 come from wavefronts 7, 6, 5 at start-up).  Every sigma receives
+        // its contributions in the same order on every run.  At most one tile per wavefront and walked panel is due,
+        // so the walk (wavefront 0) only ever waits for the tile (l-1, l) that depends on its last signs.
         int* eta_done = prog;
         int* diag_ready = prog + 1;
         int* diag_taken = prog + 2;
@@ -690,48 +711,15 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         if (c == 0 && tid == 3) prog[3] = 0;
         __syncthreads();
         const int nPc = p1 - p0;
-        // weights of tile (li, lj) -> acc, and with EMIT_G both mirror images of it to the dump
-        auto off_diag_weights = [&](floatx16 (&acc)[2][2], int li, int lj) {
-            const int I = p0 + li, J = p0 + lj;
-            Ops::template tile<false, false>(acc, nullptr, lds_rows(li << 6), lds_rows(lj << 6), aterm + (I << 6), alpha, nullptr, nullptr, foff, n, h);
-            if (EMIT_G) {
-                const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
-#pragma unroll
-                for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int row = (I << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-                        Gi[(size_t)row * b + (J << 6) + n] = acc[rb][0][r] * e0;
-                        Gi[(size_t)row * b + (J << 6) + 32 + n] = acc[rb][1][r] * e1;
-                        Gi[(size_t)((J << 6) + n) * b + row] = acc[rb][0][r] * e0;
-                        Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r] * e1;
-                    }
-            }
-        };
-        // signs of row panel li (once the walker has published them), column sums, then sigma of column panel lj in turn
-        auto sign_and_add = [&](const floatx16 (&acc)[2][2], int li, int lj) {
-            const int J = p0 + lj;
-            const float ecol = fast_exp2(aterm[(J << 6) + lane] - row_const);
-            const bool urgent = li + 1 == lj;                  // the walker is waiting for this one: go first on the SIMD and in LDS
-            if (urgent) { __builtin_amdgcn_s_setprio(3); await<true>(eta_done, li + 1, sync_err); }
-            else await(eta_done, li + 1, sync_err);
-            float sg[32];
-            Ops::signs_from_lds(sg, etaF + (li << 6) + 32 * h);
-            const float cs = Ops::signed_colsum(acc, sg, h);
-            await(col + lj, li, sync_err);
-            sigma[(J << 6) + lane] = fmaf(cs, ecol, sigma[(J << 6) + lane]);
-            publish(col + lj, li + 1);
-            if (urgent) __builtin_amdgcn_s_setprio(0);
-        };
         if (wave == 0) {
             unsigned int sign_bit = 0x80000000u;
             asm volatile("" : "+s"(sign_bit));             // stays in a scalar register
-            __builtin_amdgcn_s_setprio(3);                    // the serial chain goes first on its SIMD and in LDS
+            __builtin_amdgcn_s_setprio(3);                    // the serial chain goes first on its SIMD
             for (int l = 0; l < nPc; ++l) {
                 const int I = p0 + l;
                 // ------------------------------------------------ the walk over panel I (Alg. 2 lines 4-10)
                 // this lane's column of the diagonal tile: g[j] = g_{j,lane} for j < lane, else 0
-                await(diag_ready, l + 1, sync_err);
+                await<true>(diag_ready, l + 1, sync_err);
                 float g[64];
 #pragma unroll
                 for (int t = 0; t < 16; ++t) {
@@ -750,38 +738,41 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     const int row = 32 * (k >> 4) + 8 * ((k & 15) >> 2) + 4 * h + (k & 3);
                     etaF[(l << 6) + lane] = ((m >> row) & 1ull) ? 1.f : -1.f;
                 }
-                sigma[(I << 6) + lane] = sv;                  // decision-time values, read back for the statistics
                 publish(eta_done, l + 1);
+                sigma[(I << 6) + lane] = sv;                  // decision-time values, read back for the statistics (nobody waits for it)
             }
             __builtin_amdgcn_s_setprio(0);
-        } else if (wave == 1) {
-            // While the walk is busy on chip, this wavefront also touches the keys of the block that this compute
-            // unit is likely to receive next (one dword per 16 bytes: every cache line of one panel per tile), so that
-            // its staging pass finds them in L2 / MALL.  The values are only consumed one tile later.
+        } else {
+            const int w = wave;                               // local column panel of this wavefront
+            const bool owner = w < nPc;
+            // While the chip is busy with the walk, each of these wavefronts also touches the keys of one panel of the
+            // block that this compute unit is likely to receive next (one dword per 16 bytes: every cache line), so
+            // that its staging pass finds them in L2 / MALL.  The values are only consumed at the end.
             constexpr int PF = G::kRowBytes / 16;                               // loads per panel
             const int64_t inst_pf = inst + a.prefetch_ahead;
             const bool do_pf = a.prefetch_ahead > 0 && inst_pf < (int64_t)gridDim.x;
-            const char* Kpf = nullptr;
+            int pfv[PF], pfv0[PF], pfacc = 0;
+#pragma unroll
+            for (int j = 0; j < PF; ++j) { pfv[j] = 0; pfv0[j] = 0; }
             if (do_pf) {
                 const int64_t seq_pf = inst_pf / a.blocks_per_seq;
                 const int64_t blk_pf = inst_pf - seq_pf * a.blocks_per_seq;
-                Kpf = a.K + (seq_pf * a.in_seq_stride + blk_pf * b) * G::kRowBytes + lane * 16;
-            }
-            int pfv[PF], pfacc = 0;
+                const char* Kpf = a.K + (seq_pf * a.in_seq_stride + blk_pf * b) * G::kRowBytes + lane * 16;
+                const int pf_panel = (owner ? p0 + w : p0);   // wavefront 1 covers panel 0 as well when it owns no column
+                if (owner) {
 #pragma unroll
-            for (int j = 0; j < PF; ++j) pfv[j] = 0;
-            for (int l = 0; l < nPc; ++l) {
-                const int I = p0 + l;
-                if (do_pf) {
-#pragma unroll
-                    for (int j = 0; j < PF; ++j) {
-                        pfacc ^= pfv[j];
-                        pfv[j] = *reinterpret_cast<const int*>(Kpf + (size_t)(I << 6) * G::kRowBytes + j * 1024);
-                    }
+                    for (int j = 0; j < PF; ++j) pfv[j] = *reinterpret_cast<const int*>(Kpf + (size_t)(pf_panel << 6) * G::kRowBytes + j * 1024);
                 }
-                // ------------------------------------------------ diagonal tile of panel I, stored once the walker has taken tile I-1
+                if (w == 1) {
+#pragma unroll
+                    for (int j = 0; j < PF; ++j) pfv0[j] = *reinterpret_cast<const int*>(Kpf + (size_t)(p0 << 6) * G::kRowBytes + j * 1024);
+                }
+            }
+            // diagonal tile of local panel l from the panel's fragments P (both operands), stored in turn
+            auto diagonal = [&](const Frag (&P)[G::kGroups][2], int l) {
+                const int I = p0 + l;
                 floatx16 dv[2][2];
-                Ops::template tile<false, false>(dv, nullptr, lds_rows(l << 6), lds_rows(l << 6), aterm + (I << 6), alpha, nullptr, nullptr, foff, n, h);
+                Ops::template tile<false, true, true>(dv, P, nullptr, nullptr, aterm + (I << 6), alpha, nullptr, nullptr, foff, n, h, P);
                 const float e0 = fast_exp2(aterm[(I << 6) + n] - row_const), e1 = fast_exp2(aterm[(I << 6) + 32 + n] - row_const);
                 if (EMIT_G) {
 #pragma unroll
@@ -794,28 +785,67 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                         }
                 }
                 Ops::mask_diag(dv, e0, e1, n, h);
-                await(diag_taken, l, sync_err);
+                // the tile is complete here: the compiler must not sink its arithmetic below the wait
+                asm volatile("" : "+v"(dv[0][0]), "+v"(dv[0][1]), "+v"(dv[1][0]), "+v"(dv[1][1]));
+                await(diag_taken, l, sync_err);               // the walker holds the previous tile in registers
                 Ops::store_diag(diag, dv, n, h);
                 publish(diag_ready, l + 1);
+            };
+            Frag Bq[G::kGroups][2];
+            // Start-up: the diagonal tiles of panels 0, 1, 2 come from the wavefronts whose own columns are needed last
+            // (with fewer than 8 panels, from wavefronts without a column), so that wavefront 1 can start on tile (0, 1).
+            {
+                const int l0 = kWaves - 1 - w;                // wavefront 7 -> panel 0, 6 -> 1, 5 -> 2
+                if (l0 < 3 && l0 < nPc && (w >= 3 || nPc < 4)) {
+                    Ops::load_panel(Bq, lds_rows(l0 << 6), foff, n);
+                    diagonal(Bq, l0);
+                }
+            }
+            if (owner) {
+                const int J = p0 + w;
+                Ops::load_panel(Bq, lds_rows(w << 6), foff, n);
+                const float ecol = fast_exp2(aterm[(J << 6) + lane] - row_const);
+                float sig = sigma[(J << 6) + lane];           // minus the threshold, plus what earlier chunks added
+                for (int i = 0; i < w; ++i) {
+                    const int Ii = p0 + i;
+                    floatx16 acc[2][2];
+                    Ops::template tile<false, false, true>(acc, nullptr, lds_rows(i << 6), nullptr, aterm + (Ii << 6), alpha, nullptr, nullptr, foff, n, h, Bq);
+                    if (EMIT_G) {
+                        const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
+#pragma unroll
+                        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const int row = (Ii << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+                                Gi[(size_t)row * b + (J << 6) + n] = acc[rb][0][r] * e0;
+                                Gi[(size_t)row * b + (J << 6) + 32 + n] = acc[rb][1][r] * e1;
+                                Gi[(size_t)((J << 6) + n) * b + row] = acc[rb][0][r] * e0;
+                                Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r] * e1;
+                            }
+                    }
+                    // signs of row panel i (once the walker has published them), signed column sums
+                    const bool urgent = i == w - 1;            // the walker is waiting for this one
+                    if (urgent) { __builtin_amdgcn_s_setprio(3); await<true>(eta_done, i + 1, sync_err); }
+                    else await(eta_done, i + 1, sync_err);
+                    float sg[32];
+                    Ops::signs_from_lds(sg, etaF + (i << 6) + 32 * h);
+                    sig = fmaf(Ops::signed_colsum(acc, sg, h), ecol, sig);
+                    if (urgent) {
+                        sigma[(J << 6) + lane] = sig;
+                        publish(col + w, w);
+                        __builtin_amdgcn_s_setprio(0);
+                    }
+                }
+                // This column is complete (the walk of panel w is starting): form the diagonal tile that is due two
+                // walks from now.  Wavefront 1, which has no predecessor, also supplies the tile of panel 2.
+                if (w + 2 < nPc) {
+                    Ops::load_panel(Bq, lds_rows((w + 2) << 6), foff, n);
+                    diagonal(Bq, w + 2);
+                }
             }
 #pragma unroll
-            for (int j = 0; j < PF; ++j) pfacc ^= pfv[j];
+            for (int j = 0; j < PF; ++j) pfacc ^= pfv[j] ^ pfv0[j];
             asm volatile("" :: "v"(pfacc));                   // the touches must not be optimised away
-        } else if (wave == 2) {
-            for (int l = 1; l < nPc; ++l) {
-                floatx16 held[2][2];
-                off_diag_weights(held, l - 1, l);              // weights before the walk of panel l-1 ends, signs after
-                sign_and_add(held, l - 1, l);
-            }
-        } else {
-            int t = 0;
-            for (int lj = 2; lj < nPc; ++lj)
-                for (int li = 0; li + 1 < lj; ++li, ++t) {
-                    if (t % (kWaves - 3) != wave - 3) continue;
-                    floatx16 acc[2][2];
-                    off_diag_weights(acc, li, lj);
-                    sign_and_add(acc, li, lj);
-                }
         }
         __syncthreads();                                   // the chunk is done: LDS rows, counters and tile buffer are free
     }

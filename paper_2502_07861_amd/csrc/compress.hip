@@ -823,6 +823,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                                 Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r] * e1;
                             }
                     }
+                    // the weights are complete here: the compiler must not sink their arithmetic below the wait
+                    asm volatile("" : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]));
                     // signs of row panel i (once the walker has published them), signed column sums
                     const bool urgent = i == w - 1;            // the walker is waiting for this one
                     if (urgent) { __builtin_amdgcn_s_setprio(3); await<true>(eta_done, i + 1, sync_err); }

@@ -424,6 +424,49 @@ __device__ __forceinline__ void await(int* counter, int value, int* err) {
     __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
+// The walker's hand-overs: a counter and the data it guards are requested in one batch, counter first.  LDS serves a
+// wavefront's requests in order, so data that arrives with a counter value >= the awaited one is current; this saves
+// one LDS round trip per hand-over compared to "poll, then read".
+__device__ __forceinline__ unsigned int lds_offset(const void* p) {
+    return (unsigned int)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+// the walker's column of the diagonal tile (16 x 16 bytes) once `counter` >= value
+__device__ __forceinline__ void await_and_read_tile(int* counter, int value, const float* tile_col, float (&g)[64], int* err) {
+    const unsigned int a0 = lds_offset(counter), a2 = lds_offset(tile_col);
+    floatx4 q0, q1, q2, q3, q4, q5, q6, q7, q8, q9, q10, q11, q12, q13, q14, q15;
+    bool ok = false;
+    for (int it = 0; it < kSpinLimit && !ok; ++it) {
+        int s0;
+        asm volatile("ds_read_b32 %0, %17\n\t"
+                     "ds_read_b128 %1, %18\n\tds_read_b128 %2, %18 offset:16\n\tds_read_b128 %3, %18 offset:32\n\tds_read_b128 %4, %18 offset:48\n\t"
+                     "ds_read_b128 %5, %18 offset:64\n\tds_read_b128 %6, %18 offset:80\n\tds_read_b128 %7, %18 offset:96\n\tds_read_b128 %8, %18 offset:112\n\t"
+                     "ds_read_b128 %9, %18 offset:128\n\tds_read_b128 %10, %18 offset:144\n\tds_read_b128 %11, %18 offset:160\n\tds_read_b128 %12, %18 offset:176\n\t"
+                     "ds_read_b128 %13, %18 offset:192\n\tds_read_b128 %14, %18 offset:208\n\tds_read_b128 %15, %18 offset:224\n\tds_read_b128 %16, %18 offset:240\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&v"(s0), "=&v"(q0), "=&v"(q1), "=&v"(q2), "=&v"(q3), "=&v"(q4), "=&v"(q5), "=&v"(q6), "=&v"(q7),
+                       "=&v"(q8), "=&v"(q9), "=&v"(q10), "=&v"(q11), "=&v"(q12), "=&v"(q13), "=&v"(q14), "=&v"(q15)
+                     : "v"(a0), "v"(a2) : "memory");
+        ok = __builtin_amdgcn_readfirstlane(s0) >= value;
+    }
+    if (!ok) __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    const floatx4 q[16] = {q0, q1, q2, q3, q4, q5, q6, q7, q8, q9, q10, q11, q12, q13, q14, q15};
+#pragma unroll
+    for (int t = 0; t < 16; ++t) { g[4 * t] = q[t][0]; g[4 * t + 1] = q[t][1]; g[4 * t + 2] = q[t][2]; g[4 * t + 3] = q[t][3]; }
+}
+// one float once `counter` >= value
+__device__ __forceinline__ float await_and_read(int* counter, int value, const float* data, int* err) {
+    const unsigned int ca = lds_offset(counter), da = lds_offset(data);
+    float x = 0.f;
+    for (int it = 0; it < kSpinLimit; ++it) {
+        int seen;
+        asm volatile("ds_read_b32 %0, %2\n\tds_read_b32 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&v"(seen), "=&v"(x) : "v"(ca), "v"(da) : "memory");
+        if (__builtin_amdgcn_readfirstlane(seen) >= value) return x;
+    }
+    __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return x;
+}
+
 template <typename T, int D, bool EMIT_G>
 __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a) {
     typedef Geo<T, D> G;
@@ -699,7 +742,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         // operand and forms, in row order, the tiles (i, w), i < w (weights need nothing; the signed column sum needs
         // eta_done > i and goes into a register copy of sigma); then, its column being complete just as the walk of
         // panel w starts, the diagonal tile of panel w+2, which it stores when the walker has taken the previous one
-        // (the tiles of panels 0, 1, 2 come from wavefronts 7, 6, 5 at start-up).  Every sigma receives
+        // (the tiles of panels 0 and 1 come from wavefronts 7 and 6 at start-up, that of panel 2 from wavefront 1).  Every sigma receives
         // its contributions in the same order on every run.  At most one tile per wavefront and walked panel is due,
         // so the walk (wavefront 0) only ever waits for the tile (l-1, l) that depends on its last signs.
         int* eta_done = prog;
@@ -719,17 +762,12 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 const int I = p0 + l;
                 // ------------------------------------------------ the walk over panel I (Alg. 2 lines 4-10)
                 // this lane's column of the diagonal tile: g[j] = g_{j,lane} for j < lane, else 0
-                await<true>(diag_ready, l + 1, sync_err);
+                // sigma holds (sum of signed weights so far) - (1 - 2 u): eta = +1 <=> u < 1/2 - s/2 <=> sigma < 0; it is
+                // complete when the owner of this column panel says so (col[l] == l)
                 float g[64];
-#pragma unroll
-                for (int t = 0; t < 16; ++t) {
-                    const floatx4 v = *reinterpret_cast<const floatx4*>(diag + lane * kDiagStride + 4 * t);
-                    g[4 * t] = v[0]; g[4 * t + 1] = v[1]; g[4 * t + 2] = v[2]; g[4 * t + 3] = v[3];
-                }
+                await_and_read_tile(diag_ready, l + 1, diag + lane * kDiagStride, g, sync_err);
                 publish(diag_taken, l + 1);                   // the tile is in registers: the buffer may be overwritten
-                await<true>(col + l, l, sync_err);             // sigma of this panel is complete
-                // sigma holds (sum of signed weights so far) - (1 - 2 u): eta = +1 <=> u < 1/2 - s/2 <=> sigma < 0
-                float sv = sigma[(I << 6) + lane];
+                float sv = await_and_read(col + l, l, sigma + (I << 6) + lane, sync_err);
                 walk_panel(sv, g, sign_bit);
                 const unsigned long long m = __ballot(sv < 0.f);
                 if (lane == 0) etaMask[I] = m;
@@ -792,14 +830,13 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 publish(diag_ready, l + 1);
             };
             Frag Bq[G::kGroups][2];
-            // Start-up: the diagonal tiles of panels 0, 1, 2 come from the wavefronts whose own columns are needed last
-            // (with fewer than 8 panels, from wavefronts without a column), so that wavefront 1 can start on tile (0, 1).
-            {
-                const int l0 = kWaves - 1 - w;                // wavefront 7 -> panel 0, 6 -> 1, 5 -> 2
-                if (l0 < 3 && l0 < nPc && (w >= 3 || nPc < 4)) {
-                    Ops::load_panel(Bq, lds_rows(l0 << 6), foff, n);
-                    diagonal(Bq, l0);
-                }
+            // Start-up: the diagonal tiles of panels 0 and 1 come from wavefronts 7 and 6, whose own columns (if any) are
+            // needed last, so that the other wavefronts can start on their columns at once.
+            if (w >= kWaves - 2 && kWaves - 1 - w < nPc) {
+                if (w == kWaves - 1) __builtin_amdgcn_s_setprio(2);       // the walk cannot start without the first tile
+                Ops::load_panel(Bq, lds_rows((kWaves - 1 - w) << 6), foff, n);
+                diagonal(Bq, kWaves - 1 - w);
+                __builtin_amdgcn_s_setprio(0);
             }
             if (owner) {
                 const int J = p0 + w;
@@ -840,9 +877,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 }
                 // This column is complete (the walk of panel w is starting): form the diagonal tile that is due two
                 // walks from now.  Wavefront 1, which has no predecessor, also supplies the tile of panel 2.
-                if (w + 2 < nPc) {
-                    Ops::load_panel(Bq, lds_rows((w + 2) << 6), foff, n);
-                    diagonal(Bq, w + 2);
+                for (int l = (w == 1 ? 2 : w + 2); l <= w + 2 && l < nPc; ++l) {     // wavefront 1 also supplies panel 2's
+                    Ops::load_panel(Bq, lds_rows(l << 6), foff, n);
+                    diagonal(Bq, l);
                 }
             }
 #pragma unroll

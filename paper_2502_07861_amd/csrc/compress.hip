@@ -143,7 +143,8 @@ struct TileOps {
     // (before the column factor).
     // With BREG the column panel's fragments come from the caller's registers too (Bq), e.g. a panel that a
     // wavefront keeps for all tiles of its column.
-    template <bool SUM, bool AREG, bool BREG = false>
+    // With DIAG (a diagonal tile, not dumped) the quadrant rows 32..63 x columns 0..31, which the walk never uses, is skipped.
+    template <bool SUM, bool AREG, bool BREG = false, bool DIAG = false>
     static __device__ __forceinline__ float tile(floatx16 (&acc)[2][2], const Frag (*A)[2], const char* ldsA, const char* ldsB,
                                                  const float* aterm_panel, float alpha, const float* sg, const float* sgn_h,
                                                  const int (&foff)[G::kGroups], int n, int h, const Frag (*Bq)[2] = nullptr) {
@@ -174,7 +175,7 @@ struct TileOps {
             }
         };
         auto finish = [&](int rb, int r) {
-            acc[rb][0][r] = fast_exp2(fmaf(acc[rb][0][r], alpha, at[rb][r >> 2][r & 3]));
+            if (!(DIAG && rb == 1)) acc[rb][0][r] = fast_exp2(fmaf(acc[rb][0][r], alpha, at[rb][r >> 2][r & 3]));
             acc[rb][1][r] = fast_exp2(fmaf(acc[rb][1][r], alpha, at[rb][r >> 2][r & 3]));
             if (SUM) {
                 cs0 = fmaf(sq[rb][r >> 2][r & 3], acc[rb][0][r], cs0);
@@ -228,7 +229,7 @@ struct TileOps {
         for (int g = 0; g < KG; ++g) {
             if (!kKeepB && g + kAhead < KG) load_b(g + kAhead);
             if (g >= KG - 4) load_rowterm(1, g - (KG - 4));
-            Elem<T>::mma(acc[1][0], Ah[1][g], B0[g]);
+            if (!DIAG) Elem<T>::mma(acc[1][0], Ah[1][g], B0[g]);
             finish_group(0, g * RPI, 0);                   // scale-and-shift of this k-group's share of rows 0..31 ...
             Elem<T>::mma(acc[1][1], Ah[1][g], B1[g]);
             finish_group(0, g * RPI, 1);                   // ... their exponentials ...
@@ -333,15 +334,18 @@ struct TileOps {
     }
     // Diagonal tile: apply the column factors and zero everything that is not strictly above the diagonal
     // (the walk only ever adds eta_j * g_jl for l > j) ...
+    // Quadrant by quadrant: rows 0..31 x columns 32..63 lie above the diagonal as a whole, rows 32..63 x columns
+    // 0..31 below it as a whole; only the two diagonal quadrants need the per-entry test (local row < n in both).
     static __device__ __forceinline__ void mask_diag(floatx16 (&v)[2][2], float e0, float e1, int n, int h) {
+        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-                v[rb][0][r] = (n > row) ? v[rb][0][r] * e0 : 0.f;
-                v[rb][1][r] = (32 + n > row) ? v[rb][1][r] * e1 : 0.f;
-            }
+        for (int r = 0; r < 16; ++r) {
+            const int lrow = 8 * (r >> 2) + 4 * h + (r & 3);                  // row inside its half
+            v[0][0][r] = (n > lrow) ? v[0][0][r] * e0 : 0.f;
+            v[0][1][r] = v[0][1][r] * e1;
+            v[1][1][r] = (n > lrow) ? v[1][1][r] * e1 : 0.f;
+        }
+        v[1][0] = zero;
     }
     // ... and store it transposed, diag[col * kDiagStride + row]: four consecutive rows per 16-byte store.
     static __device__ __forceinline__ void store_diag(float* diag, const floatx16 (&v)[2][2], int n, int h) {
@@ -810,7 +814,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             auto diagonal = [&](const Frag (&P)[G::kGroups][2], int l) {
                 const int I = p0 + l;
                 floatx16 dv[2][2];
-                Ops::template tile<false, true, true>(dv, P, nullptr, nullptr, aterm + (I << 6), alpha, nullptr, nullptr, foff, n, h, P);
+                Ops::template tile<false, true, true, !EMIT_G>(dv, P, nullptr, nullptr, aterm + (I << 6), alpha, nullptr, nullptr, foff, n, h, P);
                 const float e0 = fast_exp2(aterm[(I << 6) + n] - row_const), e1 = fast_exp2(aterm[(I << 6) + 32 + n] - row_const);
                 if (EMIT_G) {
 #pragma unroll

@@ -471,7 +471,9 @@ __device__ __forceinline__ float await_and_read(int* counter, int value, const f
     return x;
 }
 
-template <typename T, int D, bool EMIT_G>
+// MULTI = false: the launcher guarantees b <= chunk_rows (the block is resident in LDS as one chunk), and the
+// multi-chunk code is compiled out.
+template <typename T, int D, bool EMIT_G, bool MULTI>
 __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a) {
     typedef Geo<T, D> G;
     typedef TileOps<T, D> Ops;
@@ -497,9 +499,6 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: roles branch on scalars
     const int n = lane & 31, h = lane >> 5;
-    int foff[G::kGroups];                      // byte offset, inside an LDS row, of this lane's fragment of k-group g
-#pragma unroll
-    for (int g = 0; g < G::kGroups; ++g) foff[g] = G::slice_off(n, 2 * g + h);
     const int64_t inst = blockIdx.x;
     const int64_t seq = inst / a.blocks_per_seq;
     const int blk = (int)(inst - seq * a.blocks_per_seq);
@@ -509,7 +508,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     const int sl = tid % SL, rg = tid / SL;
     const bool center = (a.flags & BKV_CENTER_KEYS) != 0;
     const bool need_norm = !(a.rkey2 > 0.f);
-    const bool single_chunk = (CH == b);
+    const bool single_chunk = MULTI ? (CH == b) : true;
     const float alpha = a.alpha;
     float* Gi = EMIT_G ? a.G_out + (size_t)inst * b * b : nullptr;
 
@@ -553,7 +552,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
 #pragma unroll
     for (int e = 0; e < EPL; ++e) part[e] = 0.f;
 
-    const int n_chunks = (b + CH - 1) / CH;
+    const int n_chunks = MULTI ? (b + CH - 1) / CH : 1;
     // Rows [row0, row0 + rows_here) of the block -> LDS, many rows in flight per thread; the first rows_sum rows
     // from row0 (possibly more than are staged) also enter the column sums of the mean.
     auto stage_chunk = [&](int row0, int rows_here, int rows_sum) {
@@ -596,64 +595,114 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     {
         // ---------------------------------------------------------- block statistics
         // mu = mean key (fp32), a_i = <k_i, mu>, A = largest centred squared norm (or r_key^2)
-        // every thread forms its own 16-byte slice of mu and |mu|^2 (the same value in all threads)
-        float mloc[EPL];
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) mloc[e] = 0.f;
+        // Lane l of every wavefront holds columns l, 64 + l, ... of mu; |mu|^2 is the same value in all threads.
+        constexpr int MH = D / 64;
+        float mcol[MH];
         float mumu = 0.f;
-        if (center) {
-            floatx4 wp[kWaves][EPL / 4];
+        if constexpr (!MULTI) {
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w)
+            for (int hh = 0; hh < MH; ++hh) {
+                float s0 = 0.f;
+                if (center)
 #pragma unroll
-                for (int q = 0; q < EPL / 4; ++q)
-                    wp[w][q] = *reinterpret_cast<const floatx4*>(wpart + w * D + sl * EPL + 4 * q);
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w)
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) mloc[e] += wp[w][e >> 2][e & 3];
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                mloc[e] *= 1.f / (float)b;
-                mumu = fmaf(mloc[e], mloc[e], mumu);
+                    for (int w = 0; w < kWaves; ++w) s0 += wpart[w * D + 64 * hh + lane];
+                mcol[hh] = s0 * (1.f / (float)b);
+                mumu = fmaf(mcol[hh], mcol[hh], mumu);
             }
-            mumu = group_sum<SL>(mumu);
+            mumu = wave_sum(mumu);
         }
+        // general path: every thread forms its own 16-byte slice of mu
+        float mloc[MULTI ? EPL : 1];
+        if constexpr (MULTI) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) mloc[e] = 0.f;
+            if (center) {
+                floatx4 wp[kWaves][EPL / 4];
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+                    for (int q = 0; q < EPL / 4; ++q)
+                        wp[w][q] = *reinterpret_cast<const floatx4*>(wpart + w * D + sl * EPL + 4 * q);
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) mloc[e] += wp[w][e >> 2][e & 3];
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) {
+                    mloc[e] *= 1.f / (float)b;
+                    mumu = fmaf(mloc[e], mloc[e], mumu);
+                }
+                mumu = group_sum<SL>(mumu);
+            }
+        }
+        // Resident blocks take one row per thread (at most kThreads rows are ever resident); the general path
+        // streams every row as 16-byte slices.
+        const int nres = MULTI ? 0 : b;
+        const bool has_row = tid < nres;
+        float pa_row = 0.f;
         if (center || need_norm) {
             float amax = -3.0e38f;
-            constexpr int U = 8;
-            for (int ib0 = 0; ib0 < b; ib0 += RG * U) {        // b is a multiple of 64 and of RG; whole row groups are skipped past b
-                uintx4 raw[U];
+            // One row per thread: mu comes through scalar registers, 32 columns at a time, so the dot products need
+            // no cross-lane step; |k|^2 from exact bf16 products (v_dot2c_f32_bf16).
+            if constexpr (!MULTI) {
+                constexpr int MC = 16;                          // columns of mu held in scalar registers at a time
+                constexpr int SLQ = MC * (int)sizeof(T) / 16;   // 16-byte slices per MC columns
+                float pn = 0.f;
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int ib = ib0 + u * RG;                // first row of this group: the same in every thread
-                    const int i = min(ib + rg, b - 1);
-                    if (ib < CH) raw[u] = *reinterpret_cast<const uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, sl));
-                    else raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
+                for (int qc = 0; qc < D / MC; ++qc) {
+                    float sm[MC];
+#pragma unroll
+                    for (int jj = 0; jj < MC; ++jj) sm[jj] = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(mcol[(qc * MC) >> 6]), ((qc * MC) & 63) + jj));
+                    if (has_row) {
+#pragma unroll
+                        for (int ss = 0; ss < SLQ; ++ss) {
+                            const uintx4 raw = *reinterpret_cast<const uintx4*>(ldsK + (size_t)tid * G::kLdsRow + G::slice_off(tid, qc * SLQ + ss));
+                            float f[EPL];
+                            Elem<T>::unpack(raw, f);
+#pragma unroll
+                            for (int e = 0; e < EPL; ++e) pa_row = fmaf(f[e], sm[ss * EPL + e], pa_row);
+                            pn += Elem<T>::dot(raw, raw);
+                        }
+                    }
                 }
+                if (has_row) amax = pn - 2.f * pa_row + mumu;
+            }
+            if constexpr (MULTI) {
+                // a 16-byte slice per thread, rows of the first chunk from LDS, the others from global memory; DPP sums per row
+                constexpr int U = 8;
+                for (int ib0 = 0; ib0 < b; ib0 += RG * U) {     // b and CH are multiples of 64 and of RG; whole row groups are skipped past b
+                    uintx4 raw[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int i = ib0 + u * RG + rg;
-                    float f[EPL];
-                    Elem<T>::unpack(raw[u], f);
-                    float pa = 0.f;
+                    for (int u = 0; u < U; ++u) {
+                        const int ib = ib0 + u * RG;            // first row of this group: the same in every thread
+                        const int i = min(ib + rg, b - 1);
+                        if (ib < CH) raw[u] = *reinterpret_cast<const uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, sl));
+                        else raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
+                    }
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) pa = fmaf(f[e], mloc[e], pa);
-                    float pn = Elem<T>::dot(raw[u], raw[u]);          // exact products, fp32 accumulation
-                    pa = group_sum<SL>(pa);
-                    pn = group_sum<SL>(pn);
-                    if (i < b) {
-                        if (sl == 0) aterm[i] = -alpha * pa;
-                        amax = fmaxf(amax, pn - 2.f * pa + mumu);
+                    for (int u = 0; u < U; ++u) {
+                        const int i = ib0 + u * RG + rg;
+                        float f[EPL];
+                        Elem<T>::unpack(raw[u], f);
+                        float pa = 0.f;
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) pa = fmaf(f[e], mloc[e], pa);
+                        float pn = Elem<T>::dot(raw[u], raw[u]);
+                        pa = group_sum<SL>(pa);
+                        pn = group_sum<SL>(pn);
+                        if (i < b) {
+                            if (sl == 0) aterm[i] = -alpha * pa;
+                            amax = fmaxf(amax, pn - 2.f * pa + mumu);
+                        }
                     }
                 }
             }
             amax = wave_max(amax);
             if (lane == 0) scal[2 + wave] = amax;
         } else {
-            for (int i = tid; i < b; i += kThreads) aterm[i] = 0.f;
+            for (int i = nres + tid; i < b; i += kThreads) aterm[i] = 0.f;
         }
-        __syncthreads();                                        // mu / wpart (aliasing diag) are dead from here
+        __syncthreads();                                        // wpart (aliasing diag) is dead from here
         {
             float A = a.rkey2;
             if (need_norm) {
@@ -662,11 +711,17 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 for (int w = 1; w < kWaves; ++w) A = fmaxf(A, scal[2 + w]);
             }
             const float rc = alpha * (mumu - A + a.cterm);       // row constant of the exponent
-            for (int i = tid; i < b; i += kThreads) aterm[i] += rc;
+            if (has_row) aterm[tid] = fmaf(-alpha, pa_row, rc);
+            for (int i = nres + tid; i < b; i += kThreads) aterm[i] += rc;
             if (tid == 0) scal[1] = rc;
+            if (tid < 32) prog[tid] = 0;                        // progress counters of the first chunk's pipeline
         }
         __syncthreads();
     }
+
+    int foff[G::kGroups];                      // byte offset, inside an LDS row, of this lane's fragment of k-group g
+#pragma unroll
+    for (int g = 0; g < G::kGroups; ++g) foff[g] = G::slice_off(n, 2 * g + h);
 
     for (int c = 0; c < n_chunks; ++c) {
         const int row0 = c * CH;                       // first row of the chunk
@@ -675,6 +730,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         if (c > 0) {
             __syncthreads();                           // previous users of ldsK are done
             stage_chunk(row0, rows_here, 0);
+            if (tid < 32 && tid != 3) prog[tid] = 0;   // progress counters of this chunk's pipeline (the error flag is sticky)
             __syncthreads();
         }
         const float row_const = scal[1];
@@ -754,9 +810,6 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         int* diag_taken = prog + 2;
         int* sync_err = prog + 3;
         int* col = prog + 8;
-        if (tid < 32 && tid != 3) prog[tid] = 0;
-        if (c == 0 && tid == 3) prog[3] = 0;
-        __syncthreads();
         const int nPc = p1 - p0;
         if (wave == 0) {
             unsigned int sign_bit = 0x80000000u;
@@ -1040,10 +1093,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
 }
 
 // ------------------------------------------------------------------------------------------------
-template <typename T, int D, bool EMIT_G>
+template <typename T, int D, bool EMIT_G, bool MULTI>
 static hipError_t launch_one(const CompressArgs& a, int64_t n_inst, hipStream_t st) {
     const size_t lds = compress_lds_bytes(Geo<T, D>::kRowBytes, a.b);
-    auto kern = compress_kernel<T, D, EMIT_G>;
+    auto kern = compress_kernel<T, D, EMIT_G, MULTI>;
     static thread_local size_t configured = 0;
     if (lds > configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1081,8 +1134,11 @@ hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64
     // grids are one-dimensional; split very large launches
     const int64_t kMaxGrid = 1ll << 30;
     if (n_inst > kMaxGrid) return hipErrorInvalidValue;
-#define BKV_DISPATCH(TT, DD)                                                  \
-    return emit_g ? launch_one<TT, DD, true>(a, n_inst, st) : launch_one<TT, DD, false>(a, n_inst, st)
+    const bool multi = a.b > a.chunk_rows;       // the Gram-emitting (test) variant always takes the general code
+#define BKV_DISPATCH(TT, DD)                                                                \
+    return emit_g ? launch_one<TT, DD, true, true>(a, n_inst, st)                           \
+                  : multi ? launch_one<TT, DD, false, true>(a, n_inst, st)                  \
+                          : launch_one<TT, DD, false, false>(a, n_inst, st)
     if (dtype == BKV_BF16 && d == 128) { BKV_DISPATCH(__bf16, 128); }
     if (dtype == BKV_BF16 && d == 64) { BKV_DISPATCH(__bf16, 64); }
     if (dtype == BKV_F32 && d == 128) { BKV_DISPATCH(float, 128); }

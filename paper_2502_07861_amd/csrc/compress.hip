@@ -6,18 +6,20 @@
 // of token l and accumulates sum_{i signed so far} eta_i g_il.  Wavefront 0 is the walker: for panel I it holds the
 // strictly-upper part of the 64x64 diagonal tile of kernel weights as "one column per lane" registers and takes the 64
 // sequential decisions of Alg. 2 (lane j tests the sign of its sigma; bit j of the compare mask becomes the +-1 that
-// every later lane multiplies g_jl with).  Wavefronts 1..7 form tiles on MFMA while the walker walks, in a static
-// schedule:
+// every later lane multiplies g_jl with).  Wavefronts 1..7 form tiles on MFMA while the walker walks.  There are no
+// workgroup barriers inside the pipeline: the wavefronts hand data over through progress counters in LDS.
 //
-//   superstep I:   walker            walk(I)
-//                  wave 1            diagonal tile of panel I+1 (stored to LDS between the two barriers)
-//                  wave 2            tile (I, I+1) without signs, kept in registers
-//                  waves 3..7        tiles (I-1, J), J > I: weights, times eta of row panel I-1, summed over rows,
-//                                    added into sigma[J]                              (eta_{I-1} is known)
-//                  barrier; wave 2 applies eta_I to its tile -> sigma[I+1]; barrier
+//   walker, panel I     take diagonal tile D(I) (registers), mark the buffer free, wait until column I is complete,
+//                       take sigma of the panel, walk 64 steps, publish the signs of panel I
+//   wave w = 1..7       owns column panel w (its keys stay in registers as the B operand): tiles (i, w), i = 0..w-1, in
+//                       row order: weights first, then wait for the signs of panel i, signed column sum in a register;
+//                       after tile (w-1, w) the sum goes into sigma[panel w] and column w is published.  Then the
+//                       diagonal tile of panel w+2 (start-up tiles come from the wavefronts whose columns are due last),
+//                       stored once the walker has taken the previous one.
 //
-// so the only work between two walks is one signed column sum.  Rows of earlier chunks (b larger than one chunk)
-// come back from global memory (L2) as the A operand against the resident chunk before its own panels are walked.
+// so the only work between two walks is one signed column sum and two hand-overs.  Rows of earlier chunks (b larger
+// than one chunk) come back from global memory (L2) as the A operand against the resident chunk before its own panels
+// are walked.
 //
 // Kernel weight: g_ij = exp((<k_i,k_j> - a_i - a_j + |mu|^2 - A)/sqrt(d) - ln c), a_i = <k_i,mu>
 // (mu = block mean when keys are centred, else 0), A = r_key^2 or the largest centred squared norm:
@@ -642,7 +644,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         float pa_row = 0.f;
         if (center || need_norm) {
             float amax = -3.0e38f;
-            // One row per thread: mu comes through scalar registers, 32 columns at a time, so the dot products need
+            // One row per thread: mu comes through scalar registers, MC columns at a time, so the dot products need
             // no cross-lane step; |k|^2 from exact bf16 products (v_dot2c_f32_bf16).
             if constexpr (!MULTI) {
                 constexpr int MC = 16;                          // columns of mu held in scalar registers at a time

@@ -246,16 +246,11 @@ size_t attend_workspace_bytes(int d, int64_t n_seq, int n_q) {
 
 template <typename T, int D>
 static hipError_t launch_attend_t(AttendArgs& a, int64_t n_seq, int n_qg, hipStream_t st) {
-    hipError_t e;
-    {
-        ProfScope prof(kProfAttend, n_seq * a.count, st);
-        hipLaunchKernelGGL((attend_partial_kernel<T, D>), dim3(a.n_splits, n_qg, (unsigned)n_seq), dim3(kAttWaves * 64), 0, st, a);
-        e = hipGetLastError();
-    }
+    const hipError_t e = launch_timed(kProfAttend, n_seq * a.count, attend_partial_kernel<T, D>, dim3(a.n_splits, n_qg, (unsigned)n_seq),
+                                      dim3(kAttWaves * 64), 0, st, a);
     if (e != hipSuccess) return e;
-    ProfScope prof(kProfAttendMerge, n_seq * a.n_q, st);
-    hipLaunchKernelGGL((attend_merge_kernel<T, D>), dim3(a.n_q, (unsigned)n_seq), dim3(kMergeThreads), 0, st, a, n_qg);
-    return hipGetLastError();
+    return launch_timed(kProfAttendMerge, n_seq * a.n_q, attend_merge_kernel<T, D>, dim3(a.n_q, (unsigned)n_seq), dim3(kMergeThreads), 0, st,
+                        a, n_qg);
 }
 
 hipError_t launch_attend(int dtype, int d, AttendArgs& a, int64_t n_seq, void* workspace, hipStream_t st) {

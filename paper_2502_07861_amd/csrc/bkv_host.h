@@ -1,6 +1,7 @@
 // Host-side declarations shared by the translation units of libbalancekv (not part of the ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/balancekv.h"
@@ -62,12 +63,18 @@ hipError_t launch_fill_w(float* w, int64_t n_seq, int64_t seq_stride, int64_t of
 enum { kProfCompress = 0, kProfGather = 1, kProfAttend = 2, kProfAttendMerge = 3 };
 int prof_enable(int n);
 int prof_read(int32_t* kind, float* ms, int64_t* units, int cap);
-struct ProfScope {
-    ProfScope(int kind, int64_t units, hipStream_t st);
-    ~ProfScope();
-    int slot_;
-    hipStream_t st_;
-};
+// Reserves a timing record and hands out its two events (false: timing is off or the records are used up).  The
+// caller passes them to hipExtLaunchKernelGGL, so that they carry the start and end of that kernel itself rather
+// than of a stretch of the stream around it.
+bool prof_slot(int kind, int64_t units, hipEvent_t* start, hipEvent_t* stop);
+// launch `kern`, timed when a record is available
+template <typename Kern, typename... Args>
+inline hipError_t launch_timed(int kind, int64_t units, Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args) {
+    hipEvent_t e0, e1;
+    if (prof_slot(kind, units, &e0, &e1)) hipExtLaunchKernelGGL(kern, grid, block, (uint32_t)lds, st, e0, e1, 0, args...);
+    else hipLaunchKernelGGL(kern, grid, block, lds, st, args...);
+    return hipGetLastError();
+}
 
 struct AttendArgs {
     const char* K;            // [n_seq, stride_tokens, d]

@@ -1106,9 +1106,7 @@ static hipError_t launch_one(const CompressArgs& a, int64_t n_inst, hipStream_t 
         if (e != hipSuccess) return e;
         configured = lds;
     }
-    ProfScope prof(kProfCompress, n_inst * a.b, st);
-    hipLaunchKernelGGL(kern, dim3((unsigned)n_inst), dim3(kThreads), lds, st, a);
-    return hipGetLastError();
+    return launch_timed(kProfCompress, n_inst * a.b, kern, dim3((unsigned)n_inst), dim3(kThreads), lds, st, a);
 }
 
 hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64_t n_inst, hipStream_t st) {
@@ -1173,10 +1171,8 @@ hipError_t launch_gather_rows(const void* in, const int32_t* idx, void* out, int
     if (total <= 0) return hipSuccess;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
-    ProfScope prof(kProfGather, n_seq * rows_out, st);
-    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const char*)in, idx,
-                       (char*)out, in_seq_stride, out_seq_stride, rows_out, row_bytes, total);
-    return hipGetLastError();
+    return launch_timed(kProfGather, n_seq * rows_out, gather_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                        (const char*)in, idx, (char*)out, in_seq_stride, out_seq_stride, rows_out, row_bytes, total);
 }
 
 // Fill / copy helpers (plain kernels: safe under graph capture, unlike memset nodes).
@@ -1280,8 +1276,8 @@ hipError_t launch_fill_w(float* w, int64_t n_seq, int64_t seq_stride, int64_t of
 }
 
 // ------------------------------------------------------------------------------------------------
-// Opt-in per-launch timing (diagnostics): HIP events recorded around kernel launches on the
-// caller's stream.  Disabled unless bkv_profile_enable(n > 0) was called.
+// Opt-in per-launch timing (diagnostics): HIP events attached to the kernel launches themselves
+// (start and end of the dispatch).  Disabled unless bkv_profile_enable(n > 0) was called.
 // ------------------------------------------------------------------------------------------------
 namespace {
 struct ProfRec { hipEvent_t a, b; int kind; int64_t units; };
@@ -1312,15 +1308,12 @@ int prof_read(int32_t* kind, float* ms, int64_t* units, int cap) {
     g_prof_n = 0;
     return n;
 }
-ProfScope::ProfScope(int kind, int64_t units, hipStream_t st) : slot_(-1), st_(st) {
-    if (g_prof_n < g_prof_cap) {
-        slot_ = g_prof_n++;
-        g_prof[slot_].kind = kind; g_prof[slot_].units = units;
-        (void)hipEventRecord(g_prof[slot_].a, st_);
-    }
-}
-ProfScope::~ProfScope() {
-    if (slot_ >= 0) (void)hipEventRecord(g_prof[slot_].b, st_);
+bool prof_slot(int kind, int64_t units, hipEvent_t* start, hipEvent_t* stop) {
+    if (g_prof_n >= g_prof_cap) return false;
+    ProfRec& r = g_prof[g_prof_n++];
+    r.kind = kind; r.units = units;
+    *start = r.a; *stop = r.b;
+    return true;
 }
 
 }  // namespace bkv

@@ -133,18 +133,27 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    binding.profile_enable(args.steps * (T + 4))
+    # the timed region: exactly K steps, nothing else on the stream
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # The same K steps once more, now with start/stop events attached to every launch (per-kernel durations for the
+    # roofline figures).  Kept out of the region above because the events slow a stream of 30-microsecond kernels by
+    # about a third; the kernels themselves run as before.
+    binding.profile_enable(args.steps * (T + 4))
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt_events = time.perf_counter() - t1
     recs = binding.profile_read(args.steps * (T + 4))
     binding.profile_enable(0)
 
     ms_per_step = dt / args.steps * 1e3
     tokens = n_seq * n
-    # per-kernel figures from the events recorded inside the timed region
+    # per-kernel figures from the events of the second pass
     comp = [r for r in recs if r[0] == 0]
     att = [r for r in recs if r[0] == 2]
     comp_ms = sum(r[1] for r in comp) / max(len(comp), 1)                    # average launch of the halving kernel
@@ -163,6 +172,7 @@ def main():
         "value": tokens / (dt / args.steps),
         "unit": "token-heads/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_with_launch_events": dt_events / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if elem == 2 else "f32", "data": "synthetic",
         "config": {"workload": "%s: %d KV sequences x %d tokens, d=%d, block %d, %d halving rounds (%dx), then 1 "

@@ -71,6 +71,29 @@ def merge_reduce_offline(K, V, *, b, T, seed=0, seq=0, log_c=0.0, r_key=0.0, r_v
     return dict(idx=idx, w=np.full(idx.shape[0], float(2 ** T)), rounds=rounds)
 
 
+def merge_reduce_protected(K, V, *, b, T, n_sink, n_recent, seed=0, seq=0, log_c=0.0, r_key=0.0, r_value=0.0,
+                           center=False, value_gram=False, strict=True):
+    """The cache of the paper's single-layer experiments (Full Experimental Details, ablation on single-layer
+    attention approximation): the first ``n_sink`` and the last ``n_recent`` tokens of the sequence are kept as they
+    are (weight 1) and BalanceKV runs on the rows in between only.
+
+    The rows in between are a sequence of their own for the halving tree: block ``blk`` of round ``r`` draws
+    uniform(seed, 64*seq + r, blk*b + j), counted from the first row after the sink.  Returns dict(idx = kept
+    original indices, ascending; w = 1 for the protected tokens and 2^T for the survivors; mid = the tree's result).
+    """
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    n = K.shape[0]
+    if n_sink < 0 or n_recent < 0 or n_sink + n_recent > n:
+        raise ValueError("protected windows do not fit the sequence")
+    lo, hi = n_sink, n - n_recent
+    mid = merge_reduce_offline(K[lo:hi], V[lo:hi], b=b, T=T, seed=seed, seq=seq, log_c=log_c, r_key=r_key,
+                               r_value=r_value, center=center, value_gram=value_gram, strict=strict)
+    idx = np.concatenate([np.arange(0, lo, dtype=np.int64), lo + mid["idx"], np.arange(hi, n, dtype=np.int64)])
+    w = np.concatenate([np.ones(lo), mid["w"], np.ones(n - hi)])
+    return dict(idx=idx, w=w, mid=mid)
+
+
 class MergeAndReduceStream:
     """Alg. 3 for one sequence: feed (k_j, v_j) one at a time, read C^0..C^T.
 

@@ -369,6 +369,37 @@ def test_stream_equals_offline_tree(oracle):
     np.testing.assert_allclose(st.estimate(q), oracle.attend(q, K[off["idx"]], V[off["idx"]], off["w"])[0])
 
 
+def test_protected_windows(oracle):
+    """Full Experimental Details (single-layer experiments): first and recent tokens kept exactly, BalanceKV on the
+    rows in between.  Pinned by what the construction fixes: index sets, total weight n, the tree on the middle taken
+    as a sequence of its own, and the two limits (nothing protected / everything protected)."""
+    from oracle.merge_reduce import merge_reduce_offline, merge_reduce_protected
+    r = _rng(77)
+    n, d, b, T, sink, recent = 24 + 64 + 40, 8, 16, 2, 24, 40
+    K, V, q = r.normal(size=(n, d)), r.normal(size=(n, 3)), r.normal(size=d)
+    res = merge_reduce_protected(K, V, b=b, T=T, n_sink=sink, n_recent=recent, seed=5, seq=2, log_c=0.3, center=True)
+    idx, w = res["idx"], res["w"]
+    assert idx.shape[0] == sink + (64 >> T) + recent and np.all(np.diff(idx) > 0)
+    np.testing.assert_array_equal(idx[:sink], np.arange(sink))
+    np.testing.assert_array_equal(idx[-recent:], np.arange(n - recent, n))
+    mid_idx = idx[sink:-recent]
+    assert np.all((mid_idx >= sink) & (mid_idx < n - recent))
+    assert np.all(w[:sink] == 1.0) and np.all(w[-recent:] == 1.0) and np.all(w[sink:-recent] == 2.0 ** T)
+    assert w.sum() == n                                    # every original token is represented once in total weight
+    # the middle is the plain tree run on a copy of those rows (draws counted from the first row after the sink)
+    alone = merge_reduce_offline(K[sink:n - recent].copy(), V[sink:n - recent].copy(), b=b, T=T, seed=5, seq=2, log_c=0.3, center=True)
+    np.testing.assert_array_equal(mid_idx - sink, alone["idx"])
+    # nothing protected: the plain tree; everything protected: the estimator over the kept set is exact attention
+    plain = merge_reduce_protected(K[:64], V[:64], b=b, T=T, n_sink=0, n_recent=0, seed=5, seq=2, log_c=0.3, center=True)
+    np.testing.assert_array_equal(plain["idx"], merge_reduce_offline(K[:64], V[:64], b=b, T=T, seed=5, seq=2, log_c=0.3, center=True)["idx"])
+    full = merge_reduce_protected(K, V, b=b, T=T, n_sink=70, n_recent=n - 70, seed=5)
+    np.testing.assert_array_equal(full["idx"], np.arange(n))
+    e = np.exp(K @ q / math.sqrt(d))
+    np.testing.assert_allclose(oracle.attend(q, K[full["idx"]], V[full["idx"]], full["w"])[0], (e / e.sum()) @ V, rtol=0, atol=1e-12)
+    with pytest.raises(ValueError):
+        merge_reduce_protected(K, V, b=b, T=T, n_sink=n, n_recent=1)
+
+
 def test_zero_padding_never_keeps_padded_rows(oracle):
     """App. B (Implementation Detail): if b does not divide n the block is padded with zeros."""
     from oracle.merge_reduce import merge_reduce_offline

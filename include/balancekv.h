@@ -131,6 +131,24 @@ int bkv_merge_reduce(const bkv_params* p, const void* K, const void* V, int64_t 
                      int8_t* signs_out, int32_t* status_out,
                      void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* ---- Alg. 3 offline with protected windows (Full Experimental Details, single-layer attention
+ * approximation: the first and the most recent tokens are kept as they are, BalanceKV runs on the
+ * rows in between) --------------------------------------------------------------------------------
+ * K, V          [n_seq, n, d] device.  The first n_sink and the last n_recent tokens of every
+ *               sequence are copied (weight 1); the n - n_sink - n_recent tokens in between, which
+ *               must be a multiple of block * 2^T, go through bkv_merge_reduce's tree as a sequence
+ *               of their own (blocks and uniform draws counted from the first row after the sink).
+ * Outputs hold count = n_sink + ((n - n_sink - n_recent) >> T) + n_recent tokens per sequence, in
+ * ascending original order: K_out, V_out [n_seq, count, d]; w_out [n_seq, count] (1 | 2^T | 1) or
+ * NULL; idx_out [n_seq, count] int32 original token index or NULL; status_out as bkv_merge_reduce.
+ * workspace     bkv_merge_reduce_workspace_bytes(p, n_seq, n - n_sink - n_recent) bytes.
+ * Errors as bkv_merge_reduce; BKV_EINVAL if the windows do not fit the sequence.                  */
+int bkv_merge_reduce_protected(const bkv_params* p, const void* K, const void* V, int64_t n_seq,
+                               int64_t n, int64_t n_sink, int64_t n_recent, int64_t seq_base,
+                               void* K_out, void* V_out, float* w_out, int32_t* idx_out,
+                               int32_t* status_out, void* workspace, size_t ws_bytes,
+                               void* hip_stream);
+
 /* ---- Alg. 1 output line on a flat weighted cache -------------------------------------------------
  * K_c, V_c      [n_seq, stride_tokens, d] device; only the first `count` tokens of each sequence
  *               are read.  w [n_seq, stride_tokens] fp32 (2^level; w == 0 marks an absent token).

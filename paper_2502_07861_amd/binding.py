@@ -48,6 +48,7 @@ _SIGNATURES = {
     "bkv_kernel_weights": (C.c_int, [_PP, _vp, _i64, _vp, _vp]),
     "bkv_merge_reduce_workspace_bytes": (_sz, [_PP, _i64, _i64]),
     "bkv_merge_reduce": (C.c_int, [_PP, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bkv_merge_reduce_protected": (C.c_int, [_PP, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bkv_attend_workspace_bytes": (_sz, [_PP, _i64, _i64, _i32, _i32]),
     "bkv_attend_kv": (C.c_int, [_PP, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
     "bkv_cache_bytes": (_sz, [_PP, _i64, _i64]),
@@ -188,6 +189,27 @@ def merge_reduce(p, K, V, *, seq_base=0, emit_signs=False, workspace=None, out=N
         res["signs"] = [signs_flat[n_seq * (2 * n - ((2 * n) >> r)): n_seq * (2 * n - ((2 * n) >> (r + 1)))]
                         .view(n_seq, n >> r) for r in range(T)]
     return res
+
+
+def merge_reduce_protected(p, K, V, n_sink, n_recent, *, seq_base=0, workspace=None):
+    """bkv_merge_reduce_protected on K, V [n_seq, n, d]. Returns dict(K, V, w, idx, status)."""
+    dt = _torch_dtype(p)
+    n_seq, n, d = K.shape
+    T = p.rounds
+    dev = K.device
+    n_mid = n - n_sink - n_recent
+    count = n_sink + (max(n_mid, 0) >> T) + n_recent
+    out = dict(K=torch.empty(n_seq, count, d, device=dev, dtype=dt), V=torch.empty(n_seq, count, d, device=dev, dtype=dt),
+               w=torch.empty(n_seq, count, device=dev, dtype=torch.float32),
+               idx=torch.empty(n_seq, count, device=dev, dtype=torch.int32),
+               status=torch.zeros(n_seq, max(T, 1), device=dev, dtype=torch.int32))
+    if workspace is None:
+        workspace = torch.empty(max(merge_reduce_workspace_bytes(p, n_seq, max(n_mid, 0)), 256), device=dev, dtype=torch.uint8)
+    rc = lib().bkv_merge_reduce_protected(C.byref(p), _ptr(K, dt, "K"), _ptr(V, dt, "V"), n_seq, n, n_sink, n_recent, seq_base,
+                                          _ptr(out["K"]), _ptr(out["V"]), _ptr(out["w"]), _ptr(out["idx"]),
+                                          _ptr(out["status"]) if T > 0 else None, _ptr(workspace), workspace.numel(), _stream())
+    _check(rc, "bkv_merge_reduce_protected")
+    return out
 
 
 # ------------------------------------------------------------------------------------------ estimator

@@ -146,10 +146,17 @@ size_t bkv_merge_reduce_workspace_bytes(const bkv_params* p, int64_t n_seq, int6
 
 // T rounds; the last round writes K_out / V_out / w_out with `out_stride` tokens between sequences
 // (idx_out, if given, is always dense [n_seq, n >> T]).
+// The n tokens halved may be a window of longer sequences: K points at the window's first row, rows of consecutive
+// sequences are k_stride tokens apart (0: n); V points at token 0 of the first sequence, v_stride tokens apart (0: n),
+// and the window starts at token idx_base; idx_out rows are idx_out_stride apart (0: n >> T).
+struct TreeWindow { int64_t k_stride, v_stride, idx_base, idx_out_stride; };
 static int merge_reduce_impl(const bkv_params* p, const void* K, const void* V, int64_t n_seq, int64_t n,
                              int64_t seq_base, void* K_out, void* V_out, float* w_out, int64_t out_stride,
                              int32_t* idx_out, int8_t* signs_out, int32_t* status_out, void* workspace,
-                             size_t ws_bytes, void* hip_stream) {
+                             size_t ws_bytes, void* hip_stream, const TreeWindow* win = nullptr) {
+    const int64_t k_stride = win && win->k_stride ? win->k_stride : n;
+    const int64_t v_stride = win && win->v_stride ? win->v_stride : n;
+    const int64_t idx_base = win ? win->idx_base : 0;
     int rc = check_params(p);
     if (rc) return rc;
     if (n_seq < 0 || n < 0 || seq_base < 0) return BKV_EINVAL;
@@ -164,8 +171,9 @@ static int merge_reduce_impl(const bkv_params* p, const void* K, const void* V, 
     hipError_t e;
     if (T == 0) {   // nothing to halve: weights 1
         if (idx_out) return BKV_ESHAPE;   // identity indices are not materialised
-        if ((e = bkv::launch_copy_rows(K, K_out, n_seq, n, out_stride, n, (int)rb, st)) != hipSuccess) return hip_fail(e);
-        if ((e = bkv::launch_copy_rows(V, V_out, n_seq, n, out_stride, n, (int)rb, st)) != hipSuccess) return hip_fail(e);
+        const char* Vwin = (const char*)V + (size_t)idx_base * rb;
+        if ((e = bkv::launch_copy_rows(K, K_out, n_seq, k_stride, out_stride, n, (int)rb, st)) != hipSuccess) return hip_fail(e);
+        if ((e = bkv::launch_copy_rows(Vwin, V_out, n_seq, v_stride, out_stride, n, (int)rb, st)) != hipSuccess) return hip_fail(e);
         if (w_out && (e = bkv::launch_fill_w(w_out, n_seq, out_stride, 0, n, 1.f, st)) != hipSuccess) return hip_fail(e);
         return BKV_OK;
     }
@@ -201,13 +209,15 @@ static int merge_reduce_impl(const bkv_params* p, const void* K, const void* V, 
         a.K_out = last ? (char*)K_out : kbuf[r & 1];
         a.V = last ? (const char*)V : nullptr;          // values are gathered once, from the original rows
         a.V_out = last ? (char*)V_out : nullptr;
-        a.v_seq_stride = n;
+        a.v_seq_stride = v_stride;
+        a.idx_base = idx_base;
         a.w_out = last ? w_out : nullptr;
         a.idx_in = i_in;
         a.idx_out = last ? idx_final : ibuf[r & 1];
         a.signs_out = signs_out ? signs_out + (size_t)n_seq * (size_t)(2 * n - ((2 * n) >> r)) : nullptr;
         a.status_out = status_out; a.status_stride = T;
-        a.in_seq_stride = m; a.out_seq_stride = last ? out_stride : m / 2; a.idx_out_seq_stride = m / 2;
+        a.in_seq_stride = r == 0 ? k_stride : m; a.out_seq_stride = last ? out_stride : m / 2;
+        a.idx_out_seq_stride = (last && idx_out && win && win->idx_out_stride) ? win->idx_out_stride : m / 2;
         a.blocks_per_seq = (int32_t)(m / b);
         a.tree_mode = 1; a.round = r; a.seq_base = seq_base; a.blk_base = 0;
         a.w_out_val = (float)(1u << (r + 1));
@@ -226,6 +236,46 @@ int bkv_merge_reduce(const bkv_params* p, const void* K, const void* V, int64_t 
     if (!p) return BKV_EINVAL;
     return merge_reduce_impl(p, K, V, n_seq, n, seq_base, K_out, V_out, w_out, n >> (p->rounds & 31), idx_out,
                              signs_out, status_out, workspace, ws_bytes, hip_stream);
+}
+
+int bkv_merge_reduce_protected(const bkv_params* p, const void* K, const void* V, int64_t n_seq, int64_t n,
+                               int64_t n_sink, int64_t n_recent, int64_t seq_base, void* K_out, void* V_out, float* w_out,
+                               int32_t* idx_out, int32_t* status_out, void* workspace, size_t ws_bytes, void* hip_stream) {
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (n_seq < 0 || n < 0 || n_sink < 0 || n_recent < 0 || n_sink + n_recent > n || seq_base < 0) return BKV_EINVAL;
+    const int T = p->rounds;
+    const int64_t n_mid = n - n_sink - n_recent;
+    if (n_mid % ((int64_t)p->block << T) != 0 || n > (1ll << 31) - 1) return BKV_ESHAPE;
+    if (n_seq == 0 || n == 0) return BKV_OK;
+    if (!K || !V || !K_out || !V_out || !aligned16(K) || !aligned16(V) || !aligned16(K_out) || !aligned16(V_out)) return BKV_EINVAL;
+    const int64_t kept_mid = n_mid >> T, count = n_sink + kept_mid + n_recent;
+    if (n_mid > 0 && (T > 1 || (T == 1 && !idx_out))) {      // what the tree will ask for, before anything is launched
+        const size_t need = bkv_merge_reduce_workspace_bytes(p, n_seq, n_mid);
+        if (!workspace || ws_bytes < need || !aligned16(workspace)) return BKV_EWORKSPACE;
+    }
+    const size_t rb = (size_t)row_bytes(p);
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipError_t e;
+    // the two windows: copies of the original rows, weight 1, their own indices
+    const int64_t from[2] = {0, n - n_recent}, to[2] = {0, count - n_recent}, rows[2] = {n_sink, n_recent};
+    for (int k = 0; k < 2; ++k) {
+        const char* Ks = (const char*)K + (size_t)from[k] * rb;
+        const char* Vs = (const char*)V + (size_t)from[k] * rb;
+        if ((e = bkv::launch_copy_rows(Ks, (char*)K_out + (size_t)to[k] * rb, n_seq, n, count, rows[k], (int)rb, st)) != hipSuccess) return hip_fail(e);
+        if ((e = bkv::launch_copy_rows(Vs, (char*)V_out + (size_t)to[k] * rb, n_seq, n, count, rows[k], (int)rb, st)) != hipSuccess) return hip_fail(e);
+        if (w_out && (e = bkv::launch_fill_w(w_out, n_seq, count, to[k], rows[k], 1.f, st)) != hipSuccess) return hip_fail(e);
+        if (idx_out && (e = bkv::launch_fill_iota(idx_out, n_seq, count, to[k], rows[k], (int32_t)from[k], st)) != hipSuccess) return hip_fail(e);
+    }
+    if (n_mid == 0) return BKV_OK;
+    if (T == 0) {       // the rows in between are kept as they are too
+        if (idx_out && (e = bkv::launch_fill_iota(idx_out, n_seq, count, n_sink, n_mid, (int32_t)n_sink, st)) != hipSuccess) return hip_fail(e);
+        idx_out = nullptr;
+    }
+    const TreeWindow win = {n, n, n_sink, count};
+    return merge_reduce_impl(p, (const char*)K + (size_t)n_sink * rb, V, n_seq, n_mid, seq_base, (char*)K_out + (size_t)n_sink * rb,
+                             (char*)V_out + (size_t)n_sink * rb, w_out ? w_out + n_sink : nullptr, count,
+                             idx_out ? idx_out + n_sink : nullptr, nullptr, status_out, workspace, ws_bytes, hip_stream, &win);
 }
 
 int bkv_profile_enable(int32_t max_records) { return bkv::prof_enable(max_records) == 0 ? BKV_OK : BKV_EHIP; }

@@ -28,6 +28,7 @@ struct CompressArgs {
     int64_t v_seq_stride;     // tokens between consecutive sequences in V; survivors are read at their ORIGINAL token index
     int64_t seq_base;         // added to the sequence number in the generator stream id
     int64_t blk_base;         // added to the block number in the generator counter
+    int64_t idx_base;         // without idx_in: original index of the launch's first token within its sequence (V rows, idx_out)
     uint64_t seed;
     int32_t blocks_per_seq;
     int32_t b;
@@ -58,6 +59,8 @@ hipError_t launch_copy_f32(const float* src, float* dst, int64_t n_seq, int64_t 
                            int64_t dst_seq_stride, int64_t rows, hipStream_t st);
 hipError_t launch_fill_w(float* w, int64_t n_seq, int64_t seq_stride, int64_t off, int64_t rows, float val,
                          hipStream_t st);
+hipError_t launch_fill_iota(int32_t* idx, int64_t n_seq, int64_t seq_stride, int64_t off, int64_t rows, int32_t first,
+                            hipStream_t st);
 
 // Opt-in per-launch timing with HIP events on the caller's stream (diagnostics).
 enum { kProfCompress = 0, kProfGather = 1, kProfAttend = 2, kProfAttendMerge = 3 };

@@ -1029,7 +1029,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     // survivors: rows of the ORIGINAL keys / values, ascending index (16-byte slices, several rows in flight)
     auto src_token = [&](int r) -> int64_t {      // token of survivor r within its sequence, in the value tensor's frame
         const int kept = keptIdx[r];
-        return a.idx_in ? (int64_t)a.idx_in[in_tok0 + kept] : (int64_t)blk * b + kept;
+        return a.idx_in ? (int64_t)a.idx_in[in_tok0 + kept] : a.idx_base + (int64_t)blk * b + kept;
     };
     {
         // Keys come from LDS when the whole block is still resident, else from global memory (L2); value rows
@@ -1272,6 +1272,24 @@ hipError_t launch_fill_w(float* w, int64_t n_seq, int64_t seq_stride, int64_t of
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(fill_w_kernel, dim3((unsigned)blocks), dim3(256), 0, st, w, seq_stride, off, rows, val, total);
+    return hipGetLastError();
+}
+
+// idx[seq, off + r] = first + r for r < rows
+__global__ void fill_iota_kernel(int32_t* idx, int64_t seq_stride, int64_t off, int64_t rows, int32_t first, int64_t total) {
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t seq = t / rows;
+        const int64_t r = t - seq * rows;
+        idx[seq * seq_stride + off + r] = first + (int32_t)r;
+    }
+}
+hipError_t launch_fill_iota(int32_t* idx, int64_t n_seq, int64_t seq_stride, int64_t off, int64_t rows, int32_t first,
+                            hipStream_t st) {
+    const int64_t total = n_seq * rows;
+    if (total <= 0) return hipSuccess;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(fill_iota_kernel, dim3((unsigned)blocks), dim3(256), 0, st, idx, seq_stride, off, rows, first, total);
     return hipGetLastError();
 }
 

@@ -77,6 +77,13 @@ def test_misuse_is_rejected_before_any_launch(bk):
     assert mr(512 * 4, None, 0) == bk.BKV_EWORKSPACE
     assert mr(512 * 4, one, 16) == bk.BKV_EWORKSPACE
     assert L.bkv_merge_reduce_workspace_bytes(C.byref(ok), 2, 2048) >= 2 * (1024 + 512) * 256
+    # protected windows: they must fit, and the rows in between must be a multiple of block * 2^T
+    mp = lambda n, sink, rec: L.bkv_merge_reduce_protected(C.byref(ok), one, one, 2, n, sink, rec, 0, one, one, None, None, None, None, 0, None)
+    assert mp(4096, 3000, 2000) == bk.BKV_EINVAL
+    assert mp(4096, -1, 0) == bk.BKV_EINVAL
+    assert mp(256 + 512 * 4 + 100 + 256, 256, 256) == bk.BKV_ESHAPE
+    assert mp(256 + 512 * 4 + 256, 256, 256) == bk.BKV_EWORKSPACE          # shapes fine, no workspace given
+    assert mp(0, 0, 0) == bk.BKV_OK
     # attend
     at = lambda count, stride, g: L.bkv_attend_kv(C.byref(ok), one, one, one, 2, count, stride, one, g, 1, one, None, None, 0, None)
     assert at(10, 5, 4) == bk.BKV_EINVAL

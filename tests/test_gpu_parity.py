@@ -273,6 +273,55 @@ def test_merge_reduce_three_rounds_and_seq_base(bk, synth, oracle):
         np.testing.assert_array_equal(off["idx"], res["idx"][1].cpu().numpy())
 
 
+@pytest.mark.parametrize("dtype,d,b,T,n_sink,n_recent,n_mid", [
+    (torch.bfloat16, 128, 512, 2, 256, 256, 4096),      # the paper's windows, workload-2 blocks
+    (torch.float32, 64, 128, 1, 40, 7, 512),            # ragged windows
+    (torch.bfloat16, 64, 64, 3, 0, 100, 1024),          # no sink
+    (torch.bfloat16, 128, 256, 0, 16, 16, 256),         # no rounds: a plain copy
+    (torch.bfloat16, 128, 256, 2, 300, 212, 0),         # nothing in between
+])
+def test_merge_reduce_protected_windows(bk, synth, oracle, dtype, d, b, T, n_sink, n_recent, n_mid):
+    """First and recent tokens kept exactly, tree on the rows in between (Full Experimental Details, single-layer
+    experiments).  The rows in between must equal bkv_merge_reduce on a copy of those rows (itself checked against the
+    oracle above), shifted by the sink; the free-running oracle agrees unless a margin decision occurred."""
+    from oracle.merge_reduce import merge_reduce_protected
+    from oracle.tuning import tune_log_c
+    n = n_sink + n_mid + n_recent
+    n_seq = 3
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=n, d=d, g=1, nq=1, seed=900 + n, device="cpu", dtype=dtype)
+    K, V = t["K"].cuda(), t["V"].cuda()
+    nb = min(2, n_mid // b)
+    log_c = f32(tune_log_c(to_f64(K[:1, n_sink:n_sink + nb * b]).reshape(nb, b, d), center=True)) if nb else 0.0
+    p = bk.make_params(d, b, T, dtype, log_c=log_c, seed=4242, center=True)
+    res = bk.merge_reduce_protected(p, K, V, n_sink, n_recent, seq_base=5)
+    kept_mid = n_mid >> T
+    count = n_sink + kept_mid + n_recent
+    idx = res["idx"].cpu().numpy().astype(np.int64)
+    assert idx.shape == (n_seq, count)
+    np.testing.assert_array_equal(idx[:, :n_sink], np.tile(np.arange(n_sink), (n_seq, 1)))
+    np.testing.assert_array_equal(idx[:, count - n_recent:], np.tile(np.arange(n - n_recent, n), (n_seq, 1)))
+    w = res["w"].cpu().numpy()
+    assert np.all(w[:, :n_sink] == 1.0) and np.all(w[:, count - n_recent:] == 1.0)
+    assert np.all(w[:, n_sink:count - n_recent] == float(2 ** T)) and np.all(w.sum(axis=1) == n)
+    gi = torch.from_numpy(idx).cuda()
+    assert torch.equal(res["K"], torch.gather(K, 1, gi[..., None].expand(-1, -1, d)))
+    assert torch.equal(res["V"], torch.gather(V, 1, gi[..., None].expand(-1, -1, d)))
+    if n_mid:
+        alone = bk.merge_reduce(p, K[:, n_sink:n - n_recent].contiguous(), V[:, n_sink:n - n_recent].contiguous(), seq_base=5)
+        if T > 0:
+            np.testing.assert_array_equal(idx[:, n_sink:count - n_recent] - n_sink, alone["idx"].cpu().numpy())
+            assert torch.equal(res["status"], alone["status"])
+        else:
+            np.testing.assert_array_equal(idx[:, n_sink:count - n_recent], np.tile(np.arange(n_sink, n - n_recent), (n_seq, 1)))
+        assert torch.equal(res["K"][:, n_sink:count - n_recent], alone["K"])
+        if T > 0 and int((res["status"].cpu().numpy() >> 8).sum()) == 0:
+            for s in range(n_seq):
+                off = merge_reduce_protected(to_f64(K[s]), to_f64(V[s]), b=b, T=T, n_sink=n_sink, n_recent=n_recent, seed=4242,
+                                             seq=5 + s, log_c=log_c, center=True)
+                np.testing.assert_array_equal(off["idx"], idx[s])
+                np.testing.assert_array_equal(off["w"], w[s])
+
+
 def test_merge_reduce_rounds_zero_and_empty(bk, synth):
     t = synth.gqa_layer_bf16(n_seq=2, n=128, d=64, g=1, nq=1, seed=3, device="cpu")
     K, V = t["K"].cuda(), t["V"].cuda()

@@ -1,0 +1,149 @@
+"""Ablation grid of the paper's single-layer study on synthetic data (one GPU).
+
+    python -m paper_2502_07861_amd.ablation [--seeds 10] [--json]
+
+For block sizes b in {256, 128, 64} and compression rates 2^-T in {1/2, 1/4, 1/8} (the grid of the runtime /
+relative-error tables in "Ablation Studies on Single Layer Attention Approximation", arXiv 2502.07861): the first
+and the most recent 256 tokens of every KV sequence are kept, the rows in between go through the halving tree
+(`bkv_merge_reduce_protected`), and the estimator of Alg. 1 answers a batch of queries from the kept set.  Reported
+per cell: the run time of the compression and the relative error ||z - Attn|| / ||Attn|| per query, mean and standard
+deviation over seeds, next to independent uniform sampling of the same number of rows in between (the paper's
+comparator).  Next to it the relative error of the softmax normaliser sum_i w_i exp(<k_i,q>/sqrt d), the quantity
+that balancing the keys alone controls directly (the denominator instance of Alg. 1).  Exact attention and both
+estimates come from the same attend kernel (weights 1 for exact attention).
+
+The inputs are synthetic stand-ins (synth.gqa_layer_bf16, one layer of 8 KV heads, 4 query heads each, 64 queries
+per head); the paper's tables are on Llama-3.1-8B / TriviaQA activations, so only the shape of the study carries over.
+ln c per block size was bisected once on the CPU oracle (oracle/tuning.py, mean |2p - 1| = 0.25 on the first two
+sequences) so that the walk's decisions depend on the kernel weights.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+
+import torch
+
+from . import binding, synth
+
+BLOCKS = (256, 128, 64)
+ROUNDS = (1, 2, 3)
+N_SINK = N_RECENT = 256
+N_MID = 8192
+SEED_DATA = 0x250207861006
+LOG_C = {64: -53.9166, 128: -59.3241, 256: -61.8303}
+
+
+def make_inputs(device="cuda", n_seq=8, n_mid=N_MID, d=128, g=4, nq=64):
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=N_SINK + n_mid + N_RECENT, d=d, g=g, nq=nq, seed=SEED_DATA, device="cpu")
+    return t["K"].to(device).contiguous(), t["V"].to(device).contiguous(), t["Q"].to(device).contiguous()
+
+
+def uniform_sample_protected(n_seq, n, n_sink, n_recent, T, seed, device):
+    """The comparator: windows kept, a uniformly random 2^-T fraction of the rows in between (without replacement,
+    independently per sequence).  Returns (idx [n_seq, count] int64 ascending, w [n_seq, count] fp32)."""
+    n_mid = n - n_sink - n_recent
+    kept = n_mid >> T
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(int(seed))
+    rows = []
+    for _ in range(n_seq):
+        pick = torch.randperm(n_mid, generator=gen)[:kept].sort().values + n_sink
+        rows.append(torch.cat([torch.arange(n_sink), pick, torch.arange(n - n_recent, n)]))
+    idx = torch.stack(rows).to(device)
+    w = torch.ones(n_seq, idx.shape[1], dtype=torch.float32)
+    w[:, n_sink:n_sink + kept] = float(2 ** T)
+    return idx, w.to(device)
+
+
+def relative_error(z, exact):
+    """Mean over all queries of ||z - Attn|| / ||Attn|| (norms over the head dimension)."""
+    z, exact = z.float(), exact.float()
+    return float(((z - exact).norm(dim=-1) / exact.norm(dim=-1)).mean())
+
+
+def normaliser_error(lse, lse_exact):
+    """Mean over all queries of |D_est / D - 1| for the softmax normaliser D (lse = ln D)."""
+    return float((torch.exp(lse.double() - lse_exact.double()) - 1.0).abs().mean())
+
+
+def run(seeds=10, blocks=BLOCKS, rounds=ROUNDS, n_mid=N_MID, n_seq=8, device="cuda", nq=64, keep_outputs=False):
+    """The grid.  keep_outputs: every cell also carries the tensors of its first counted seed (kept indices, weights,
+    both estimates, the uniform comparator's indices) and the result the inputs, for checking against a reference."""
+    K, V, Q = make_inputs(device, n_seq=n_seq, n_mid=n_mid, nq=nq)
+    n, d = K.shape[1], K.shape[2]
+    p0 = binding.make_params(d, 64, 0, K.dtype, log_c=0.0, seed=0, center=True)
+    exact, lse_exact = binding.attend_kv(p0, K, V, torch.ones(n_seq, n, device=device, dtype=torch.float32), Q)
+    cells = []
+    for b in blocks:
+        for T in rounds:
+            if n_mid % (b << T):
+                continue
+            err_b, err_u, den_b, den_u, ms = [], [], [], [], []
+            for s in range(seeds + 1):                      # run 0 warms up and is not counted
+                p = binding.make_params(d, b, T, K.dtype, log_c=LOG_C.get(b, 0.0), seed=1000 + s, center=True)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                res = binding.merge_reduce_protected(p, K, V, N_SINK, N_RECENT)
+                e1.record()
+                z, lse_b = binding.attend_kv(p, res["K"], res["V"], res["w"], Q)
+                idx_u, w_u = uniform_sample_protected(n_seq, n, N_SINK, N_RECENT, T, 7000 + s, device)
+                gi = idx_u[..., None].expand(-1, -1, d)
+                zu, lse_u = binding.attend_kv(p, torch.gather(K, 1, gi), torch.gather(V, 1, gi), w_u, Q)
+                torch.cuda.synchronize()
+                if s == 0:
+                    continue
+                if s == 1 and keep_outputs:
+                    first = dict(idx=res["idx"], w=res["w"], z=z, lse=lse_b, idx_uniform=idx_u, w_uniform=w_u, z_uniform=zu,
+                                 lse_uniform=lse_u, seed=1000 + s)
+                ms.append(e0.elapsed_time(e1))
+                err_b.append(relative_error(z, exact))
+                err_u.append(relative_error(zu, exact))
+                den_b.append(normaliser_error(lse_b, lse_exact))
+                den_u.append(normaliser_error(lse_u, lse_exact))
+            tb, tu, tm = torch.tensor(err_b), torch.tensor(err_u), torch.tensor(ms)
+            db, du = torch.tensor(den_b), torch.tensor(den_u)
+            cells.append(dict(block=b, rate="1/%d" % (1 << T), rounds=T, kept=int(res["K"].shape[1]),
+                              compress_ms=float(tm.mean()), balancekv_rel_err=float(tb.mean()), balancekv_std=float(tb.std()),
+                              uniform_rel_err=float(tu.mean()), uniform_std=float(tu.std()),
+                              balancekv_normaliser_err=float(db.mean()), balancekv_normaliser_std=float(db.std()),
+                              uniform_normaliser_err=float(du.mean()), uniform_normaliser_std=float(du.std())))
+            if keep_outputs:
+                cells[-1]["first"] = first
+    return dict(workload="%d KV sequences x (%d + %d + %d) tokens, d=%d, %d x %d queries, bf16, synthetic"
+                         % (n_seq, N_SINK, n_mid, N_RECENT, d, Q.shape[1], Q.shape[2]), seeds=seeds, cells=cells,
+                **(dict(K=K, V=V, Q=Q, exact=exact) if keep_outputs else {}))
+
+
+def as_table(result):
+    lines = ["| block | rate | kept | compress ms | BalanceKV rel. err | uniform rel. err | BalanceKV normaliser err | uniform normaliser err |",
+             "|---|---|---|---|---|---|---|---|"]
+    for c in result["cells"]:
+        lines.append("| %d | %s | %d | %.3f | %.4f ± %.4f | %.4f ± %.4f | %.5f ± %.5f | %.5f ± %.5f |"
+                     % (c["block"], c["rate"], c["kept"], c["compress_ms"], c["balancekv_rel_err"], c["balancekv_std"],
+                        c["uniform_rel_err"], c["uniform_std"], c["balancekv_normaliser_err"], c["balancekv_normaliser_std"],
+                        c["uniform_normaliser_err"], c["uniform_normaliser_std"]))
+    return "\n".join(lines)
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--seeds", type=int, default=10)
+    ap.add_argument("--json", action="store_true", help="print one JSON line instead of the table")
+    args = ap.parse_args(argv)
+    if not torch.cuda.is_available():
+        print("ablation: needs a GPU", file=sys.stderr)
+        return 2
+    binding.lib()
+    result = run(seeds=args.seeds)
+    if args.json:
+        print(json.dumps(result))
+    else:
+        print(result["workload"] + ", %d seeds" % result["seeds"])
+        print(as_table(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -101,3 +101,22 @@ def test_misuse_is_rejected_before_any_launch(bk):
 def test_literal_log_c(bk, oracle):
     assert abs(bk.literal_log_c(512, 1e-6) - oracle.log_c_literal(512, 1e-6)) < 1e-12
     assert abs(bk.literal_log_c(512, 1e-6) - math.log(30 * math.log(512e6))) < 1e-12
+
+
+def test_ablation_comparator_and_error_formula():
+    """Host logic of the ablation grid: the uniform-sampling comparator keeps the windows and a duplicate-free sample
+    of the right size with total weight n; the reported error is the mean per-query relative error."""
+    import numpy as np
+    import torch
+    from paper_2502_07861_amd import ablation
+    n, sink, rec, T = 256 + 512 + 100, 256, 100, 2
+    idx, w = ablation.uniform_sample_protected(3, n, sink, rec, T, seed=5, device="cpu")
+    assert idx.shape == (3, sink + (512 >> T) + rec) and bool((idx[:, 1:] > idx[:, :-1]).all())
+    assert bool((idx[:, :sink] == torch.arange(sink)).all()) and bool((idx[:, -rec:] == torch.arange(n - rec, n)).all())
+    assert bool((w.sum(dim=1) == n).all()) and bool((w[:, sink:-rec] == 4.0).all())
+    assert not torch.equal(idx[0], idx[1])                       # sequences draw independently
+    again, _ = ablation.uniform_sample_protected(3, n, sink, rec, T, seed=5, device="cpu")
+    assert torch.equal(idx, again)
+    z, e = torch.randn(2, 3, 4, 8), torch.randn(2, 3, 4, 8)
+    ref = np.mean(np.linalg.norm((z - e).numpy(), axis=-1) / np.linalg.norm(e.numpy(), axis=-1))
+    assert abs(ablation.relative_error(z, e) - ref) < 1e-6

@@ -553,3 +553,37 @@ def test_cache_prefill_equals_merge_reduce(bk, synth):
         small = bk.Cache(dec, n_seq, max_tokens=256)
         small.prefill(bk.make_params(d, 256, 1, torch.bfloat16, log_c=0.0), K, V)
     assert e.value.code == -5
+
+
+# ------------------------------------------------------------------------------------------ ablation grid
+def test_ablation_grid_cell_against_oracle(bk, synth, oracle):
+    """The single-layer ablation (grid of block size x rate, uniform-sampling comparator) on a small instance: every
+    number of a cell is recomputed by the oracle from the kept sets (Alg. 1 output line in fp64 against Eq. 1)."""
+    from paper_2502_07861_amd import ablation
+    r = ablation.run(seeds=2, blocks=(64,), rounds=(1, 2), n_mid=1024, n_seq=2, nq=4, keep_outputs=True)
+    K, V, Q = to_f64(r["K"]), to_f64(r["V"]), to_f64(r["Q"])
+    n = K.shape[1]
+    assert [c["rate"] for c in r["cells"]] == ["1/2", "1/4"]
+    for c in r["cells"]:
+        f = c["first"]
+        T = c["rounds"]
+        assert c["kept"] == 256 + (1024 >> T) + 256 and c["compress_ms"] > 0
+        for idx_t, w_t, z_t in ((f["idx"], f["w"], f["z"]), (f["idx_uniform"], f["w_uniform"], f["z_uniform"])):
+            idx, w, z = idx_t.cpu().numpy().astype(np.int64), w_t.cpu().numpy().astype(np.float64), to_f64(z_t)
+            errs = []
+            for s in range(K.shape[0]):
+                assert np.all(np.diff(idx[s]) > 0) and idx[s, 0] == 0 and idx[s, -1] == n - 1 and w[s].sum() == n
+                for a in range(Q.shape[1]):
+                    for j in range(Q.shape[2]):
+                        exact = oracle.exact_attention(Q[s, a, j], K[s], V[s])
+                        est = oracle.attend(Q[s, a, j], K[s][idx[s]], V[s][idx[s]], w[s])[0]
+                        np.testing.assert_allclose(z[s, a, j], est, rtol=0, atol=2e-2 * np.linalg.norm(est))
+                        errs.append(np.linalg.norm(est - exact) / np.linalg.norm(exact))
+            # the cell's figure is a mean over two seeds of values like this one
+            assert 0.2 * np.mean(errs) < (c["balancekv_rel_err"] if idx_t is f["idx"] else c["uniform_rel_err"]) < 5 * np.mean(errs) + 2e-2
+        # the comparator keeps the windows and a duplicate-free sample of the right size in between
+        iu = f["idx_uniform"].cpu().numpy()
+        assert np.all(iu[:, :256] == np.arange(256)) and np.all(iu[:, -256:] == np.arange(n - 256, n))
+        mid = iu[:, 256:-256]
+        assert mid.shape[1] == 1024 >> T and np.all((mid >= 256) & (mid < n - 256))
+

@@ -14,7 +14,8 @@ namespace bkv {
 constexpr int kQT = 4;           // query vectors per pass over the cache
 constexpr int kAttWaves = 4;
 constexpr int kUnroll = 4;       // rows in flight per lane group
-constexpr int kTargetWGs = 4096;   // workgroups of the streaming pass when the token range is split
+constexpr int kTargetWGs = 512;    // workgroups of the streaming pass when the token range is split (two per compute unit:
+                                   // more only lengthen the merge, measured from 8 to 256 sequences)
 constexpr float kNeg = -1.0e30f; // "minus infinity" that stays finite under subtraction
 
 template <typename T, int D>
@@ -163,13 +164,19 @@ __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const At
     }
 }
 
-// One workgroup (2 wavefronts) per (sequence, query): merge the split partials, normalise, store.
-constexpr int kMergeThreads = 128;
+// One workgroup (4 wavefronts) per (sequence, query): merge the split partials, normalise, store.  The numerator
+// pass spreads the splits over the threads (a thread owns two columns and every SR-th split, several loads in
+// flight), so its latency does not grow with the number of splits; the partial sums meet in LDS in a fixed order.
+constexpr int kMergeThreads = 256;
 constexpr int kScaleCache = 512;
 template <typename T, int D>
 __global__ __launch_bounds__(kMergeThreads) void attend_merge_kernel(const AttendArgs a, int n_qgroups) {
-    __shared__ float red[4];
+    constexpr int NW = kMergeThreads / 64;
+    constexpr int CG = D / 2;                        // column pairs (the rows of a partial are 8-byte aligned)
+    constexpr int SR = kMergeThreads / CG;           // splits summed side by side
+    __shared__ float red[2 * NW];
     __shared__ float scale[kScaleCache];
+    __shared__ float part[SR][D];
     const int64_t seq = blockIdx.y;
     const int q = blockIdx.x, tid = threadIdx.x, ns = a.n_splits;
     const int qg = q / kQT, qi = q % kQT;
@@ -181,7 +188,9 @@ __global__ __launch_bounds__(kMergeThreads) void attend_merge_kernel(const Atten
     m = wave_max(m);
     if ((tid & 63) == 0) red[tid >> 6] = m;
     __syncthreads();
-    const float M = fmaxf(red[0], red[1]);
+    float M = red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) M = fmaxf(M, red[w]);
     // denominators, rescaled; the per-split factors are kept for the numerator pass
     float l = 0.f;
     for (int s = tid; s < ns; s += kMergeThreads) {
@@ -190,24 +199,40 @@ __global__ __launch_bounds__(kMergeThreads) void attend_merge_kernel(const Atten
         if (s < kScaleCache) scale[s] = sc;
     }
     l = wave_sum(l);
-    if ((tid & 63) == 0) red[2 + (tid >> 6)] = l;
+    if ((tid & 63) == 0) red[NW + (tid >> 6)] = l;
     __syncthreads();
-    const float L = red[2] + red[3];
+    float L = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) L += red[NW + w];
     const float inv = L > 0.f ? 1.f / L : 0.f;
+    // numerators
+    const int cg = tid % CG, sg = tid / CG;
+    auto factor = [&](int s) -> float { return s < kScaleCache ? scale[s] : fast_exp2(src[s * sstride + D] - M); };
+    float acc0 = 0.f, acc1 = 0.f;
+    int s = sg;
+    for (; s + 3 * SR < ns; s += 4 * SR) {                         // four independent loads in flight
+        const floatx2 p0 = *reinterpret_cast<const floatx2*>(src + (size_t)s * sstride + 2 * cg);
+        const floatx2 p1 = *reinterpret_cast<const floatx2*>(src + (size_t)(s + SR) * sstride + 2 * cg);
+        const floatx2 p2 = *reinterpret_cast<const floatx2*>(src + (size_t)(s + 2 * SR) * sstride + 2 * cg);
+        const floatx2 p3 = *reinterpret_cast<const floatx2*>(src + (size_t)(s + 3 * SR) * sstride + 2 * cg);
+        const float f0 = factor(s), f1 = factor(s + SR), f2 = factor(s + 2 * SR), f3 = factor(s + 3 * SR);
+        acc0 = fmaf(p0[0], f0, acc0); acc1 = fmaf(p0[1], f0, acc1);
+        acc0 = fmaf(p1[0], f1, acc0); acc1 = fmaf(p1[1], f1, acc1);
+        acc0 = fmaf(p2[0], f2, acc0); acc1 = fmaf(p2[1], f2, acc1);
+        acc0 = fmaf(p3[0], f3, acc0); acc1 = fmaf(p3[1], f3, acc1);
+    }
+    for (; s < ns; s += SR) {
+        const floatx2 p0 = *reinterpret_cast<const floatx2*>(src + (size_t)s * sstride + 2 * cg);
+        const float f0 = factor(s);
+        acc0 = fmaf(p0[0], f0, acc0); acc1 = fmaf(p0[1], f0, acc1);
+    }
+    part[sg][2 * cg] = acc0; part[sg][2 * cg + 1] = acc1;
+    __syncthreads();
     for (int c = tid; c < D; c += kMergeThreads) {
-        float acc = 0.f;
-        int s = 0;
-        for (; s + 4 <= ns && s + 4 <= kScaleCache; s += 4) {      // four independent loads in flight
-            const float p0 = src[(s + 0) * sstride + c], p1 = src[(s + 1) * sstride + c];
-            const float p2 = src[(s + 2) * sstride + c], p3 = src[(s + 3) * sstride + c];
-            acc = fmaf(p0, scale[s], acc); acc = fmaf(p1, scale[s + 1], acc);
-            acc = fmaf(p2, scale[s + 2], acc); acc = fmaf(p3, scale[s + 3], acc);
-        }
-        for (; s < ns; ++s) {
-            const float sc = s < kScaleCache ? scale[s] : fast_exp2(src[s * sstride + D] - M);
-            acc = fmaf(src[s * sstride + c], sc, acc);
-        }
-        const float z = acc * inv;
+        float z = 0.f;
+#pragma unroll
+        for (int r = 0; r < SR; ++r) z += part[r][c];
+        z *= inv;
         const size_t oi = ((size_t)seq * a.n_q + q) * D + c;
         if (sizeof(T) == 2) reinterpret_cast<unsigned short*>(a.out)[oi] = (unsigned short)f32_to_bf16_bits(z);
         else reinterpret_cast<float*>(a.out)[oi] = z;
@@ -223,7 +248,7 @@ static void attend_plan(int d, int dtype_bytes, int64_t n_seq, int64_t count, in
     *n_qg = (n_q + kQT - 1) / kQT;
     int64_t wgs = n_seq * (*n_qg);
     int64_t want = wgs > 0 ? (kTargetWGs + wgs - 1) / wgs : 1;
-    int64_t max_splits = (count + 2 * rows_it - 1) / (2 * rows_it);
+    int64_t max_splits = (count + rows_it - 1) / rows_it;      // a split is at least one batch of rows
     if (max_splits < 1) max_splits = 1;
     if (want > max_splits) want = max_splits;
     if (want < 1) want = 1;

@@ -210,8 +210,9 @@ int bkv_attend(const bkv_cache* c, const void* Q, int32_t g, int32_t nq, void* o
 
 /* ---- diagnostics: per-launch kernel times ---------------------------------------------------------
  * For callers that want the duration of the individual kernels behind a call (benchmarks): after
- * bkv_profile_enable(n > 0) the library brackets each kernel launch with a pair of HIP events on the
- * caller's stream (up to n launches; creating the events allocates).  bkv_profile_read waits for the
+ * bkv_profile_enable(n > 0) the library attaches a start and a stop event to each kernel launch (the
+ * dispatch's own begin and end; up to n launches; creating the events allocates; not for use under
+ * stream capture).  bkv_profile_read waits for the
  * recorded launches, returns how many were written and clears the log.  kind: 0 halving kernel,
  * 1 value gather, 2 attend pass, 3 attend merge; units: tokens the launch consumed.
  * bkv_profile_enable(0) turns it off.  Not thread-safe; off by default.                             */

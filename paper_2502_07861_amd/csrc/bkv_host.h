@@ -62,7 +62,7 @@ hipError_t launch_fill_w(float* w, int64_t n_seq, int64_t seq_stride, int64_t of
 hipError_t launch_fill_iota(int32_t* idx, int64_t n_seq, int64_t seq_stride, int64_t off, int64_t rows, int32_t first,
                             hipStream_t st);
 
-// Opt-in per-launch timing with HIP events on the caller's stream (diagnostics).
+// Opt-in per-launch timing (diagnostics): start/stop events attached to the launches themselves.
 enum { kProfCompress = 0, kProfGather = 1, kProfAttend = 2, kProfAttendMerge = 3 };
 int prof_enable(int n);
 int prof_read(int32_t* kind, float* ms, int64_t* units, int cap);

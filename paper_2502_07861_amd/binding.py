@@ -202,7 +202,9 @@ def merge_reduce_protected(p, K, V, n_sink, n_recent, *, seq_base=0, workspace=N
     out = dict(K=torch.empty(n_seq, count, d, device=dev, dtype=dt), V=torch.empty(n_seq, count, d, device=dev, dtype=dt),
                w=torch.empty(n_seq, count, device=dev, dtype=torch.float32),
                idx=torch.empty(n_seq, count, device=dev, dtype=torch.int32),
-               status=torch.zeros(n_seq, max(T, 1), device=dev, dtype=torch.int32))
+               # the library writes every entry when T > 0 (poisoned here so that a test can tell)
+               status=torch.full((n_seq, T), -1, device=dev, dtype=torch.int32) if T > 0
+               else torch.zeros(n_seq, 1, device=dev, dtype=torch.int32))
     if workspace is None:
         workspace = torch.empty(max(merge_reduce_workspace_bytes(p, n_seq, max(n_mid, 0)), 256), device=dev, dtype=torch.uint8)
     rc = lib().bkv_merge_reduce_protected(C.byref(p), _ptr(K, dt, "K"), _ptr(V, dt, "V"), n_seq, n, n_sink, n_recent, seq_base,

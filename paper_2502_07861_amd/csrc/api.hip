@@ -267,7 +267,10 @@ int bkv_merge_reduce_protected(const bkv_params* p, const void* K, const void* V
         if (w_out && (e = bkv::launch_fill_w(w_out, n_seq, count, to[k], rows[k], 1.f, st)) != hipSuccess) return hip_fail(e);
         if (idx_out && (e = bkv::launch_fill_iota(idx_out, n_seq, count, to[k], rows[k], (int32_t)from[k], st)) != hipSuccess) return hip_fail(e);
     }
-    if (n_mid == 0) return BKV_OK;
+    if (n_mid == 0) {   // nothing to halve: no events to report
+        if (status_out && T > 0 && (e = bkv::launch_fill_u32(status_out, 0u, n_seq * T, st)) != hipSuccess) return hip_fail(e);
+        return BKV_OK;
+    }
     if (T == 0) {       // the rows in between are kept as they are too
         if (idx_out && (e = bkv::launch_fill_iota(idx_out, n_seq, count, n_sink, n_mid, (int32_t)n_sink, st)) != hipSuccess) return hip_fail(e);
         idx_out = nullptr;

@@ -306,6 +306,10 @@ def test_merge_reduce_protected_windows(bk, synth, oracle, dtype, d, b, T, n_sin
     gi = torch.from_numpy(idx).cuda()
     assert torch.equal(res["K"], torch.gather(K, 1, gi[..., None].expand(-1, -1, d)))
     assert torch.equal(res["V"], torch.gather(V, 1, gi[..., None].expand(-1, -1, d)))
+    if T > 0:
+        assert int(res["status"].min()) >= 0                    # written by the library for every sequence and round
+    if not n_mid:
+        assert int(res["status"].abs().sum()) == 0
     if n_mid:
         alone = bk.merge_reduce(p, K[:, n_sink:n - n_recent].contiguous(), V[:, n_sink:n - n_recent].contiguous(), seq_base=5)
         if T > 0:

@@ -81,29 +81,64 @@ __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const At
             for (int qi = 0; qi < kQT; ++qi) {
                 float part = Elem<T>::dot(qraw[qi], t.k[u]);
                 part = group_sum<SL>(part);
-                lg2[u][qi] = live ? fmaf(part, a.scale_log2, bias) : kNeg;
+                lg2[u][qi] = live ? fmaf(part, a.scale_log2, bias) : 2.f * kNeg;   // below every running maximum: weight 0
                 mb[qi] = fmaxf(mb[qi], lg2[u][qi]);
             }
         }
+        // a new running maximum rescales what has been accumulated; once the maxima have settled this is rare, and
+        // the whole wavefront skips it
+        bool grew = false;
 #pragma unroll
-        for (int qi = 0; qi < kQT; ++qi) {
-            const float mnew = fmaxf(m[qi], mb[qi]);
-            const float sc = fast_exp2(m[qi] - mnew);
-            m[qi] = mnew;
-            l[qi] *= sc;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) o[qi][e] *= sc;
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            float vf[EPL];
-            Elem<T>::unpack(t.v[u], vf);
+        for (int qi = 0; qi < kQT; ++qi) grew |= mb[qi] > m[qi];
+        if (__builtin_amdgcn_ballot_w64(grew) != 0ull) {
 #pragma unroll
             for (int qi = 0; qi < kQT; ++qi) {
-                const float p = (lg2[u][qi] > 0.5f * kNeg) ? fast_exp2(lg2[u][qi] - m[qi]) : 0.f;
-                l[qi] += p;
+                const float mnew = fmaxf(m[qi], mb[qi]);
+                const float sc = fast_exp2(m[qi] - mnew);
+                m[qi] = mnew;
+                l[qi] *= sc;
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) o[qi][e] = fmaf(p, vf[e], o[qi][e]);
+                for (int e = 0; e < EPL; ++e) o[qi][e] *= sc;
+            }
+        }
+        if constexpr (sizeof(T) == 2) {
+            // bf16 values: two rows at a time on the packed dot product.  The weights p are cut to bf16 (the
+            // denominator adds the same cut values, so numerator and denominator stay one estimator); element e of
+            // rows a and b is paired by byte permutes, and o[e] += p_a v_a[e] + p_b v_b[e] is one v_dot2c_f32_bf16
+            // (exact products, fp32 sum) instead of two conversions and two multiply-adds.
+            typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+            static_assert(kUnroll % 2 == 0, "rows are consumed in pairs");
+#pragma unroll
+            for (int u = 0; u < kUnroll; u += 2) {
+                bf16x2_t vp[EPL];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const unsigned int wa = t.v[u][i], wb = t.v[u + 1][i];
+                    vp[2 * i] = __builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(wb, wa, 0x05040100u));       // (a[2i], b[2i])
+                    vp[2 * i + 1] = __builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(wb, wa, 0x07060302u));   // (a[2i+1], b[2i+1])
+                }
+#pragma unroll
+                for (int qi = 0; qi < kQT; ++qi) {
+                    const unsigned int pa = __float_as_uint(fast_exp2(lg2[u][qi] - m[qi]));        // dead rows: 2^(2 kNeg - m) = 0, m >= kNeg
+                    const unsigned int pb = __float_as_uint(fast_exp2(lg2[u + 1][qi] - m[qi]));
+                    l[qi] += __uint_as_float(pa & 0xffff0000u) + __uint_as_float(pb & 0xffff0000u);
+                    const bf16x2_t pp = __builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(pb, pa, 0x07060302u));
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) o[qi][e] = __builtin_amdgcn_fdot2_f32_bf16(pp, vp[e], o[qi][e], false);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                float vf[EPL];
+                Elem<T>::unpack(t.v[u], vf);
+#pragma unroll
+                for (int qi = 0; qi < kQT; ++qi) {
+                    const float p = fast_exp2(lg2[u][qi] - m[qi]);        // dead rows: 2^(2 kNeg - m) = 0, m >= kNeg
+                    l[qi] += p;
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) o[qi][e] = fmaf(p, vf[e], o[qi][e]);
+                }
             }
         }
     };

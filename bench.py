@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--attend-alone", action="store_true",
+                    help="after the prefill, time the attend pass on its own (back to back, and after a 2 GiB fill that "
+                         "leaves the last-level cache dirty) and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy 5 times and exit (reference for FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -133,6 +136,29 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.attend_alone:
+        # Inside a step the attend pass follows a prefill that has just written the cache, and part of its time goes
+        # into writing those lines back.  Here it runs on its own: the same launches, the same cache.
+        count = int(cache.count)
+        att_bytes = n_seq * count * (2 * d * elem + 4)
+        dirty = torch.empty(2 << 30, device="cuda", dtype=torch.uint8)
+        res = {}
+        for label, fill in (("back_to_back", False), ("after_2GiB_fill", True)):
+            binding.profile_enable(4 * args.steps)
+            for _ in range(args.steps):
+                if fill:
+                    dirty.fill_(1)
+                cache.attend(Q, out=out, lse=False)
+            torch.cuda.synchronize()
+            recs = [r for r in binding.profile_read(4 * args.steps) if r[0] == 2]
+            binding.profile_enable(0)
+            ms = sum(r[1] for r in recs) / len(recs)
+            res[label] = {"attend_ms": ms, "attend_gbs": att_bytes / (ms * 1e-3) / 1e9,
+                          "frac_hbm": att_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        print(json.dumps({"attend_alone": res, "workload": args.workload, "cache_tokens_per_sequence": count,
+                          "n_seq": n_seq, "query_heads_per_kv_head": g, "bytes": att_bytes, "launches": args.steps}))
+        cache.close()
+        return
     # the timed region: exactly K steps, nothing else on the stream
     t0 = time.perf_counter()
     for _ in range(args.steps):

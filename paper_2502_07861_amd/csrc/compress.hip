@@ -670,33 +670,54 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 if (has_row) amax = pn - 2.f * pa_row + mumu;
             }
             if constexpr (MULTI) {
-                // a 16-byte slice per thread, rows of the first chunk from LDS, the others from global memory; DPP sums per row
+                // a 16-byte slice per thread, DPP sums per row.  Rows of the first chunk come from LDS, the others from
+                // global memory (L2: the staging pass has just read them); the first batch of those is requested
+                // before the resident rows are worked on, so that its latency is hidden.
                 constexpr int U = 8;
-                for (int ib0 = 0; ib0 < b; ib0 += RG * U) {     // b and CH are multiples of 64 and of RG; whole row groups are skipped past b
+                auto row_terms = [&](const uintx4& raw, int i) {
+                    float f[EPL];
+                    Elem<T>::unpack(raw, f);
+                    float pa = 0.f;
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) pa = fmaf(f[e], mloc[e], pa);
+                    float pn = Elem<T>::dot(raw, raw);
+                    pa = group_sum<SL>(pa);
+                    pn = group_sum<SL>(pn);
+                    if (i < b) {
+                        if (sl == 0) aterm[i] = -alpha * pa;
+                        amax = fmaxf(amax, pn - 2.f * pa + mumu);
+                    }
+                };
+                auto load_global = [&](uintx4 (&raw)[U], int ib0) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int i = min(ib0 + u * RG + rg, b - 1);
+                        raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
+                    }
+                };
+                const int n_lds = min(CH, b);                    // b and CH are multiples of 64 and of RG
+                uintx4 ahead[U];
+                if (n_lds < b) load_global(ahead, n_lds);
+                for (int ib0 = 0; ib0 < n_lds; ib0 += RG * U) {
                     uintx4 raw[U];
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        const int ib = ib0 + u * RG;            // first row of this group: the same in every thread
-                        const int i = min(ib + rg, b - 1);
-                        if (ib < CH) raw[u] = *reinterpret_cast<const uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, sl));
-                        else raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
+                        const int i = min(ib0 + u * RG + rg, n_lds - 1);
+                        raw[u] = *reinterpret_cast<const uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, sl));
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         const int i = ib0 + u * RG + rg;
-                        float f[EPL];
-                        Elem<T>::unpack(raw[u], f);
-                        float pa = 0.f;
-#pragma unroll
-                        for (int e = 0; e < EPL; ++e) pa = fmaf(f[e], mloc[e], pa);
-                        float pn = Elem<T>::dot(raw[u], raw[u]);
-                        pa = group_sum<SL>(pa);
-                        pn = group_sum<SL>(pn);
-                        if (i < b) {
-                            if (sl == 0) aterm[i] = -alpha * pa;
-                            amax = fmaxf(amax, pn - 2.f * pa + mumu);
-                        }
+                        row_terms(raw[u], i < n_lds ? i : b);      // rows past the chunk's end are not counted here
                     }
+                }
+                for (int ib0 = n_lds; ib0 < b; ib0 += RG * U) {
+                    uintx4 raw[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) raw[u] = ahead[u];
+                    if (ib0 + RG * U < b) load_global(ahead, ib0 + RG * U);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) row_terms(raw[u], ib0 + u * RG + rg);
                 }
             }
             amax = wave_max(amax);

@@ -214,6 +214,10 @@ def main():
         "phases": {"compress_tokens_per_s": tokens / (comp_step_ms * 1e-3) if comp_step_ms > 0 else None,
                    "compress_ms_per_step": comp_step_ms,
                    "gram_mfma_tflops_algorithmic": (comp_tokens * b * d) / (comp_ms * 1e-3) / 1e12 if comp_ms > 0 else None,
+                   # executed: 64x64 tiles above the diagonal in full (32 MFMAs of 32x32x16), diagonal tiles three quarters
+                   "gram_mfma_tflops_executed": ((comp_tokens / b) * ((b // 64) * (b // 64 - 1) // 2 * 32 + (b // 64) * 24)
+                                                 * (2 * 32 * 32 * 16 * d / 128)) / (comp_ms * 1e-3) / 1e12 if comp_ms > 0 else None,
+                   "walk_instances_per_s": (comp_tokens / b) / (comp_ms * 1e-3) if comp_ms > 0 else None,
                    "attend_ms": att_ms, "attend_gbs": att_bytes / (att_ms * 1e-3) / 1e9 if att_ms > 0 else None,
                    "attend_frac_hbm": att_bytes / (att_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if att_ms > 0 else None,
                    "attend_bytes": att_bytes},

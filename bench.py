@@ -86,7 +86,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus %d is not supported (the path shards over "
-              "sequences without communication, see DESIGN.md)" % args.gpus, file=sys.stderr)
+              "sequences without communication)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -214,7 +214,7 @@ int bkv_attend(const bkv_cache* c, const void* Q, int32_t g, int32_t nq, void* o
  * dispatch's own begin and end; up to n launches; creating the events allocates; not for use under
  * stream capture).  bkv_profile_read waits for the
  * recorded launches, returns how many were written and clears the log.  kind: 0 halving kernel,
- * 1 value gather, 2 attend pass, 3 attend merge; units: tokens the launch consumed.
+ * 2 attend pass, 3 attend merge (1 is not in use); units: tokens the launch consumed.
  * bkv_profile_enable(0) turns it off.  Not thread-safe; off by default.                             */
 int bkv_profile_enable(int32_t max_records);
 int bkv_profile_read(int32_t* kind, float* ms, int64_t* units, int32_t cap);

@@ -48,8 +48,6 @@ struct CompressArgs {
 
 size_t compress_lds_bytes(int row_bytes, int b);
 hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64_t n_inst, hipStream_t st);
-hipError_t launch_gather_rows(const void* in, const int32_t* idx, void* out, int64_t n_seq, int64_t in_seq_stride,
-                              int64_t out_seq_stride, int64_t rows_out, int row_bytes, hipStream_t st);
 hipError_t launch_fill_u32(void* p, uint32_t v, int64_t n, hipStream_t st);
 hipError_t launch_copy_rows(const void* src, void* dst, int64_t n_seq, int64_t src_seq_stride,
                             int64_t dst_seq_stride, int64_t rows, int row_bytes, hipStream_t st);
@@ -63,7 +61,7 @@ hipError_t launch_fill_iota(int32_t* idx, int64_t n_seq, int64_t seq_stride, int
                             hipStream_t st);
 
 // Opt-in per-launch timing (diagnostics): start/stop events attached to the launches themselves.
-enum { kProfCompress = 0, kProfGather = 1, kProfAttend = 2, kProfAttendMerge = 3 };
+enum { kProfCompress = 0, kProfAttend = 2, kProfAttendMerge = 3 };     // record kinds (1 is not in use)
 int prof_enable(int n);
 int prof_read(int32_t* kind, float* ms, int64_t* units, int cap);
 // Reserves a timing record and hands out its two events (false: timing is off or the records are used up).  The

@@ -1168,34 +1168,6 @@ hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64
     return hipErrorInvalidValue;
 }
 
-// ------------------------------------------------------------------------------------------------
-// Row gather: out[seq, r, :] = in[seq, idx[seq, r], :]  (values of the final survivors).
-// ------------------------------------------------------------------------------------------------
-__global__ void gather_rows_kernel(const char* in, const int32_t* idx, char* out, int64_t in_seq_stride,
-                                   int64_t out_seq_stride, int64_t rows_out, int row_bytes, int64_t total_slices) {
-    const int slices = row_bytes >> 4;
-    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total_slices;
-         t += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t row = t / slices;
-        const int s = (int)(t - row * slices);
-        const int64_t seq = row / rows_out;
-        const int64_t src = seq * in_seq_stride + idx[row];
-        const int64_t dst = seq * out_seq_stride + (row - seq * rows_out);
-        *reinterpret_cast<uintx4*>(out + (size_t)dst * row_bytes + s * 16) =
-            *reinterpret_cast<const uintx4*>(in + (size_t)src * row_bytes + s * 16);
-    }
-}
-
-hipError_t launch_gather_rows(const void* in, const int32_t* idx, void* out, int64_t n_seq, int64_t in_seq_stride,
-                              int64_t out_seq_stride, int64_t rows_out, int row_bytes, hipStream_t st) {
-    const int64_t total = n_seq * rows_out * (row_bytes >> 4);
-    if (total <= 0) return hipSuccess;
-    int64_t blocks = (total + 255) / 256;
-    if (blocks > 65536) blocks = 65536;
-    return launch_timed(kProfGather, n_seq * rows_out, gather_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
-                        (const char*)in, idx, (char*)out, in_seq_stride, out_seq_stride, rows_out, row_bytes, total);
-}
-
 // Fill / copy helpers (plain kernels: safe under graph capture, unlike memset nodes).
 __global__ void fill_u32_kernel(uint32_t* p, uint32_t v, int64_t n) {
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n; t += (int64_t)gridDim.x * blockDim.x)

@@ -559,6 +559,48 @@ def test_cache_prefill_equals_merge_reduce(bk, synth):
     assert e.value.code == -5
 
 
+def test_prefill_and_attend_replay_from_a_captured_graph(bk, synth):
+    """The launches behind bkv_cache_prefill and bkv_attend are plain kernels (no memset nodes, no allocation, no
+    synchronisation), so a caller may capture them: every replay, with unrelated eager work and synchronisations in
+    between, must reproduce the eager result bit for bit."""
+    d, n_seq, n = 128, 4, 4096
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=n, d=d, g=4, nq=1, seed=77, device="cpu")
+    K, V, Q = t["K"].cuda(), t["V"].cuda(), t["Q"].cuda()
+    pre = bk.make_params(d, 512, 2, torch.bfloat16, log_c=-70.0, seed=5, center=True)
+    dec = bk.make_params(d, 512, 2, torch.bfloat16, log_c=-70.0, seed=6, center=True)
+    cache = bk.Cache(dec, n_seq, max_tokens=n)
+    ws = torch.empty(int(bk.lib().bkv_cache_prefill_workspace_bytes(cache.h, pre, n)), device="cuda", dtype=torch.uint8)
+    out = torch.empty(n_seq, 4, 1, d, device="cuda", dtype=torch.bfloat16)
+
+    def step():
+        cache.prefill(pre, K, V, workspace=ws)
+        cache.attend(Q, out=out, lse=False)
+
+    step()                                          # eager: sets up the attend workspace, function attributes, reference
+    torch.cuda.synchronize()
+    ref = out.clone()
+    Kc_ref = cache.views()[0].clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                   # warm-up on the capture stream, as torch asks
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    other = torch.randn(1 << 20, device="cuda")
+    for rep in range(4):
+        out.zero_()
+        cache.views()[0].zero_()                   # the replay must rebuild the cache and the output
+        (other * 2).sum().item()                    # unrelated eager work and a synchronisation between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), rep
+        assert torch.equal(cache.views()[0], Kc_ref), rep
+    cache.close()
+
+
 # ------------------------------------------------------------------------------------------ ablation grid
 def test_ablation_grid_cell_against_oracle(bk, synth, oracle):
     """The single-layer ablation (grid of block size x rate, uniform-sampling comparator) on a small instance: every

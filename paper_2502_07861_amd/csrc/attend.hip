@@ -181,6 +181,32 @@ __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const At
         }
     }
     __syncthreads();
+    if (a.n_splits == 1) {
+        // The whole token range was one split: normalise and store the result here (the same arithmetic as partial +
+        // merge, which is not launched then).
+        for (int t = tid; t < kQT * D; t += kAttWaves * 64) {
+            const int qi = t / D, c = t - qi * D;
+            const int q = qg * kQT + qi;
+            if (q >= a.n_q) continue;
+            float M = red[0][qi][D];
+#pragma unroll
+            for (int w = 1; w < kAttWaves; ++w) M = fmaxf(M, red[w][qi][D]);
+            float val = 0.f, L = 0.f;
+#pragma unroll
+            for (int w = 0; w < kAttWaves; ++w) {
+                const float sc = fast_exp2(red[w][qi][D] - M);
+                val += red[w][qi][c] * sc;
+                L += red[w][qi][D + 1] * sc;
+            }
+            const float z = val * (L > 0.f ? 1.f / L : 0.f);
+            const size_t oi = ((size_t)seq * a.n_q + q) * D + c;
+            if (sizeof(T) == 2) reinterpret_cast<unsigned short*>(a.out)[oi] = (unsigned short)f32_to_bf16_bits(z);
+            else reinterpret_cast<float*>(a.out)[oi] = z;
+            if (c == 0 && a.lse_out)
+                a.lse_out[(size_t)seq * a.n_q + q] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f : -INFINITY;
+        }
+        return;
+    }
     // merge the wavefronts and store the partial: [seq][qg][split][qi][D + 2]
     float* dst = a.partial + ((((size_t)seq * gridDim.y + qg) * a.n_splits + split) * kQT) * (D + 2);
     for (int t = tid; t < kQT * (D + 2); t += kAttWaves * 64) {
@@ -308,7 +334,7 @@ template <typename T, int D>
 static hipError_t launch_attend_t(AttendArgs& a, int64_t n_seq, int n_qg, hipStream_t st) {
     const hipError_t e = launch_timed(kProfAttend, n_seq * a.count, attend_partial_kernel<T, D>, dim3(a.n_splits, n_qg, (unsigned)n_seq),
                                       dim3(kAttWaves * 64), 0, st, a);
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || a.n_splits == 1) return e;          // a single split stores the final result itself
     return launch_timed(kProfAttendMerge, n_seq * a.n_q, attend_merge_kernel<T, D>, dim3(a.n_q, (unsigned)n_seq), dim3(kMergeThreads), 0, st,
                         a, n_qg);
 }

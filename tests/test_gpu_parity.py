@@ -376,6 +376,8 @@ def _attend_ref(oracle, Kc, Vc, w, Q, count):
     (torch.bfloat16, 64, 2, 77, 80, 3, 1),          # g*nq not a multiple of the query tile
     (torch.float32, 128, 2, 1, 8, 2, 3),            # a single token
     (torch.bfloat16, 128, 1, 20000, 20000, 4, 1),   # many splits
+    (torch.bfloat16, 128, 180, 300, 304, 12, 1),    # many sequences: one split each, no merge launch
+    (torch.float32, 64, 140, 70, 70, 16, 1),        # the same in fp32
 ])
 def test_attend_matches_oracle(bk, synth, oracle, dtype, d, n_seq, count, stride, g, nq):
     tol = 1e-4 if dtype == torch.float32 else 2e-2

@@ -45,7 +45,10 @@ extern "C" {
 /* flags */
 #define BKV_CENTER_KEYS 1u  /* shift keys by the block mean for the selection (App. B.5 item 1) */
 #define BKV_STRICT_HALF 2u  /* keep exactly block/2 per block (App. B, Implementation Detail); required */
-#define BKV_VALUE_GRAM  4u  /* multiply kernel weights by <v_i,v_j>/r_value^2 (Alg. 2 line 5); not built: BKV_ESHAPE */
+#define BKV_VALUE_GRAM  4u  /* multiply kernel weights by <v_i,v_j>/r_value^2 (Alg. 2 line 5): the walk then balances
+                             * the numerator instance of Alg. 1.  Built for blocks whose keys and values fit the
+                             * 160 KB of LDS together (d=128: block <= 256 bf16 / 128 fp32; d=64: block <= 512 bf16 /
+                             * 256 fp32); larger blocks: BKV_ESHAPE.  V is required wherever K is.               */
 
 /* return codes */
 #define BKV_OK          0
@@ -69,7 +72,7 @@ typedef struct bkv_params {
     float    log_c;    /* ln c of Alg. 2 line 3; NaN => ln(30 ln(block/delta))                  */
     float    delta;    /* failure probability of Alg. 2; only read when log_c is NaN            */
     float    r_key;    /* key radius of Alg. 2; <= 0 => largest (centred) key norm of the block */
-    float    r_value;  /* value radius; only read with BKV_VALUE_GRAM                           */
+    float    r_value;  /* value radius (BKV_VALUE_GRAM only); <= 0 => largest value norm of the block */
     uint64_t seed;     /* key of the counter-based generator behind "with probability p_j"      */
     uint32_t flags;    /* BKV_* flags                                                           */
     uint32_t reserved; /* must be 0                                                             */
@@ -99,7 +102,9 @@ uint32_t bkv_uniform_bits(uint64_t seed, uint64_t stream, uint64_t ctr);
  * stats_out     [n_inst, 2] fp32 or NULL: {min_j |u_j - p_j|, max_j |y^T eta|/(c R^2)}.
  * workspace     bkv_compress_workspace_bytes() bytes (may be 0 => NULL allowed).
  * Kernel weights are exp((<k_i,k_j> - r_key^2)/sqrt(d) - ln c) (Alg. 2 lines 2-7 divided
- * through by c R^2), keys optionally centred by the block mean; n_inst == 0 is a no-op.          */
+ * through by c R^2), keys optionally centred by the block mean, times <v_i,v_j>/r_value^2 with
+ * BKV_VALUE_GRAM (V then must be given; a block of all-zero values has weight 0 everywhere);
+ * n_inst == 0 is a no-op.                                                                        */
 size_t bkv_compress_workspace_bytes(const bkv_params* p, int64_t n_inst);
 int bkv_compress_block(const bkv_params* p, const void* K, const void* V, int64_t n_inst,
                        const uint64_t* inst_ids, float w_in, const float* uniforms,
@@ -109,7 +114,8 @@ int bkv_compress_block(const bkv_params* p, const void* K, const void* V, int64_
 
 /* The kernel-weight matrix itself, for inspection: G_out [n_inst, block, block] fp32, entry
  * (i,j) = exp((<k_i,k_j> - r_key^2)/sqrt(d) - ln c) as the walk sees it (Alg. 2 line 5, v = 1).
- * Symmetric; produced by the same tile code as the walk.                                        */
+ * Symmetric; produced by the same tile code as the walk.  BKV_VALUE_GRAM: BKV_ESHAPE (no values
+ * are passed here).                                                                              */
 int bkv_kernel_weights(const bkv_params* p, const void* K, int64_t n_inst, float* G_out,
                        void* hip_stream);
 

@@ -13,20 +13,20 @@ import numpy as np
 from . import softmax_balance_batch, uniform_fill
 
 
-def walk_activity(K_blocks, log_c, *, center=False, seed=12345):
-    """Mean |2 p_j - 1| and the FAIL rate over blocks K_blocks [n_inst,b,d]."""
+def walk_activity(K_blocks, log_c, *, center=False, seed=12345, V_blocks=None):
+    """Mean |2 p_j - 1| and the FAIL rate over blocks K_blocks [n_inst,b,d] (V_blocks: with the value factor)."""
     K_blocks = np.asarray(K_blocks, dtype=np.float64)
     n_inst, b, _ = K_blocks.shape
     u = np.stack([uniform_fill(seed, t, 0, b) for t in range(n_inst)])
-    res = softmax_balance_batch(K_blocks, u=u, log_c=log_c, center=center)
+    res = softmax_balance_batch(K_blocks, V_blocks, u=u, log_c=log_c, center=center)
     return float(np.abs(2.0 * res["p"] - 1.0).mean()), float(res["fails"].sum()) / (n_inst * b)
 
 
-def tune_log_c(K_blocks, *, target=0.25, center=False, lo=-400.0, hi=20.0, iters=30):
+def tune_log_c(K_blocks, *, target=0.25, center=False, lo=-400.0, hi=20.0, iters=30, V_blocks=None):
     """Bisection: activity falls as ln c grows."""
     for _ in range(iters):
         mid = 0.5 * (lo + hi)
-        act, _ = walk_activity(K_blocks, mid, center=center)
+        act, _ = walk_activity(K_blocks, mid, center=center, V_blocks=V_blocks)
         if act > target:
             lo = mid
         else:

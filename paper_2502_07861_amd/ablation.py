@@ -1,6 +1,6 @@
 """Ablation grid of the paper's single-layer study on synthetic data (one GPU).
 
-    python -m paper_2502_07861_amd.ablation [--seeds 10] [--json]
+    python -m paper_2502_07861_amd.ablation [--seeds 10] [--json] [--value-factor]
 
 For block sizes b in {256, 128, 64} and compression rates 2^-T in {1/2, 1/4, 1/8} (the grid of the runtime /
 relative-error tables in "Ablation Studies on Single Layer Attention Approximation", arXiv 2502.07861): the first
@@ -15,7 +15,9 @@ estimates come from the same attend kernel (weights 1 for exact attention).
 The inputs are synthetic stand-ins (synth.gqa_layer_bf16, one layer of 8 KV heads, 4 query heads each, 64 queries
 per head); the paper's tables are on Llama-3.1-8B / TriviaQA activations, so only the shape of the study carries over.
 ln c per block size was bisected once on the CPU oracle (oracle/tuning.py, mean |2p - 1| = 0.25 on the first two
-sequences) so that the walk's decisions depend on the kernel weights.
+sequences) so that the walk's decisions depend on the kernel weights.  --value-factor: the walk's weights carry the
+value factor <v_i,v_j>/r_value^2 of Alg. 2 line 5 (the numerator instance of Alg. 1 selects the kept set), with its own
+ln c per block size found the same way.
 """
 from __future__ import annotations
 
@@ -33,6 +35,7 @@ N_SINK = N_RECENT = 256
 N_MID = 8192
 SEED_DATA = 0x250207861006
 LOG_C = {64: -53.9166, 128: -59.3241, 256: -61.8303}
+LOG_C_VALUE = {64: -57.0969, 128: -63.0066, 256: -67.8165}      # with the value factor
 
 
 def make_inputs(device="cuda", n_seq=8, n_mid=N_MID, d=128, g=4, nq=64):
@@ -68,8 +71,9 @@ def normaliser_error(lse, lse_exact):
     return float((torch.exp(lse.double() - lse_exact.double()) - 1.0).abs().mean())
 
 
-def run(seeds=10, blocks=BLOCKS, rounds=ROUNDS, n_mid=N_MID, n_seq=8, device="cuda", nq=64, keep_outputs=False):
-    """The grid.  keep_outputs: every cell also carries the tensors of its first counted seed (kept indices, weights,
+def run(seeds=10, blocks=BLOCKS, rounds=ROUNDS, n_mid=N_MID, n_seq=8, device="cuda", nq=64, keep_outputs=False,
+        value_gram=False):
+    """The grid.  value_gram: kernel weights with the value factor of Alg. 2 line 5.  keep_outputs: every cell also carries the tensors of its first counted seed (kept indices, weights,
     both estimates, the uniform comparator's indices) and the result the inputs, for checking against a reference."""
     K, V, Q = make_inputs(device, n_seq=n_seq, n_mid=n_mid, nq=nq)
     n, d = K.shape[1], K.shape[2]
@@ -82,7 +86,8 @@ def run(seeds=10, blocks=BLOCKS, rounds=ROUNDS, n_mid=N_MID, n_seq=8, device="cu
                 continue
             err_b, err_u, den_b, den_u, ms = [], [], [], [], []
             for s in range(seeds + 1):                      # run 0 warms up and is not counted
-                p = binding.make_params(d, b, T, K.dtype, log_c=LOG_C.get(b, 0.0), seed=1000 + s, center=True)
+                p = binding.make_params(d, b, T, K.dtype, log_c=(LOG_C_VALUE if value_gram else LOG_C).get(b, 0.0),
+                                        seed=1000 + s, center=True, value_gram=value_gram)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
                 res = binding.merge_reduce_protected(p, K, V, N_SINK, N_RECENT)
@@ -111,8 +116,9 @@ def run(seeds=10, blocks=BLOCKS, rounds=ROUNDS, n_mid=N_MID, n_seq=8, device="cu
                               uniform_normaliser_err=float(du.mean()), uniform_normaliser_std=float(du.std())))
             if keep_outputs:
                 cells[-1]["first"] = first
-    return dict(workload="%d KV sequences x (%d + %d + %d) tokens, d=%d, %d x %d queries, bf16, synthetic"
-                         % (n_seq, N_SINK, n_mid, N_RECENT, d, Q.shape[1], Q.shape[2]), seeds=seeds, cells=cells,
+    return dict(workload="%d KV sequences x (%d + %d + %d) tokens, d=%d, %d x %d queries, bf16, synthetic%s"
+                         % (n_seq, N_SINK, n_mid, N_RECENT, d, Q.shape[1], Q.shape[2],
+                            ", weights with the value factor" if value_gram else ""), seeds=seeds, cells=cells,
                 **(dict(K=K, V=V, Q=Q, exact=exact) if keep_outputs else {}))
 
 
@@ -131,12 +137,13 @@ def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--seeds", type=int, default=10)
     ap.add_argument("--json", action="store_true", help="print one JSON line instead of the table")
+    ap.add_argument("--value-factor", action="store_true", help="kernel weights times <v_i,v_j>/r_value^2 (Alg. 2 line 5)")
     args = ap.parse_args(argv)
     if not torch.cuda.is_available():
         print("ablation: needs a GPU", file=sys.stderr)
         return 2
     binding.lib()
-    result = run(seeds=args.seeds)
+    result = run(seeds=args.seeds, value_gram=args.value_factor)
     if args.json:
         print(json.dumps(result))
     else:

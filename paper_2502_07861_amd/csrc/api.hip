@@ -27,7 +27,8 @@ int check_params(const bkv_params* p) {
     if (p->rounds < 0 || p->rounds > 30) return BKV_ESHAPE;
     if (p->dtype != BKV_F32 && p->dtype != BKV_BF16) return BKV_ESHAPE;
     if (p->flags & ~(BKV_CENTER_KEYS | BKV_STRICT_HALF | BKV_VALUE_GRAM)) return BKV_EINVAL;
-    if (p->flags & BKV_VALUE_GRAM) return BKV_ESHAPE;          // value factor of Alg. 2 line 5 not built
+    // value factor of Alg. 2 line 5: built for blocks whose keys and values are resident in LDS together
+    if ((p->flags & BKV_VALUE_GRAM) && !bkv::compress_value_gram_fits(p->d * (p->dtype == BKV_BF16 ? 2 : 4), p->block)) return BKV_ESHAPE;
     if (!(p->flags & BKV_STRICT_HALF)) return BKV_ESHAPE;      // variable-size output not built
     if (isnan(p->log_c) && !(p->delta > 0.f && p->delta < (float)p->block)) return BKV_EINVAL;
     return BKV_OK;
@@ -49,6 +50,7 @@ void fill_common(bkv::CompressArgs& a, const bkv_params* p) {
     a.alpha = (float)(1.4426950408889634 / sqrt((double)p->d));
     a.cterm = (float)(-sqrt((double)p->d) * (double)resolve_log_c(p));
     a.rkey2 = p->r_key > 0.f ? p->r_key * p->r_key : 0.f;
+    a.rvalue2 = p->r_value > 0.f ? p->r_value * p->r_value : 0.f;
 }
 
 }  // namespace
@@ -101,6 +103,7 @@ int bkv_compress_block(const bkv_params* p, const void* K, const void* V, int64_
     if (n_inst == 0) return BKV_OK;
     if (!K || !aligned16(K) || (K_out && !aligned16(K_out))) return BKV_EINVAL;
     if (V_out && (!V || !aligned16(V) || !aligned16(V_out))) return BKV_EINVAL;
+    if ((p->flags & BKV_VALUE_GRAM) && (!V || !aligned16(V))) return BKV_EINVAL;
     if (!(w_in > 0.f)) return BKV_EINVAL;
     bkv::CompressArgs a;
     fill_common(a, p);
@@ -119,6 +122,7 @@ int bkv_kernel_weights(const bkv_params* p, const void* K, int64_t n_inst, float
     if (n_inst < 0) return BKV_EINVAL;
     if (n_inst == 0) return BKV_OK;
     if (!K || !aligned16(K) || !G_out) return BKV_EINVAL;
+    if (p->flags & BKV_VALUE_GRAM) return BKV_ESHAPE;          // the dump takes no values
     bkv::CompressArgs a;
     fill_common(a, p);
     a.K = (const char*)K; a.G_out = G_out;
@@ -207,7 +211,8 @@ static int merge_reduce_impl(const bkv_params* p, const void* K, const void* V, 
         fill_common(a, p);
         a.K = k_in;
         a.K_out = last ? (char*)K_out : kbuf[r & 1];
-        a.V = last ? (const char*)V : nullptr;          // values are gathered once, from the original rows
+        // values are gathered once, from the original rows; the value factor reads them (by original index) in every round
+        a.V = (last || (p->flags & BKV_VALUE_GRAM)) ? (const char*)V : nullptr;
         a.V_out = last ? (char*)V_out : nullptr;
         a.v_seq_stride = v_stride;
         a.idx_base = idx_base;

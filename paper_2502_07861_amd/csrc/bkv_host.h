@@ -40,13 +40,15 @@ struct CompressArgs {
     float alpha;              // log2(e)/sqrt(d)
     float cterm;              // -sqrt(d) * ln c
     float rkey2;              // r_key^2, <= 0: measure
+    float rvalue2;            // r_value^2 (value factor only), <= 0: the largest |v_i|^2 of the block
     uint32_t flags;
     int32_t stagger_blocks;   // the first stagger_blocks workgroups (one per compute unit) start stagger_step clock
     int32_t stagger_step;     // ticks apart, so that the memory-bound phases of successive blocks do not coincide chip-wide
     int32_t prefetch_ahead;   // > 0: while walking, touch the keys of block (this + prefetch_ahead) so that they sit in L2 / MALL
 };
 
-size_t compress_lds_bytes(int row_bytes, int b);
+size_t compress_lds_bytes(int row_bytes, int b, bool value_gram = false);
+bool compress_value_gram_fits(int row_bytes, int b);   // keys and values of one block resident in LDS together
 hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64_t n_inst, hipStream_t st);
 hipError_t launch_fill_u32(void* p, uint32_t v, int64_t n, hipStream_t st);
 hipError_t launch_copy_rows(const void* src, void* dst, int64_t n_seq, int64_t src_seq_stride,

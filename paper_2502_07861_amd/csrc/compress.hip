@@ -61,15 +61,19 @@ static inline size_t lds_fixed_bytes(int b) {
            + 128;                        // progress counters of the panel pipeline
 }
 // rows of the block staged in LDS at a time: as many 64-row panels as fit, at most 8
-static inline int chunk_rows_for(int row_bytes, int b) {
+// (with the value factor of Alg. 2 line 5 the value rows are staged next to the key rows: twice the bytes per row)
+static inline int chunk_rows_for(int row_bytes, int b, bool value_gram = false) {
+    const int rb = value_gram ? 2 * row_bytes : row_bytes;
     int rows = 512;
-    while (rows > 64 && (size_t)rows * row_bytes + lds_fixed_bytes(b) > (size_t)kLdsLimit) rows -= 64;
+    while (rows > 64 && (size_t)rows * rb + lds_fixed_bytes(b) > (size_t)kLdsLimit) rows -= 64;
     return b < rows ? b : rows;
 }
 
-size_t compress_lds_bytes(int row_bytes, int b) {
-    return (size_t)chunk_rows_for(row_bytes, b) * row_bytes + lds_fixed_bytes(b);
+size_t compress_lds_bytes(int row_bytes, int b, bool value_gram) {
+    return (size_t)chunk_rows_for(row_bytes, b, value_gram) * (value_gram ? 2 : 1) * row_bytes + lds_fixed_bytes(b);
 }
+// the value-factor variant keeps keys and values of the whole block in LDS
+bool compress_value_gram_fits(int row_bytes, int b) { return chunk_rows_for(row_bytes, b, true) >= b; }
 
 template <typename T, int D>
 struct TileOps {
@@ -146,16 +150,44 @@ struct TileOps {
     // With BREG the column panel's fragments come from the caller's registers too (Bq), e.g. a panel that a
     // wavefront keeps for all tiles of its column.
     // With DIAG (a diagonal tile, not dumped) the quadrant rows 32..63 x columns 0..31, which the walk never uses, is skipped.
-    template <bool SUM, bool AREG, bool BREG = false, bool DIAG = false>
+    // With VG the weights carry the value factor of Alg. 2 line 5: the Gram of the value rows of the same two panels
+    // (ldsVA: the 64 rows that match the tile's rows, ldsVB: those that match its columns) is formed first, scaled by
+    // 1 / r_value^2, and multiplies every weight after its exp2.
+    template <bool SUM, bool AREG, bool BREG = false, bool DIAG = false, bool VG = false>
     static __device__ __forceinline__ float tile(floatx16 (&acc)[2][2], const Frag (*A)[2], const char* ldsA, const char* ldsB,
                                                  const float* aterm_panel, float alpha, const float* sg, const float* sgn_h,
-                                                 const int (&foff)[G::kGroups], int n, int h, const Frag (*Bq)[2] = nullptr) {
+                                                 const int (&foff)[G::kGroups], int n, int h, const Frag (*Bq)[2] = nullptr,
+                                                 const char* ldsVA = nullptr, const char* ldsVB = nullptr, float inv_rv2 = 0.f) {
         constexpr int KG = G::kGroups;
         constexpr int RPI = 16 / KG;                       // accumulator registers (per column half) finished per k-group
         constexpr int kAhead = KG < 4 ? KG : 4;              // k-groups between the request of a B fragment and its use
         static_assert(RPI >= 1 && KG >= 4, "4 to 16 k-groups per row");
         const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         float cs0 = 0.f, cs1 = 0.f;
+        floatx16 vg[2][2];                                   // value Gram / r_value^2 (VG only)
+        if constexpr (VG) {
+            const char* va = ldsVA + (size_t)n * G::kLdsRow;
+            const char* vb = ldsVB + (size_t)n * G::kLdsRow;
+            vg[0][0] = zero; vg[0][1] = zero; vg[1][0] = zero; vg[1][1] = zero;
+#pragma unroll
+            for (int g = 0; g < KG; ++g) {
+                const Frag a0 = *reinterpret_cast<const Frag*>(va + foff[g]);
+                const Frag a1 = *reinterpret_cast<const Frag*>(va + (size_t)32 * G::kLdsRow + foff[g]);
+                const Frag b0 = *reinterpret_cast<const Frag*>(vb + foff[g]);
+                const Frag b1 = *reinterpret_cast<const Frag*>(vb + (size_t)32 * G::kLdsRow + foff[g]);
+                Elem<T>::mma(vg[0][0], a0, b0);
+                Elem<T>::mma(vg[0][1], a0, b1);
+                if (!DIAG) Elem<T>::mma(vg[1][0], a1, b0);
+                Elem<T>::mma(vg[1][1], a1, b1);
+            }
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) vg[rb][cb][r] *= inv_rv2;
+            __builtin_amdgcn_sched_barrier(0);
+        }
         const char* bp0 = BREG ? nullptr : ldsB + (size_t)n * G::kLdsRow;
         const char* bp1 = BREG ? nullptr : bp0 + (size_t)32 * G::kLdsRow;
         const char* ap = AREG ? nullptr : ldsA + (size_t)n * G::kLdsRow;
@@ -179,6 +211,10 @@ struct TileOps {
         auto finish = [&](int rb, int r) {
             if (!(DIAG && rb == 1)) acc[rb][0][r] = fast_exp2(fmaf(acc[rb][0][r], alpha, at[rb][r >> 2][r & 3]));
             acc[rb][1][r] = fast_exp2(fmaf(acc[rb][1][r], alpha, at[rb][r >> 2][r & 3]));
+            if constexpr (VG) {
+                if (!(DIAG && rb == 1)) acc[rb][0][r] *= vg[rb][0][r];
+                acc[rb][1][r] *= vg[rb][1][r];
+            }
             if (SUM) {
                 cs0 = fmaf(sq[rb][r >> 2][r & 3], acc[rb][0][r], cs0);
                 cs1 = fmaf(sq[rb][r >> 2][r & 3], acc[rb][1][r], cs1);
@@ -194,6 +230,7 @@ struct TileOps {
                 } else if (step == 1) {
                     acc[rb][0][r] = fast_exp2(acc[rb][0][r]);
                     acc[rb][1][r] = fast_exp2(acc[rb][1][r]);
+                    if constexpr (VG) { acc[rb][0][r] *= vg[rb][0][r]; acc[rb][1][r] *= vg[rb][1][r]; }
                 } else if (SUM) {
                     cs0 = fmaf(sq[rb][r >> 2][r & 3], acc[rb][0][r], cs0);
                     cs1 = fmaf(sq[rb][r >> 2][r & 3], acc[rb][1][r], cs1);
@@ -475,8 +512,11 @@ __device__ __forceinline__ float await_and_read(int* counter, int value, const f
 
 // MULTI = false: the launcher guarantees b <= chunk_rows (the block is resident in LDS as one chunk), and the
 // multi-chunk code is compiled out.
-template <typename T, int D, bool EMIT_G, bool MULTI>
+// VG = true (resident blocks only): the kernel weights carry the value factor <v_i,v_j> / r_value^2 of Alg. 2 line 5;
+// the block's value rows are staged in LDS behind the key rows.
+template <typename T, int D, bool EMIT_G, bool MULTI, bool VG = false>
 __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a) {
+    static_assert(!VG || (!MULTI && !EMIT_G), "the value factor is built for resident blocks only");
     typedef Geo<T, D> G;
     typedef TileOps<T, D> Ops;
     typedef typename Elem<T>::Frag Frag;
@@ -488,7 +528,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     extern __shared__ __align__(16) char smem[];
     const int b = a.b, nP = b >> 6, CH = a.chunk_rows;
     char* ldsK = smem;
-    float* sigma = reinterpret_cast<float*>(smem + (size_t)CH * G::kLdsRow);
+    char* ldsV = smem + (size_t)CH * G::kLdsRow;                   // value rows, same layout as the keys (VG only)
+    float* sigma = reinterpret_cast<float*>(smem + (size_t)(VG ? 2 : 1) * CH * G::kLdsRow);
     float* aterm = sigma + b;                                      // -alpha * a_i; column factor = exp2(aterm)
     unsigned long long* etaMask = reinterpret_cast<unsigned long long*>(aterm + b);   // bit j of entry I: eta of token 64 I + j is +1
     float* etaF = reinterpret_cast<float*>(etaMask + 16);          // [8][2][32]: +-1 of the chunk's panel l, entry h*32 + 16*rb + r
@@ -581,6 +622,34 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         }
     };
     stage_chunk(0, min(CH, b), center ? b : 0);
+    // Value factor: the value row of every token of the block -> LDS (the row of token i is the ORIGINAL row of that
+    // token, as in the gather at the end); |v_i|^2 on the way when r_value has to be measured.
+    float vmax = 0.f;
+    if constexpr (VG) {
+        const char* Vseq = a.V + (size_t)seq * a.v_seq_stride * G::kRowBytes;
+        constexpr int U = 16;
+        for (int i0 = rg; i0 < b; i0 += RG * U) {
+            uintx4 raw[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * RG;
+                if (i < b) {
+                    const int64_t tok = a.idx_in ? (int64_t)a.idx_in[in_tok0 + i] : a.idx_base + (int64_t)blk * b + i;
+                    raw[u] = *reinterpret_cast<const uintx4*>(Vseq + (size_t)tok * G::kRowBytes + sl * 16);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * RG;
+                if (i < b) {
+                    *reinterpret_cast<uintx4*>(ldsV + (size_t)i * G::kLdsRow + G::slice_off(i, sl)) = raw[u];
+                    vmax = fmaxf(vmax, group_sum<SL>(Elem<T>::dot(raw[u], raw[u])));
+                }
+            }
+        }
+        vmax = wave_max(vmax);
+        if (lane == 0) diag[kDiagFloats - 64 + wave] = vmax;   // the tail of the buffer: beyond the mean partials
+    }
     if (center) {                        // column sums of every wavefront -> LDS
 #pragma unroll
         for (int o = SL; o < 64; o <<= 1)
@@ -594,6 +663,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             }
     }
     __syncthreads();
+    float inv_rv2 = 0.f;
     {
         // ---------------------------------------------------------- block statistics
         // mu = mean key (fp32), a_i = <k_i, mu>, A = largest centred squared norm (or r_key^2)
@@ -724,6 +794,15 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             if (lane == 0) scal[2 + wave] = amax;
         } else {
             for (int i = nres + tid; i < b; i += kThreads) aterm[i] = 0.f;
+        }
+        if constexpr (VG) {                                     // 1 / r_value^2: given, or the largest |v_i|^2 of the block
+            float r2 = a.rvalue2;
+            if (!(r2 > 0.f)) {
+                r2 = diag[kDiagFloats - 64];
+#pragma unroll
+                for (int w = 1; w < kWaves; ++w) r2 = fmaxf(r2, diag[kDiagFloats - 64 + w]);
+            }
+            inv_rv2 = r2 > 0.f ? 1.f / r2 : 0.f;               // all values zero: every weight is zero
         }
         __syncthreads();                                        // wpart (aliasing diag) is dead from here
         {
@@ -890,7 +969,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             auto diagonal = [&](const Frag (&P)[G::kGroups][2], int l) {
                 const int I = p0 + l;
                 floatx16 dv[2][2];
-                Ops::template tile<false, true, true, !EMIT_G>(dv, P, nullptr, nullptr, aterm + (I << 6), alpha, nullptr, nullptr, foff, n, h, P);
+                const char* vrows = VG ? ldsV + (size_t)(l << 6) * G::kLdsRow : nullptr;
+                Ops::template tile<false, true, true, !EMIT_G, VG>(dv, P, nullptr, nullptr, aterm + (I << 6), alpha, nullptr, nullptr, foff, n, h, P,
+                                                                   vrows, vrows, inv_rv2);
                 const float e0 = fast_exp2(aterm[(I << 6) + n] - row_const), e1 = fast_exp2(aterm[(I << 6) + 32 + n] - row_const);
                 if (EMIT_G) {
 #pragma unroll
@@ -926,7 +1007,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 for (int i = 0; i < w; ++i) {
                     const int Ii = p0 + i;
                     floatx16 acc[2][2];
-                    Ops::template tile<false, false, true>(acc, nullptr, lds_rows(i << 6), nullptr, aterm + (Ii << 6), alpha, nullptr, nullptr, foff, n, h, Bq);
+                    Ops::template tile<false, false, true, false, VG>(acc, nullptr, lds_rows(i << 6), nullptr, aterm + (Ii << 6), alpha, nullptr, nullptr, foff, n, h, Bq,
+                                                                      VG ? ldsV + (size_t)(i << 6) * G::kLdsRow : nullptr,
+                                                                      VG ? ldsV + (size_t)(w << 6) * G::kLdsRow : nullptr, inv_rv2);
                     if (EMIT_G) {
                         const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
 #pragma unroll
@@ -1116,10 +1199,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
 }
 
 // ------------------------------------------------------------------------------------------------
-template <typename T, int D, bool EMIT_G, bool MULTI>
+template <typename T, int D, bool EMIT_G, bool MULTI, bool VG = false>
 static hipError_t launch_one(const CompressArgs& a, int64_t n_inst, hipStream_t st) {
-    const size_t lds = compress_lds_bytes(Geo<T, D>::kRowBytes, a.b);
-    auto kern = compress_kernel<T, D, EMIT_G, MULTI>;
+    const size_t lds = compress_lds_bytes(Geo<T, D>::kRowBytes, a.b, VG);
+    auto kern = compress_kernel<T, D, EMIT_G, MULTI, VG>;
     static thread_local size_t configured = 0;
     if (lds > configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1132,7 +1215,10 @@ static hipError_t launch_one(const CompressArgs& a, int64_t n_inst, hipStream_t 
 
 hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64_t n_inst, hipStream_t st) {
     const int row_bytes = d * (dtype == BKV_BF16 ? 2 : 4);
-    a.chunk_rows = chunk_rows_for(row_bytes, a.b);
+    const bool vgram = (a.flags & BKV_VALUE_GRAM) != 0;
+    // value factor: keys and values of a block are resident together, no Gram dump, value rows required
+    if (vgram && (emit_g || !a.V || !compress_value_gram_fits(row_bytes, a.b))) return hipErrorInvalidValue;
+    a.chunk_rows = chunk_rows_for(row_bytes, a.b, vgram);
     if (n_inst <= 0) return hipSuccess;
     {
         // one workgroup per compute unit is resident (LDS); with at least two rounds of workgroups, spread the first
@@ -1157,7 +1243,8 @@ hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64
     if (n_inst > kMaxGrid) return hipErrorInvalidValue;
     const bool multi = a.b > a.chunk_rows;       // the Gram-emitting (test) variant always takes the general code
 #define BKV_DISPATCH(TT, DD)                                                                \
-    return emit_g ? launch_one<TT, DD, true, true>(a, n_inst, st)                           \
+    return vgram ? launch_one<TT, DD, false, false, true>(a, n_inst, st)                    \
+         : emit_g ? launch_one<TT, DD, true, true>(a, n_inst, st)                           \
                   : multi ? launch_one<TT, DD, false, true>(a, n_inst, st)                  \
                           : launch_one<TT, DD, false, false>(a, n_inst, st)
     if (dtype == BKV_BF16 && d == 128) { BKV_DISPATCH(__bf16, 128); }

@@ -15,14 +15,15 @@ def f32(x: float) -> float:
     return float(np.float32(x))
 
 
-def verify_halving(oracle, K_blocks, u, gpu_signs, *, log_c, center, r_key=0.0):
+def verify_halving(oracle, K_blocks, u, gpu_signs, *, log_c, center, r_key=0.0, V_blocks=None, r_value=0.0):
     """Feed the GPU's signs to the oracle (teacher forcing) and classify every decision.
 
     Decision j is a hard mismatch if the oracle's rule (u_j < p_j), evaluated on the GPU's own
     prefix of signs, disagrees with the GPU and |u_j - p_j| >= MARGIN; a margin case if it
-    disagrees with a smaller margin.  Returns dict(hard, margin, n, res).
+    disagrees with a smaller margin.  V_blocks: the value rows, when the weights carry the value factor.
+    Returns dict(hard, margin, n, res).
     """
-    res = oracle.softmax_balance_batch(K_blocks, u=u, log_c=log_c, r_key=r_key, center=center,
+    res = oracle.softmax_balance_batch(K_blocks, V_blocks, u=u, log_c=log_c, r_key=r_key, r_value=r_value, center=center,
                                        forced=gpu_signs)
     differ = res["dec"] != gpu_signs
     marg = np.abs(u - res["p"])

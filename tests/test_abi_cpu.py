@@ -64,7 +64,11 @@ def test_misuse_is_rejected_before_any_launch(bk):
     assert compress(bk.make_params(128, 2048, 2, bk.BKV_BF16, log_c=0.0)) == bk.BKV_ESHAPE
     assert compress(bk.make_params(128, 512, 2, 7, log_c=0.0)) == bk.BKV_ESHAPE                # dtype
     assert compress(bk.make_params(128, 512, 2, bk.BKV_BF16, log_c=0.0, strict=False)) == bk.BKV_ESHAPE
+    # value factor: only where keys and values of a block fit LDS together; the values must be given
     assert compress(bk.make_params(128, 512, 2, bk.BKV_BF16, log_c=0.0, value_gram=True)) == bk.BKV_ESHAPE
+    assert compress(bk.make_params(128, 256, 2, bk.BKV_F32, log_c=0.0, value_gram=True)) == bk.BKV_ESHAPE
+    assert compress(bk.make_params(128, 256, 2, bk.BKV_BF16, log_c=0.0, value_gram=True)) == bk.BKV_EINVAL   # V is null
+    assert L.bkv_kernel_weights(C.byref(bk.make_params(128, 256, 2, bk.BKV_BF16, log_c=0.0, value_gram=True)), one, 2, one, None) == bk.BKV_ESHAPE
     assert compress(bk.make_params(128, 512, 2, bk.BKV_BF16)) == bk.BKV_EINVAL                 # NaN log_c, no delta
     assert compress(ok, K=None) == bk.BKV_EINVAL
     assert compress(ok, K=C.c_void_p(0x1004)) == bk.BKV_EINVAL                                 # misaligned

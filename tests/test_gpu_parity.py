@@ -137,6 +137,66 @@ def test_compress_block_teacher_forced(bk, synth, oracle, dtype, d, b, n_inst, c
             assert abs(u[t, first] - free["p"][t, first]) < MARGIN
 
 
+VALUE_CASES = [
+    # dtype, d, b, n_inst, center, r_value (0: measured per block)
+    (torch.bfloat16, 128, 256, 4, True, 0.0),     # the largest block whose keys and values share LDS at d=128 bf16
+    (torch.bfloat16, 128, 128, 5, True, 0.0),
+    (torch.bfloat16, 128, 64, 7, False, 0.0),     # a single panel
+    (torch.bfloat16, 64, 512, 3, True, 0.0),      # eight panels
+    (torch.bfloat16, 64, 192, 4, False, 30.0),    # three panels, radius given
+    (torch.float32, 64, 256, 3, False, 0.0),
+    (torch.float32, 128, 128, 3, True, 25.0),
+]
+
+
+@pytest.mark.parametrize("dtype,d,b,n_inst,center,r_value", VALUE_CASES)
+@pytest.mark.parametrize("c_kind", ["one", "tuned"])
+def test_compress_block_with_value_factor(bk, synth, oracle, dtype, d, b, n_inst, center, r_value, c_kind):
+    """Alg. 2 line 5 with its value factor: weights exp(...) <v_i,v_j> / r_value^2, teacher-forced against the oracle."""
+    from oracle.tuning import tune_log_c
+    K, V = _blocks(synth, dtype, d, b, n_inst, seed=311 + b + d)
+    Kd, Vd = to_f64(K), to_f64(V)
+    if r_value > 0.0:
+        assert r_value ** 2 > (Vd ** 2).sum(-1).max() * 0.25          # a radius of the right order, not the measured one
+    log_c = 0.0 if c_kind == "one" else f32(tune_log_c(Kd[:3], target=0.25, center=center, V_blocks=Vd[:3]))
+    seed = 0x5EED + b
+    p = bk.make_params(d, b, 1, dtype, log_c=log_c, seed=seed, center=center, value_gram=True, r_value=r_value)
+    u = np.stack([oracle.uniform_fill(seed, t, 0, b) for t in range(n_inst)])
+    out = bk.compress_block(p, K, V, uniforms=torch.from_numpy(u.astype(np.float32)).cuda())
+    torch.cuda.synchronize()
+    signs = out["signs"].cpu().numpy()
+    assert set(np.unique(signs).tolist()) <= {-1, 1}
+    assert not np.any(out["status"].cpu().numpy() & 2)                # no internal error
+    v = verify_halving(oracle, Kd, u, signs, log_c=log_c, center=center, V_blocks=Vd, r_value=f32(r_value))
+    print("c=%s: %d decisions, %d within margin, %d margin flips, %d hard" % (c_kind, v["n"], v["near"], v["margin"], v["hard"]))
+    assert v["hard"] == 0
+    if c_kind == "tuned":          # (tuned with the measured radius: a given, larger one lowers the activity)
+        assert np.abs(2 * v["res"]["p"] - 1).mean() > 0.05
+        # ... and they depend on the VALUE factor: the keys-only walk on the same draws decides differently
+        keys_only = oracle.softmax_balance_batch(Kd, u=u, log_c=log_c, center=center)
+        assert np.count_nonzero(keys_only["eta"] != signs) > 0.05 * signs.size
+    idx = out["idx"].cpu().numpy()
+    np.testing.assert_array_equal(idx, expected_survivors(oracle, signs))
+    gi = torch.from_numpy(idx.astype(np.int64)).cuda()
+    assert torch.equal(out["K"], torch.gather(K, 1, gi[..., None].expand(-1, -1, d)))
+    assert torch.equal(out["V"], torch.gather(V, 1, gi[..., None].expand(-1, -1, d)))
+    stats = out["stats"].cpu().numpy()
+    np.testing.assert_allclose(stats[:, 0], np.abs(u - v["res"]["p"]).min(axis=1), atol=2e-5)
+    np.testing.assert_allclose(stats[:, 1], np.abs(v["res"]["sigma"]).max(axis=1), rtol=1e-3, atol=1e-5)
+
+
+def test_value_factor_with_zero_values_is_a_fair_coin(bk, synth, oracle):
+    """All value rows zero: every weight is zero (r_value measured as 0 must not divide), p_j = 1/2."""
+    dtype, d, b, n_inst = torch.bfloat16, 128, 128, 2
+    K, V = _blocks(synth, dtype, d, b, n_inst, seed=5)
+    V = torch.zeros_like(V)
+    p = bk.make_params(d, b, 1, dtype, log_c=0.0, seed=9, center=True, value_gram=True)
+    u = np.stack([oracle.uniform_fill(9, t, 0, b) for t in range(n_inst)])
+    out = bk.compress_block(p, K, V, uniforms=torch.from_numpy(u.astype(np.float32)).cuda())
+    np.testing.assert_array_equal(out["signs"].cpu().numpy(), np.where(u < 0.5, 1, -1).astype(np.int8))
+    assert not np.any(out["status"].cpu().numpy() & 3)
+
+
 def test_generator_on_device_equals_oracle_draws(bk, synth, oracle):
     """Internal draws (seed, stream = inst_id, ctr = j) == the same run fed the oracle's uniforms."""
     dtype, d, b, n_inst = torch.bfloat16, 128, 256, 5
@@ -199,7 +259,10 @@ def _verify_tree(bk, oracle, K, V, p, res, seq_base=0, sample=None, rng=None):
             Kb = np.stack([to_f64(K[s][torch.from_numpy(rows[i]).cuda()]) for i, (s, _) in enumerate(picks)])
         u = np.stack([oracle.uniform_fill(seed, 64 * (seq_base + s) + r, blk * b, b) for s, blk in picks])
         sg = np.stack([signs[s, blk * b:(blk + 1) * b] for s, blk in picks])
-        v = verify_halving(oracle, Kb, u, sg, log_c=log_c, center=center)
+        Vb = None
+        if p.flags & bk.BKV_VALUE_GRAM:      # the value rows of the same surviving tokens
+            Vb = np.stack([to_f64(V[s][torch.from_numpy(rows[i]).cuda()]) for i, (s, _) in enumerate(picks)])
+        v = verify_halving(oracle, Kb, u, sg, log_c=log_c, center=center, V_blocks=Vb, r_value=float(p.r_value))
         for k in tot:
             tot[k] += v[k]
         # survivors of this round from the GPU's own signs (all blocks: integer work only)
@@ -271,6 +334,31 @@ def test_merge_reduce_three_rounds_and_seq_base(bk, synth, oracle):
         from oracle.merge_reduce import merge_reduce_offline
         off = merge_reduce_offline(to_f64(K[1]), to_f64(V[1]), b=128, T=3, seed=99, seq=11, log_c=tuned, center=True)
         np.testing.assert_array_equal(off["idx"], res["idx"][1].cpu().numpy())
+
+
+def test_merge_reduce_with_value_factor(bk, synth, oracle):
+    """Three rounds with the value factor: from the second round on the value rows are found through the survivor
+    indices.  Also through the protected-window entry point and the streaming cache (same kept set)."""
+    from oracle.tuning import tune_log_c
+    dtype, d, b, T, n_seq, n = torch.bfloat16, 128, 128, 3, 3, 2048
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=n + 96, d=d, g=1, nq=1, seed=4242, device="cpu")
+    Kall, Vall = t["K"].cuda().contiguous(), t["V"].cuda().contiguous()
+    K, V = Kall[:, 32:32 + n].contiguous(), Vall[:, 32:32 + n].contiguous()
+    log_c = f32(tune_log_c(to_f64(K[0]).reshape(-1, b, d)[:3], center=True, V_blocks=to_f64(V[0]).reshape(-1, b, d)[:3]))
+    p = bk.make_params(d, b, T, dtype, log_c=log_c, seed=77, center=True, value_gram=True)
+    res = bk.merge_reduce(p, K, V, seq_base=5, emit_signs=True)
+    torch.cuda.synchronize()
+    assert not np.any(res["status"].cpu().numpy() & 2)
+    tot = _verify_tree(bk, oracle, K, V, p, res, seq_base=5)
+    print("value-factor tree:", tot)
+    # the keys-only tree keeps a different set
+    res0 = bk.merge_reduce(bk.make_params(d, b, T, dtype, log_c=log_c, seed=77, center=True), K, V, seq_base=5)
+    assert not torch.equal(res0["idx"], res["idx"])
+    # protected windows around the same rows: identical choice in between (indices shifted by the sink window)
+    prot = bk.merge_reduce_protected(p, Kall, Vall, 32, 64, seq_base=5)
+    kept = n >> T
+    assert torch.equal(prot["idx"][:, 32:32 + kept], res["idx"] + 32)
+    assert torch.equal(prot["V"][:, 32:32 + kept], res["V"]) and torch.equal(prot["K"][:, 32:32 + kept], res["K"])
 
 
 @pytest.mark.parametrize("dtype,d,b,T,n_sink,n_recent,n_mid", [
@@ -447,20 +535,24 @@ def test_end_to_end_workload1_error_vs_exact(bk, synth, oracle):
 
 
 # ------------------------------------------------------------------------------------------ a9: streaming
-def test_streaming_cache_equals_offline_tree_and_oracle(bk, synth, oracle):
+@pytest.mark.parametrize("value_gram", [False, True])
+def test_streaming_cache_equals_offline_tree_and_oracle(bk, synth, oracle, value_gram):
     """Alg. 3 on the device: sum of weights = tokens seen at every step; at multiples of b*2^T the
-    state equals the offline tree (same draws); the oracle's stream agrees when no margin case arose."""
+    state equals the offline tree (same draws); the oracle's stream agrees when no margin case arose.
+    Keys-only weights and weights with the value factor of Alg. 2 line 5."""
     from oracle.merge_reduce import MergeAndReduceStream
     from oracle.tuning import tune_log_c
     d, b, T, n_seq = 64, 64, 2, 3
     n = b * 4 * 2 + 37
     t = synth.gqa_layer_bf16(n_seq=n_seq, n=n, d=d, g=2, nq=1, seed=77, device="cpu", dtype=torch.float32)
     K, V, Q = t["K"].cuda(), t["V"].cuda(), t["Q"].cuda()
-    tuned = f32(tune_log_c(to_f64(K[:, :256]).reshape(-1, 64, 64), center=True))
-    p = bk.make_params(d, b, T, torch.float32, log_c=tuned, seed=4242, center=True)
+    tuned = f32(tune_log_c(to_f64(K[:, :256]).reshape(-1, 64, 64), center=True,
+                           V_blocks=to_f64(V[:, :256]).reshape(-1, 64, 64) if value_gram else None))
+    p = bk.make_params(d, b, T, torch.float32, log_c=tuned, seed=4242, center=True, value_gram=value_gram)
     cache = bk.Cache(p, n_seq, max_tokens=512)
     status = torch.zeros(n_seq, T, dtype=torch.int32, device="cuda")
-    streams = [MergeAndReduceStream(d, d, t=b, T=T, seed=4242, seq=s, log_c=tuned, center=True) for s in range(n_seq)]
+    streams = [MergeAndReduceStream(d, d, t=b, T=T, seed=4242, seq=s, log_c=tuned, center=True, value_gram=value_gram)
+               for s in range(n_seq)]
     Kd, Vd = to_f64(K), to_f64(V)
     Kv, Vv, wv = cache.views()
     n_carry = 0

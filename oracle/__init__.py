@@ -1,7 +1,8 @@
 """BalanceKV reference oracle -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
 
 A thin ctypes/numpy front for ``balancekv_oracle.c`` (plain C, double precision)
-plus the Alg. 3 bookkeeping in ``merge_reduce.py``.  Only ``tests/``, the smoke
+plus the Alg. 3 bookkeeping in ``merge_reduce.py`` and the bucketed two-instance
+procedure of Alg. 1 in ``balancekv.py``.  Only ``tests/``, the smoke
 check and the benchmark's ``cpu_baseline`` leg may import this package.  It
 shares nothing with the HIP library and neither imports the other.
 

@@ -499,3 +499,103 @@ def test_balancekv_beats_uniform_sampling_on_denominator(oracle):
         est_u = (2.0 ** T) * np.exp(K[pick] @ Q.T / math.sqrt(d)).sum(axis=0)
         err_u.append(np.abs(est_u - full) / full)
     assert np.mean(err_b) < 0.9 * np.mean(err_u)
+
+
+# ----------------------------------------------------------------------------- Alg. 1 (buckets, two instances)
+def test_alg1_bucket_index_brute_force():
+    """Alg. 1 line 5: 2^i >= |v| >= 2^(i-1); on a boundary the smaller i; searched by brute force over i."""
+    from oracle.balancekv import bucket_index
+    r = _rng(31)
+    norms = np.concatenate([np.exp(r.uniform(-30, 30, size=500)), 2.0 ** np.arange(-20, 21), np.nextafter(2.0 ** np.arange(-5, 6), np.inf),
+                            np.nextafter(2.0 ** np.arange(-5, 6), 0.0)])
+    for x in norms:
+        brute = min(i for i in range(-60, 61) if 2.0 ** i >= x)
+        assert bucket_index(float(x)) == brute and 2.0 ** brute >= x > 2.0 ** (brute - 1)
+    assert bucket_index(0.0) is None
+
+
+def _alg1_inputs(seed, n, d, s, scales):
+    r = _rng(seed)
+    K = 0.6 * r.normal(size=(n, d))
+    V = r.normal(size=(n, s)) * r.choice(scales, size=n)[:, None]
+    return K, V, 0.6 * r.normal(size=d)
+
+
+def test_alg1_without_compression_is_exact_attention(oracle):
+    """T = 0 and nothing erased: V^0 = K^0 = the whole stream, the output line is Eq. 1 whatever the bucketing."""
+    from oracle.balancekv import BalanceKVStream
+    n, d, s = 150, 8, 5
+    K, V, q = _alg1_inputs(3, n, d, s, [1e-3, 0.1, 1.0, 30.0])
+    st = BalanceKVStream(d, s, t=16, T=0, n_total=n)
+    for j in range(n):
+        st.append(K[j], V[j])
+    assert len(st.numerator_sets()) >= 4
+    e = np.exp(K @ q / math.sqrt(d))
+    np.testing.assert_allclose(st.estimate(q), (e / e.sum()) @ V, rtol=0, atol=1e-12)
+
+
+def test_alg1_routing_weights_and_output_line(oracle):
+    """Every token reaches exactly one numerator bucket (by its norm) and the denominator instance; level weights add
+    up to the tokens routed (Thm 3.3: level-l tokens weigh 2^l); a bucket is the MergeAndReduce run on its own
+    sub-stream with value radius 2^i; the output line is the ratio of the two weighted sums, written out here."""
+    from oracle.balancekv import BalanceKVStream, bucket_index
+    from oracle.merge_reduce import MergeAndReduceStream
+    n, d, s, t, T = 700, 6, 4, 16, 2
+    K, V, q = _alg1_inputs(8, n, d, s, [0.05, 1.0, 7.0])
+    st = BalanceKVStream(d, s, t=t, T=T, n_total=n, seed=9, seq=3, log_c=-2.0, center=True)
+    for j in range(n):
+        st.append(K[j], V[j])
+    sets = st.numerator_sets()
+    norms = np.linalg.norm(V, axis=1)
+    which = np.array([bucket_index(float(x)) for x in norms])
+    assert sorted(sets) == sorted(set(which.tolist()))
+    seen = []
+    for i, (idx, w) in sets.items():
+        members = np.flatnonzero(which == i)
+        assert set(idx.tolist()) <= set(members.tolist()) and w.sum() == members.size
+        assert np.all(norms[idx] <= 2.0 ** i) and np.all(norms[idx] > 2.0 ** (i - 1))
+        # the bucket's instance on its own sub-stream
+        alone = MergeAndReduceStream(d, s, t=t, T=T, seed=9, seq=512 * 3 + 256 + i, log_c=-2.0, center=True, value_gram=True, r_value=2.0 ** i)
+        for j in members:
+            alone.append(K[j], V[j])
+        ia, wa = alone.flat()
+        np.testing.assert_array_equal(members[ia], idx)
+        np.testing.assert_array_equal(wa, w)
+        assert idx.size < members.size or members.size < t          # buckets with a full block were compressed
+        seen.append(idx)
+    idx_d, w_d = st.denominator_set()
+    assert w_d.sum() == n and idx_d.size == (n // (t << T)) * (t << T) // (1 << T) + sum(
+        (t // 2) * ((n % (t << T)) // t >> l & 1) for l in range(T)) + n % t
+    # output line from the sets, plain sums
+    sd = math.sqrt(d)
+    num = sum((w * np.exp(K[idx] @ q / sd)) @ V[idx] for idx, w in sets.values())
+    den = (w_d * np.exp(K[idx_d] @ q / sd)).sum()
+    np.testing.assert_allclose(st.estimate(q), num / den, rtol=1e-12, atol=1e-14)
+
+
+def test_alg1_erase_rule(oracle):
+    """Alg. 1 line 8: buckets with 2^i <= eps/(2n) e^{-r^2/sqrt d} v_max are dropped.  Each dropped token adds at most
+    e^{r^2/sqrt d} 2^i to the numerator, so the numerator changes by at most (eps/2) v_max; the denominator is at
+    least n e^{-r^2/sqrt d}; hence the output moves by at most (eps/2) v_max e^{r^2/sqrt d} / n (and does move)."""
+    from oracle.balancekv import BalanceKVStream, bucket_index
+    n, d, s = 200, 8, 4
+    r_ = _rng(12)
+    K = r_.normal(size=(n, d))
+    K *= 1.5 / np.maximum(np.linalg.norm(K, axis=1, keepdims=True), 1.5)
+    q = K[5].copy()
+    radius = 1.5
+    V = r_.normal(size=(n, s))
+    tiny = r_.choice(n, size=60, replace=False)
+    V[tiny] *= 1e-9
+    eps = 1e-3
+    kept, cut = (BalanceKVStream(d, s, t=16, T=0, n_total=n, eps=e, r=radius) for e in (0.0, eps))
+    for j in range(n):
+        kept.append(K[j], V[j])
+        cut.append(K[j], V[j])
+    v_max = np.linalg.norm(V, axis=1).max()
+    thr = eps / (2 * n) * math.exp(-radius ** 2 / math.sqrt(d)) * v_max
+    gone = {bucket_index(float(np.linalg.norm(v))) for v in V[tiny]}
+    assert all(2.0 ** i <= thr for i in gone) and gone.isdisjoint(cut.numerator_sets()) and gone <= set(kept.numerator_sets())
+    assert set(cut.numerator_sets()) == set(kept.numerator_sets()) - gone
+    err = np.linalg.norm(cut.estimate(q) - kept.estimate(q))
+    assert 0.0 < err <= 0.5 * eps * v_max * math.exp(radius ** 2 / math.sqrt(d)) / n

@@ -170,6 +170,51 @@ int bkv_attend_kv(const bkv_params* p, const void* K_c, const void* V_c, const f
                   int32_t nq, void* out, float* lse_out, void* workspace, size_t ws_bytes,
                   void* hip_stream);
 
+/* ---- Alg. 1 as listed: value-norm buckets, MR-Numerator_i per bucket, MR-Denominator ---------------
+ * Offline form on K, V [n_seq, n, d] (any n >= 0): every instance is brought to the state Alg. 3
+ * (MergeAndReduce) holds after its last token -- full blocks halved level by level, at most one half
+ * block left at each level 1..T-1 (weight 2^l), the level-T survivors (weight 2^T) and a tail of fewer
+ * than `block` tokens (weight 1).
+ *   which = BKV_SET_NUMERATOR   Alg. 1 lines 5-10: token j goes to bucket i, the smallest i with
+ *           2^i >= |v_j| (|v_j|^2 accumulated in fp32; i is clamped to [-60, 60]); every bucket is an
+ *           instance with the value factor of Alg. 2 line 5 and r_value = 2^i; buckets with
+ *           2^i <= eps/(2n) e^{-r^2/sqrt d} max_j |v_j| are erased (line 8; eps <= 0: none).  Rows with
+ *           a zero or non-finite norm belong to no bucket.  The result is the union of the buckets'
+ *           sets V^l, bucket by bucket in ascending i.  Needs a block for which BKV_VALUE_GRAM is
+ *           built (else BKV_ESHAPE); the flag itself need not be set in p.
+ *   which = BKV_SET_DENOMINATOR lines 11-12: one keys-only instance per sequence (the sets K^l).
+ * Draws: instance q = 512 (seq_base + seq) + slot, slot = 0 for the denominator and 256 + i for bucket
+ * i; decision j of the blk-th block reaching level l of instance q draws uniform(seed, 64 q + l,
+ * blk*block + j).
+ * Outputs (device): K_out, V_out [n_seq, capacity, d] or NULL; w_out [n_seq, capacity] fp32 or NULL
+ * (0 beyond the count); idx_out [n_seq, capacity] int32 or NULL (original index of every kept token);
+ * count_out [n_seq] int32 or NULL: tokens kept per sequence -- if it exceeds `capacity` the surplus was
+ * not written (bkv_sets_capacity gives a bound).  slot_out [n_seq, n] int32 or NULL: slot of every token
+ * (511: in no bucket).  signs_out int8 or NULL: eta of every halving, round r at offset
+ * n_seq * sum_{r' < r} (n >> r') in the coordinates of that round's input [n_seq, n >> r]: the segment
+ * of slot s that starts at position p of the slot-ordered sequence occupies positions from p >> r.
+ * status_out [n_seq, max(rounds,1)] int32 or NULL as in bkv_merge_reduce (cleared here).
+ * One host-independent pass: no count travels to the host, grids are upper bounds.                 */
+#define BKV_SET_NUMERATOR   1
+#define BKV_SET_DENOMINATOR 0
+int64_t bkv_sets_capacity(const bkv_params* p, int64_t n, int32_t max_buckets);
+size_t bkv_balancekv_sets_workspace_bytes(const bkv_params* p, int64_t n_seq, int64_t n, int64_t capacity);
+int bkv_balancekv_sets(const bkv_params* p, int32_t which, const void* K, const void* V, int64_t n_seq,
+                       int64_t n, int64_t seq_base, float eps, float r, void* K_out, void* V_out,
+                       float* w_out, int32_t* idx_out, int64_t capacity, int32_t* count_out,
+                       int32_t* slot_out, int8_t* signs_out, int32_t* status_out, void* workspace,
+                       size_t ws_bytes, void* hip_stream);
+
+/* Alg. 1 output line with separate sets: the numerator sum over (K_n, V_n, w_n) divided by the
+ * denominator sum over (K_d, w_d); layouts as in bkv_attend_kv, each set with its own count and
+ * stride.  lse_out: natural log of the denominator sum.  count_d == 0 with count_n > 0: BKV_EINVAL. */
+size_t bkv_attend_sets_workspace_bytes(const bkv_params* p, int64_t n_seq, int32_t g, int32_t nq);
+int bkv_attend_sets(const bkv_params* p, const void* K_n, const void* V_n, const float* w_n,
+                    int64_t count_n, int64_t stride_n, const void* K_d, const float* w_d,
+                    int64_t count_d, int64_t stride_d, int64_t n_seq, const void* Q, int32_t g,
+                    int32_t nq, void* out, float* lse_out, void* workspace, size_t ws_bytes,
+                    void* hip_stream);
+
 /* ---- Alg. 3 streaming: the levels C^0..C^T of n_seq sequences --------------------------------------
  * The levels of one sequence live in one flat array, highest level first: level-T survivors, then
  * levels T-1..1 (each empty or block/2 tokens), then the raw tail C^0.  A carry halves the last

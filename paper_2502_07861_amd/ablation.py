@@ -1,6 +1,6 @@
 """Ablation grid of the paper's single-layer study on synthetic data (one GPU).
 
-    python -m paper_2502_07861_amd.ablation [--seeds 10] [--json] [--value-factor]
+    python -m paper_2502_07861_amd.ablation [--seeds 10] [--json] [--value-factor | --alg1]
 
 For block sizes b in {256, 128, 64} and compression rates 2^-T in {1/2, 1/4, 1/8} (the grid of the runtime /
 relative-error tables in "Ablation Studies on Single Layer Attention Approximation", arXiv 2502.07861): the first
@@ -122,6 +122,67 @@ def run(seeds=10, blocks=BLOCKS, rounds=ROUNDS, n_mid=N_MID, n_seq=8, device="cu
                 **(dict(K=K, V=V, Q=Q, exact=exact) if keep_outputs else {}))
 
 
+def heavy_tailed(V, seed=77):
+    """Value rows rescaled by 2^U(-3.5, 3.5) per token: norms spread over about eight buckets of Alg. 1 line 5."""
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed)
+    scale = torch.exp2(torch.rand(V.shape[0], V.shape[1], generator=gen) * 7.0 - 3.5).to(V.device)
+    return (V.float() * scale[..., None]).to(V.dtype)
+
+
+def run_alg1(seeds=5, block=128, rounds=ROUNDS, n=8192, n_seq=8, device="cuda", nq=64):
+    """Alg. 1 as listed (value-norm buckets with one numerator instance each + the keys-only denominator instance, two
+    kept sets) next to the single keys-only set and to uniform sampling, on values with heavy-tailed norms.  Per
+    rate: time of building the two sets, time of the two-set output line, relative errors."""
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=n, d=128, g=4, nq=nq, seed=SEED_DATA, device="cpu")
+    K, Q = t["K"].to(device).contiguous(), t["Q"].to(device).contiguous()
+    V = heavy_tailed(t["V"]).to(device).contiguous()
+    d = K.shape[2]
+    p0 = binding.make_params(d, block, 0, K.dtype, log_c=0.0, seed=0, center=True)
+    exact, _ = binding.attend_kv(p0, K, V, torch.ones(n_seq, n, device=device, dtype=torch.float32), Q)
+    rows = []
+    for T in rounds:
+        acc = dict(sets_ms=[], attend_ms=[], alg1=[], single=[], uniform=[], kept_num=[], kept_den=[])
+        for s in range(seeds + 1):
+            pk = binding.make_params(d, block, T, K.dtype, log_c=LOG_C[block], seed=500 + s, center=True)
+            pv = binding.make_params(d, block, T, K.dtype, log_c=LOG_C_VALUE[block], seed=500 + s, center=True)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            ev[0].record()
+            num = binding.balancekv_sets(pv, binding.BKV_SET_NUMERATOR, K, V, max_buckets=16, emit_slots=False)
+            den = binding.balancekv_sets(pk, binding.BKV_SET_DENOMINATOR, K, V, emit_slots=False)
+            ev[1].record()
+            z, _ = binding.attend_sets(pk, (num["K"], num["V"], num["w"]), (den["K"], den["w"]), Q)
+            ev[2].record()
+            one = binding.merge_reduce(pk, K, V)
+            z1, _ = binding.attend_kv(pk, one["K"], one["V"], one["w"], Q)
+            idx_u, w_u = uniform_sample_protected(n_seq, n, 0, 0, T, 9000 + s, device)
+            gi = idx_u[..., None].expand(-1, -1, d)
+            zu, _ = binding.attend_kv(pk, torch.gather(K, 1, gi), torch.gather(V, 1, gi), w_u, Q)
+            torch.cuda.synchronize()
+            if s == 0:
+                continue
+            acc["sets_ms"].append(ev[0].elapsed_time(ev[1])); acc["attend_ms"].append(ev[1].elapsed_time(ev[2]))
+            acc["alg1"].append(relative_error(z, exact)); acc["single"].append(relative_error(z1, exact))
+            acc["uniform"].append(relative_error(zu, exact))
+            acc["kept_num"].append(float(num["count"].float().mean())); acc["kept_den"].append(float(den["count"].float().mean()))
+        m = {k: float(torch.tensor(v).mean()) for k, v in acc.items()}
+        m.update({k + "_std": float(torch.tensor(acc[k]).std()) for k in ("alg1", "single", "uniform")})
+        m.update(rate="1/%d" % (1 << T), block=block)
+        rows.append(m)
+    return dict(workload="%d KV sequences x %d tokens, d=%d, 4 x %d queries, bf16, synthetic, value norms x 2^U(-3.5,3.5)"
+                         % (n_seq, n, d, nq), seeds=seeds, rows=rows)
+
+
+def alg1_table(result):
+    lines = ["| block | rate | kept (numerator / denominator set) | build sets ms | two-set attend ms | Alg. 1 rel. err | one keys-only set | uniform |",
+             "|---|---|---|---|---|---|---|---|"]
+    for r in result["rows"]:
+        lines.append("| %d | %s | %.0f / %.0f | %.3f | %.3f | %.4f ± %.4f | %.4f ± %.4f | %.4f ± %.4f |"
+                     % (r["block"], r["rate"], r["kept_num"], r["kept_den"], r["sets_ms"], r["attend_ms"], r["alg1"], r["alg1_std"],
+                        r["single"], r["single_std"], r["uniform"], r["uniform_std"]))
+    return "\n".join(lines)
+
+
 def as_table(result):
     lines = ["| block | rate | kept | compress ms | BalanceKV rel. err | uniform rel. err | BalanceKV normaliser err | uniform normaliser err |",
              "|---|---|---|---|---|---|---|---|"]
@@ -138,11 +199,16 @@ def main(argv=None):
     ap.add_argument("--seeds", type=int, default=10)
     ap.add_argument("--json", action="store_true", help="print one JSON line instead of the table")
     ap.add_argument("--value-factor", action="store_true", help="kernel weights times <v_i,v_j>/r_value^2 (Alg. 2 line 5)")
+    ap.add_argument("--alg1", action="store_true", help="Alg. 1 as listed (buckets, two kept sets) on heavy-tailed value norms")
     args = ap.parse_args(argv)
     if not torch.cuda.is_available():
         print("ablation: needs a GPU", file=sys.stderr)
         return 2
     binding.lib()
+    if args.alg1:
+        result = run_alg1(seeds=args.seeds)
+        print(json.dumps(result) if args.json else result["workload"] + ", %d seeds\n" % result["seeds"] + alg1_table(result))
+        return 0
     result = run(seeds=args.seeds, value_gram=args.value_factor)
     if args.json:
         print(json.dumps(result))

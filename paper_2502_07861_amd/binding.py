@@ -51,6 +51,13 @@ _SIGNATURES = {
     "bkv_merge_reduce_protected": (C.c_int, [_PP, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bkv_attend_workspace_bytes": (_sz, [_PP, _i64, _i64, _i32, _i32]),
     "bkv_attend_kv": (C.c_int, [_PP, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
+    "bkv_sets_capacity": (_i64, [_PP, _i64, _i32]),
+    "bkv_balancekv_sets_workspace_bytes": (_sz, [_PP, _i64, _i64, _i64]),
+    "bkv_balancekv_sets": (C.c_int, [_PP, _i32, _vp, _vp, _i64, _i64, _i64, C.c_float, C.c_float, _vp, _vp, _vp, _vp, _i64,
+                                     _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bkv_attend_sets_workspace_bytes": (_sz, [_PP, _i64, _i32, _i32]),
+    "bkv_attend_sets": (C.c_int, [_PP, _vp, _vp, _vp, _i64, _i64, _vp, _vp, _i64, _i64, _i64, _vp, _i32, _i32, _vp, _vp,
+                                  _vp, _sz, _vp]),
     "bkv_cache_bytes": (_sz, [_PP, _i64, _i64]),
     "bkv_cache_init": (C.c_int, [C.POINTER(_vp), _PP, _i64, _i64, _vp, _sz, _vp]),
     "bkv_cache_load": (C.c_int, [_vp, _vp, _vp, _vp, _i64, _vp]),
@@ -237,6 +244,64 @@ def attend_kv(p, K_c, V_c, w, Q, *, count=None, workspace=None, out=None, lse=Tr
                              workspace.numel(), _stream())
     _check(rc, "bkv_attend_kv")
     return out, lse_t
+
+
+# ------------------------------------------------------------------------------------------ Alg. 1: buckets, two instances
+BKV_SET_NUMERATOR, BKV_SET_DENOMINATOR = 1, 0
+
+
+def balancekv_sets(p, which, K, V, *, seq_base=0, eps=0.0, r=0.0, capacity=None, max_buckets=8, emit_signs=False,
+                   emit_slots=True, workspace=None):
+    """bkv_balancekv_sets on K, V [n_seq, n, d]: the kept set of the bucketed numerator instances (which = 1) or of the
+    keys-only denominator instance (which = 0).  Returns dict(K, V, w, idx [n_seq, capacity], count [n_seq], slot
+    [n_seq, n], signs (list per round, [n_seq, n >> r]), status)."""
+    dt = _torch_dtype(p)
+    n_seq, n, d = K.shape
+    dev = K.device
+    T = p.rounds
+    if capacity is None:
+        capacity = int(lib().bkv_sets_capacity(C.byref(p), n, max_buckets if which == BKV_SET_NUMERATOR else 1))
+    res = dict(K=torch.empty(n_seq, capacity, d, device=dev, dtype=dt), V=torch.empty(n_seq, capacity, d, device=dev, dtype=dt),
+               w=torch.empty(n_seq, capacity, device=dev, dtype=torch.float32),
+               idx=torch.empty(n_seq, capacity, device=dev, dtype=torch.int32),
+               count=torch.empty(n_seq, device=dev, dtype=torch.int32),
+               slot=torch.empty(n_seq, n, device=dev, dtype=torch.int32) if emit_slots else None,
+               status=torch.empty(n_seq, max(T, 1), device=dev, dtype=torch.int32))
+    sizes = [n_seq * (n >> r_) for r_ in range(T)]
+    signs_flat = torch.zeros(max(sum(sizes), 1), device=dev, dtype=torch.int8) if emit_signs else None
+    need = int(lib().bkv_balancekv_sets_workspace_bytes(C.byref(p), n_seq, n, capacity))
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), device=dev, dtype=torch.uint8)
+    rc = lib().bkv_balancekv_sets(C.byref(p), which, _ptr(K, dt, "K"), _ptr(V, dt, "V"), n_seq, n, seq_base, float(eps), float(r),
+                                  _ptr(res["K"]), _ptr(res["V"]), _ptr(res["w"]), _ptr(res["idx"]), capacity, _ptr(res["count"]),
+                                  _ptr(res["slot"]), _ptr(signs_flat), _ptr(res["status"]), _ptr(workspace), workspace.numel(),
+                                  _stream())
+    _check(rc, "bkv_balancekv_sets")
+    if emit_signs:
+        res["signs"], off = [], 0
+        for r_ in range(T):
+            res["signs"].append(signs_flat[off:off + sizes[r_]].view(n_seq, n >> r_))
+            off += sizes[r_]
+    return res
+
+
+def attend_sets(p, num, den, Q, *, count_n=None, count_d=None, workspace=None):
+    """bkv_attend_sets: numerator sum over num = (K, V, w), denominator sum over den = (K, w); Q [n_seq, g, nq, d].
+    Returns (out, ln of the denominator sum)."""
+    dt = _torch_dtype(p)
+    Kn, Vn, wn = num
+    Kd, wd = den
+    n_seq, g, nq, d = Q.shape
+    out = torch.empty(n_seq, g, nq, d, device=Q.device, dtype=dt)
+    lse = torch.empty(n_seq, g, nq, device=Q.device, dtype=torch.float32)
+    if workspace is None:
+        workspace = torch.empty(int(lib().bkv_attend_sets_workspace_bytes(C.byref(p), n_seq, g, nq)), device=Q.device, dtype=torch.uint8)
+    rc = lib().bkv_attend_sets(C.byref(p), _ptr(Kn, dt, "K_n"), _ptr(Vn, dt, "V_n"), _ptr(wn, torch.float32, "w_n"),
+                               Kn.shape[1] if count_n is None else count_n, Kn.shape[1], _ptr(Kd, dt, "K_d"),
+                               _ptr(wd, torch.float32, "w_d"), Kd.shape[1] if count_d is None else count_d, Kd.shape[1], n_seq,
+                               _ptr(Q, dt, "Q"), g, nq, _ptr(out), _ptr(lse), _ptr(workspace), workspace.numel(), _stream())
+    _check(rc, "bkv_attend_sets")
+    return out, lse
 
 
 # ------------------------------------------------------------------------------------------ Alg. 3 streaming

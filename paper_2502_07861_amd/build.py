@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbalancekv.so")
-SOURCES = ["compress.hip", "attend.hip", "api.hip"]
+SOURCES = ["compress.hip", "attend.hip", "sets.hip", "api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 instruction selection
          "-Wno-unused-command-line-argument"]

@@ -328,6 +328,103 @@ int bkv_attend_kv(const bkv_params* p, const void* K_c, const void* V_c, const f
     return e == hipSuccess ? BKV_OK : hip_fail(e);
 }
 
+// ------------------------------------------------------------------------------------------ Alg. 1: buckets, two instances
+int64_t bkv_sets_capacity(const bkv_params* p, int64_t n, int32_t max_buckets) {
+    if (check_params(p) || n < 0 || max_buckets < 1) return 0;
+    // per instance: level-T survivors (at most its share of n >> T), one half block per level below, a tail < block
+    const int64_t per = (int64_t)p->block + (int64_t)(p->rounds > 1 ? p->rounds - 1 : 0) * (p->block / 2);
+    const int64_t cap = (n >> p->rounds) + (int64_t)max_buckets * per;
+    return cap < n ? cap : n;
+}
+
+size_t bkv_balancekv_sets_workspace_bytes(const bkv_params* p, int64_t n_seq, int64_t n, int64_t capacity) {
+    if (check_params(p) || n_seq < 0 || n < 0 || capacity < 0) return 0;
+    return bkv::sets_workspace_bytes(row_bytes(p), p->block, n_seq, n) + align_up((size_t)n_seq * capacity * 4, 256) +
+           align_up((size_t)n_seq * 4, 256) + 256;
+}
+
+int bkv_balancekv_sets(const bkv_params* p_in, int32_t which, const void* K, const void* V, int64_t n_seq, int64_t n,
+                       int64_t seq_base, float eps, float r, void* K_out, void* V_out, float* w_out, int32_t* idx_out,
+                       int64_t capacity, int32_t* count_out, int32_t* slot_out, int8_t* signs_out, int32_t* status_out,
+                       void* workspace, size_t ws_bytes, void* hip_stream) {
+    if (!p_in) return BKV_EINVAL;
+    if (which != BKV_SET_NUMERATOR && which != BKV_SET_DENOMINATOR) return BKV_EINVAL;
+    bkv_params p = *p_in;
+    p.flags = which == BKV_SET_NUMERATOR ? (p.flags | BKV_VALUE_GRAM) : (p.flags & ~BKV_VALUE_GRAM);
+    int rc = check_params(&p);
+    if (rc) return rc;
+    if (n_seq < 0 || n < 0 || seq_base < 0 || capacity < 0 || !(r >= 0.f)) return BKV_EINVAL;
+    if (n > (1ll << 30) || n_seq > 65535 || n_seq * (n / p.block + 1) > (1ll << 30)) return BKV_ESHAPE;
+    if (n_seq == 0) return BKV_OK;
+    if (n > 0 && (!K || !aligned16(K))) return BKV_EINVAL;
+    if (n > 0 && (which == BKV_SET_NUMERATOR || V_out) && (!V || !aligned16(V))) return BKV_EINVAL;
+    if ((K_out && !aligned16(K_out)) || (V_out && !aligned16(V_out))) return BKV_EINVAL;
+    const size_t need = bkv_balancekv_sets_workspace_bytes(&p, n_seq, n, capacity);
+    if (!workspace || ws_bytes < need || !aligned16(workspace)) return BKV_EWORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipError_t e;
+    const int T = p.rounds;
+    if (status_out && (e = bkv::launch_fill_u32(status_out, 0u, n_seq * (T > 0 ? T : 1), st)) != hipSuccess) return hip_fail(e);
+    bkv::SetsArgs q;
+    memset(&q, 0, sizeof(q));
+    fill_common(q.common, &p);
+    q.K = (const char*)K; q.V = (const char*)V;
+    q.n_seq = n_seq; q.n = n; q.seq_base = seq_base; q.capacity = capacity;
+    q.dtype = p.dtype; q.d = p.d; q.row_bytes = row_bytes(&p); q.b = p.block; q.T = T;
+    q.numerator = which == BKV_SET_NUMERATOR;
+    q.erase2 = 0.f;
+    if (eps > 0.f && n > 0) {
+        const double f = (double)eps / (2.0 * (double)n) * exp(-(double)r * (double)r / sqrt((double)p.d));
+        q.erase2 = (float)(f * f);
+    }
+    q.K_out = (char*)K_out; q.V_out = (char*)V_out; q.w_out = w_out;
+    char* ws = (char*)workspace;
+    q.idx_ws = idx_out;
+    if (!q.idx_ws) { q.idx_ws = (int32_t*)ws; }
+    ws += align_up((size_t)n_seq * capacity * 4, 256);
+    q.count_out = count_out;
+    if (!q.count_out) { q.count_out = (int32_t*)ws; }
+    ws += align_up((size_t)n_seq * 4, 256);
+    q.slot_out = slot_out; q.signs_out = signs_out; q.status_out = status_out;
+    q.workspace = ws;
+    e = bkv::run_sets(q, st);
+    return e == hipSuccess ? BKV_OK : hip_fail(e);
+}
+
+size_t bkv_attend_sets_workspace_bytes(const bkv_params* p, int64_t n_seq, int32_t g, int32_t nq) {
+    if (check_params(p) || n_seq < 0 || g <= 0 || nq <= 0) return 0;
+    const size_t rows = (size_t)n_seq * g * nq;
+    return align_up(bkv::attend_workspace_bytes(p->d, n_seq, g * nq), 256) + 2 * align_up(rows * 4, 256) +
+           align_up(rows * (size_t)row_bytes(p), 256);
+}
+
+int bkv_attend_sets(const bkv_params* p, const void* K_n, const void* V_n, const float* w_n, int64_t count_n, int64_t stride_n,
+                    const void* K_d, const float* w_d, int64_t count_d, int64_t stride_d, int64_t n_seq, const void* Q,
+                    int32_t g, int32_t nq, void* out, float* lse_out, void* workspace, size_t ws_bytes, void* hip_stream) {
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (n_seq < 0 || g <= 0 || nq <= 0 || count_n < 0 || count_d < 0) return BKV_EINVAL;
+    if (count_d == 0 && count_n > 0) return BKV_EINVAL;
+    if (n_seq == 0) return BKV_OK;
+    const size_t need = bkv_attend_sets_workspace_bytes(p, n_seq, g, nq);
+    if (!workspace || ws_bytes < need || !aligned16(workspace)) return BKV_EWORKSPACE;
+    const size_t rows = (size_t)n_seq * g * nq;
+    char* ws = (char*)workspace;
+    void* att_ws = ws;
+    const size_t att_bytes = align_up(bkv::attend_workspace_bytes(p->d, n_seq, g * nq), 256);
+    ws += att_bytes;
+    float* lse_n = (float*)ws; ws += align_up(rows * 4, 256);
+    float* lse_d = (float*)ws; ws += align_up(rows * 4, 256);
+    void* scratch = ws;
+    // numerator sum / its own normaliser, then the normaliser of the denominator set (its keys stand in for values)
+    rc = bkv_attend_kv(p, K_n, V_n, w_n, n_seq, count_n, stride_n, Q, g, nq, out, lse_n, att_ws, att_bytes, hip_stream);
+    if (rc) return rc;
+    rc = bkv_attend_kv(p, K_d, K_d, w_d, n_seq, count_d, stride_d, Q, g, nq, scratch, lse_out ? lse_out : lse_d, att_ws, att_bytes, hip_stream);
+    if (rc) return rc;
+    hipError_t e = bkv::launch_rescale(p->dtype, out, lse_n, lse_out ? lse_out : lse_d, (int64_t)rows, p->d, (hipStream_t)hip_stream);
+    return e == hipSuccess ? BKV_OK : hip_fail(e);
+}
+
 // ------------------------------------------------------------------------------------------ Alg. 3 streaming
 size_t bkv_cache_bytes(const bkv_params* p, int64_t n_seq, int64_t max_tokens) {
     if (check_params(p) || n_seq <= 0 || max_tokens < p->block) return 0;

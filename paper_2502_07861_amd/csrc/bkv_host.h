@@ -8,6 +8,18 @@
 
 namespace bkv {
 
+// One instance of a ragged launch (blocks of segments of different lengths, see sets.hip): where its block starts in
+// the round's input and output buffers (tokens from the buffers' bases; idx_out and signs_out use the same
+// coordinates as K_out and K), its sequence (value rows, status word), its generator stream and first counter, and
+// r_value^2 (<= 0: as in CompressArgs).  valid = 0: the slot of the grid is not in use.
+struct InstDesc {
+    int64_t in_tok, out_tok;
+    uint64_t stream, ctr0;
+    int32_t seq, valid;
+    float rvalue2;
+    int32_t pad;
+};
+
 struct CompressArgs {
     const char* K;            // input keys, dtype T
     const char* V;            // input values or null
@@ -21,6 +33,7 @@ struct CompressArgs {
     float* stats_out;
     const uint64_t* inst_ids;
     const float* uniforms;
+    const InstDesc* desc;     // ragged launches: per-instance coordinates (then blocks_per_seq, strides and bases are not read)
     float* G_out;             // kernel-weight dump (EMIT_G variant only)
     int64_t in_seq_stride;    // tokens between consecutive sequences in K / V / idx_in
     int64_t out_seq_stride;   // tokens between consecutive sequences in K_out / V_out / w_out
@@ -78,6 +91,29 @@ inline hipError_t launch_timed(int kind, int64_t units, Kern kern, dim3 grid, di
     else hipLaunchKernelGGL(kern, grid, block, lds, st, args...);
     return hipGetLastError();
 }
+
+// Alg. 1's kept sets (sets.hip): value-norm buckets with one MergeAndReduce instance each (numerator = 1), or the
+// keys-only instance over the whole sequence (numerator = 0), brought to the state Alg. 3 reaches after the last token.
+struct SetsArgs {
+    const char* K;            // [n_seq, n, d]
+    const char* V;
+    int64_t n_seq, n, seq_base, capacity;
+    int32_t dtype, d, row_bytes, b, T, numerator;
+    float erase2;             // (eps / (2n) * exp(-r^2 / sqrt d))^2, 0: nothing is erased
+    CompressArgs common;      // flags, seed, alpha, cterm, radii
+    char* K_out;              // [n_seq, capacity, d] or null
+    char* V_out;
+    float* w_out;             // [n_seq, capacity]: 2^level, 0 beyond the count
+    int32_t* idx_ws;          // [n_seq, capacity]: original index of every kept token (required)
+    int32_t* count_out;       // [n_seq] (required)
+    int32_t* slot_out;        // [n_seq, n] or null
+    int8_t* signs_out;        // rounds one after the other, round r at the coordinates of its level-r buffer [n_seq, n >> r]
+    int32_t* status_out;      // [n_seq, T]
+    void* workspace;
+};
+size_t sets_workspace_bytes(int row_bytes, int b, int64_t n_seq, int64_t n);
+hipError_t run_sets(const SetsArgs& q, hipStream_t st);
+hipError_t launch_rescale(int dtype, void* out, const float* lse_num, const float* lse_den, int64_t rows, int d, hipStream_t st);
 
 struct AttendArgs {
     const char* K;            // [n_seq, stride_tokens, d]

@@ -543,10 +543,24 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: roles branch on scalars
     const int n = lane & 31, h = lane >> 5;
     const int64_t inst = blockIdx.x;
-    const int64_t seq = inst / a.blocks_per_seq;
+    int64_t seq = inst / a.blocks_per_seq;
     const int blk = (int)(inst - seq * a.blocks_per_seq);
-    const int64_t in_tok0 = seq * a.in_seq_stride + (int64_t)blk * b;          // first input token
-    const int64_t out_tok0 = seq * a.out_seq_stride + (int64_t)blk * (b / 2);  // first output token
+    int64_t in_tok0 = seq * a.in_seq_stride + (int64_t)blk * b;                // first input token
+    int64_t out_tok0 = seq * a.out_seq_stride + (int64_t)blk * (b / 2);        // first output token
+    int64_t idx_out0 = seq * a.idx_out_seq_stride + (int64_t)blk * (b / 2);    // first entry of idx_out
+    int64_t signs0 = inst * b;                                                 // first entry of signs_out
+    // generator stream and first counter of this instance
+    uint64_t stream = a.tree_mode ? (uint64_t)(64 * (a.seq_base + seq) + a.round) : (uint64_t)inst;
+    if (a.inst_ids) stream = a.inst_ids[inst];
+    uint64_t ctr0 = a.tree_mode ? (uint64_t)(a.blk_base + blk) * (uint64_t)b : 0ull;
+    float rvalue2 = a.rvalue2;
+    if (a.desc) {                               // ragged launches: every coordinate of the instance comes from a table
+        const InstDesc ds = a.desc[inst];
+        if (!ds.valid) return;                  // the grid is an upper bound; uniform for the workgroup, before any barrier
+        seq = ds.seq; in_tok0 = ds.in_tok; out_tok0 = ds.out_tok; idx_out0 = ds.out_tok; signs0 = ds.in_tok;
+        stream = ds.stream; ctr0 = ds.ctr0;
+        if (ds.rvalue2 > 0.f) rvalue2 = ds.rvalue2;
+    }
     const char* Kin = a.K + in_tok0 * G::kRowBytes;
     const int sl = tid % SL, rg = tid / SL;
     const bool center = (a.flags & BKV_CENTER_KEYS) != 0;
@@ -564,11 +578,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         while (__builtin_amdgcn_s_memtime() - t0 < wait) __builtin_amdgcn_s_sleep(32);
     }
 
-    // generator stream of this instance
-    uint64_t stream = a.tree_mode ? (uint64_t)(64 * (a.seq_base + seq) + a.round) : (uint64_t)inst;
-    if (a.inst_ids) stream = a.inst_ids[inst];
     const uint64_t key = stream_key(a.seed, stream);
-    const uint64_t ctr0 = a.tree_mode ? (uint64_t)(a.blk_base + blk) * (uint64_t)b : 0ull;
 
     // decision threshold of token i: eta_i = +1 <=> u_i < 1/2 - s_i/2 <=> s_i < 1 - 2 u_i (exact in fp32)
     auto threshold = [&](int i) -> float {
@@ -796,7 +806,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             for (int i = nres + tid; i < b; i += kThreads) aterm[i] = 0.f;
         }
         if constexpr (VG) {                                     // 1 / r_value^2: given, or the largest |v_i|^2 of the block
-            float r2 = a.rvalue2;
+            float r2 = rvalue2;
             if (!(r2 > 0.f)) {
                 r2 = diag[kDiagFloats - 64];
 #pragma unroll
@@ -1094,7 +1104,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     if (wave == 0) {      // side outputs: issued after the barrier so that nobody waits for these stores
         if (a.signs_out)
             for (int p = 0; p < nP; ++p)
-                a.signs_out[(size_t)inst * b + (p << 6) + lane] = ((etaMask[p] >> lane) & 1ull) ? 1 : -1;
+                a.signs_out[(size_t)signs0 + (p << 6) + lane] = ((etaMask[p] >> lane) & 1ull) ? 1 : -1;
     } else if (wave == 2 && (a.status_out || a.stats_out)) {
         // walk statistics from the decision-time values: FAIL events (Alg. 2 line 6), near-tie decisions
         int n_margin = 0, any_fail = 0;
@@ -1194,7 +1204,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     }
     for (int r = tid; r < half; r += kThreads) {
         if (a.w_out) a.w_out[out_tok0 + r] = a.w_out_val;
-        if (a.idx_out) a.idx_out[seq * a.idx_out_seq_stride + (int64_t)blk * half + r] = (int32_t)src_token(r);
+        if (a.idx_out) a.idx_out[idx_out0 + r] = (int32_t)src_token(r);
     }
 }
 
@@ -1230,7 +1240,7 @@ hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64
             n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
         }
         a.stagger_blocks = 0; a.stagger_step = 0; a.prefetch_ahead = 0;
-        if (n_inst >= 2 * (int64_t)n_cu) {
+        if (n_inst >= 2 * (int64_t)n_cu && !a.desc) {   // (a ragged grid has unused slots: neighbours in the grid are not neighbours in memory)
             // rough duration of one block in clock ticks (measured: about 75k for 512 bf16 tokens, 200k for 1024)
             const double ticks = (40.0e3 + 0.15 * (double)a.b * (double)a.b) * (dtype == BKV_BF16 ? 1.0 : 1.5);
             a.stagger_blocks = n_cu;

@@ -88,6 +88,22 @@ def test_misuse_is_rejected_before_any_launch(bk):
     assert mp(256 + 512 * 4 + 100 + 256, 256, 256) == bk.BKV_ESHAPE
     assert mp(256 + 512 * 4 + 256, 256, 256) == bk.BKV_EWORKSPACE          # shapes fine, no workspace given
     assert mp(0, 0, 0) == bk.BKV_OK
+    # Alg. 1 sets: shapes that the value factor is not built for, missing values, missing workspace; empty input is a no-op
+    small = bk.make_params(128, 128, 2, bk.BKV_BF16, log_c=0.0)
+    sets = lambda p, which, V=one, n=1000, ws=None, wsb=0, n_seq=2: L.bkv_balancekv_sets(
+        C.byref(p), which, one, V, n_seq, n, 0, 0.0, 0.0, None, None, None, None, 64, None, None, None, None, ws, wsb, None)
+    assert sets(ok, 1) == bk.BKV_ESHAPE                       # block 512 at d=128 bf16: keys and values do not share LDS
+    assert sets(ok, 0) == bk.BKV_EWORKSPACE                   # the denominator instance has no such limit
+    assert sets(small, 1) == bk.BKV_EWORKSPACE
+    assert sets(small, 1, V=None) == bk.BKV_EINVAL
+    assert sets(small, 2) == bk.BKV_EINVAL
+    assert sets(small, 1, n=-1) == bk.BKV_EINVAL
+    assert sets(small, 1, n_seq=0) == bk.BKV_OK
+    assert L.bkv_balancekv_sets_workspace_bytes(C.byref(small), 2, 1000, 64) >= 2 * 1000 * (256 + 128 + 64 + 16)
+    cap = L.bkv_sets_capacity(C.byref(small), 100000, 8)
+    assert 100000 // 4 < cap <= 100000 // 4 + 8 * (128 + 64) and L.bkv_sets_capacity(C.byref(small), 100, 8) == 100
+    ats = lambda cn, cd: L.bkv_attend_sets(C.byref(small), one, one, one, cn, 64, one, one, cd, 64, 2, one, 4, 1, one, None, None, 0, None)
+    assert ats(10, 0) == bk.BKV_EINVAL and ats(10, 10) == bk.BKV_EWORKSPACE
     # attend
     at = lambda count, stride, g: L.bkv_attend_kv(C.byref(ok), one, one, one, 2, count, stride, one, g, 1, one, None, None, 0, None)
     assert at(10, 5, 4) == bk.BKV_EINVAL

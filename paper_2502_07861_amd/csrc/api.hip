@@ -416,12 +416,23 @@ int bkv_attend_sets(const bkv_params* p, const void* K_n, const void* V_n, const
     float* lse_n = (float*)ws; ws += align_up(rows * 4, 256);
     float* lse_d = (float*)ws; ws += align_up(rows * 4, 256);
     void* scratch = ws;
-    // numerator sum / its own normaliser, then the normaliser of the denominator set (its keys stand in for values)
+    // numerator sum / its own normaliser, then the normaliser of the denominator set (no value rows are read for it)
     rc = bkv_attend_kv(p, K_n, V_n, w_n, n_seq, count_n, stride_n, Q, g, nq, out, lse_n, att_ws, att_bytes, hip_stream);
     if (rc) return rc;
-    rc = bkv_attend_kv(p, K_d, K_d, w_d, n_seq, count_d, stride_d, Q, g, nq, scratch, lse_out ? lse_out : lse_d, att_ws, att_bytes, hip_stream);
-    if (rc) return rc;
-    hipError_t e = bkv::launch_rescale(p->dtype, out, lse_n, lse_out ? lse_out : lse_d, (int64_t)rows, p->d, (hipStream_t)hip_stream);
+    float* lse_den = lse_out ? lse_out : lse_d;
+    hipError_t e;
+    if (count_d == 0) {
+        if ((e = bkv::launch_fill_u32(lse_den, 0xff800000u, (int64_t)rows, (hipStream_t)hip_stream)) != hipSuccess) return hip_fail(e);
+    } else {
+        if (stride_d < count_d || !K_d || !w_d || !aligned16(K_d) || !Q || !aligned16(Q)) return BKV_EINVAL;
+        bkv::AttendArgs a;
+        memset(&a, 0, sizeof(a));
+        a.K = (const char*)K_d; a.V = nullptr; a.w = w_d; a.Q = (const char*)Q; a.out = (char*)scratch;
+        a.lse_out = lse_den; a.stride_tokens = stride_d; a.count = count_d; a.n_q = g * nq;
+        a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)p->d));
+        if ((e = bkv::launch_attend(p->dtype, p->d, a, n_seq, att_ws, (hipStream_t)hip_stream)) != hipSuccess) return hip_fail(e);
+    }
+    e = bkv::launch_rescale(p->dtype, out, lse_n, lse_den, (int64_t)rows, p->d, (hipStream_t)hip_stream);
     return e == hipSuccess ? BKV_OK : hip_fail(e);
 }
 

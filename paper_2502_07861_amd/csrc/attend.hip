@@ -18,7 +18,9 @@ constexpr int kTargetWGs = 512;    // workgroups of the streaming pass when the 
                                    // more only lengthen the merge, measured from 8 to 256 sequences)
 constexpr float kNeg = -1.0e30f; // "minus infinity" that stays finite under subtraction
 
-template <typename T, int D>
+// HASV = false: the normaliser alone (Alg. 1's denominator sum over a set of its own): no value row is read, the
+// output columns are zero, lse_out carries the result.
+template <typename T, int D, bool HASV = true>
 __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const AttendArgs a) {
     constexpr int ROWB = D * (int)sizeof(T);
     constexpr int SL = ROWB / 16;              // lanes per row
@@ -36,7 +38,7 @@ __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const At
     const int64_t r_end = min(a.count, r_begin + a.rows_per_split);
 
     const char* Kb = a.K + (size_t)seq * a.stride_tokens * ROWB;
-    const char* Vb = a.V + (size_t)seq * a.stride_tokens * ROWB;
+    const char* Vb = HASV ? a.V + (size_t)seq * a.stride_tokens * ROWB : nullptr;
     const float* wb = a.w + (size_t)seq * a.stride_tokens;
 
     // queries of this pass: raw 16-byte slices (bf16 path: consumed by packed dot products) and, for
@@ -63,7 +65,7 @@ __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const At
             const int64_t row = base + (u * kAttWaves + wave) * RPW + lg;
             const int64_t rr = row < r_end ? row : r_end - 1;          // stay in bounds; masked in consume()
             t.k[u] = *reinterpret_cast<const uintx4*>(Kb + (size_t)rr * ROWB + sl * 16);
-            t.v[u] = *reinterpret_cast<const uintx4*>(Vb + (size_t)rr * ROWB + sl * 16);
+            if constexpr (HASV) t.v[u] = *reinterpret_cast<const uintx4*>(Vb + (size_t)rr * ROWB + sl * 16);
             t.w[u] = wb[rr];
         }
     };
@@ -111,6 +113,7 @@ __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const At
 #pragma unroll
             for (int u = 0; u < kUnroll; u += 2) {
                 bf16x2_t vp[EPL];
+                if constexpr (HASV)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const unsigned int wa = t.v[u][i], wb = t.v[u + 1][i];
@@ -122,22 +125,25 @@ __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const At
                     const unsigned int pa = __float_as_uint(fast_exp2(lg2[u][qi] - m[qi]));        // dead rows: 2^(2 kNeg - m) = 0, m >= kNeg
                     const unsigned int pb = __float_as_uint(fast_exp2(lg2[u + 1][qi] - m[qi]));
                     l[qi] += __uint_as_float(pa & 0xffff0000u) + __uint_as_float(pb & 0xffff0000u);
-                    const bf16x2_t pp = __builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(pb, pa, 0x07060302u));
+                    if constexpr (HASV) {
+                        const bf16x2_t pp = __builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(pb, pa, 0x07060302u));
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) o[qi][e] = __builtin_amdgcn_fdot2_f32_bf16(pp, vp[e], o[qi][e], false);
+                        for (int e = 0; e < EPL; ++e) o[qi][e] = __builtin_amdgcn_fdot2_f32_bf16(pp, vp[e], o[qi][e], false);
+                    }
                 }
             }
         } else {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 float vf[EPL];
-                Elem<T>::unpack(t.v[u], vf);
+                if constexpr (HASV) Elem<T>::unpack(t.v[u], vf);
 #pragma unroll
                 for (int qi = 0; qi < kQT; ++qi) {
                     const float p = fast_exp2(lg2[u][qi] - m[qi]);        // dead rows: 2^(2 kNeg - m) = 0, m >= kNeg
                     l[qi] += p;
+                    if constexpr (HASV)
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) o[qi][e] = fmaf(p, vf[e], o[qi][e]);
+                        for (int e = 0; e < EPL; ++e) o[qi][e] = fmaf(p, vf[e], o[qi][e]);
                 }
             }
         }
@@ -332,8 +338,9 @@ size_t attend_workspace_bytes(int d, int64_t n_seq, int n_q) {
 
 template <typename T, int D>
 static hipError_t launch_attend_t(AttendArgs& a, int64_t n_seq, int n_qg, hipStream_t st) {
-    const hipError_t e = launch_timed(kProfAttend, n_seq * a.count, attend_partial_kernel<T, D>, dim3(a.n_splits, n_qg, (unsigned)n_seq),
-                                      dim3(kAttWaves * 64), 0, st, a);
+    const dim3 grid(a.n_splits, n_qg, (unsigned)n_seq);
+    const hipError_t e = a.V ? launch_timed(kProfAttend, n_seq * a.count, attend_partial_kernel<T, D, true>, grid, dim3(kAttWaves * 64), 0, st, a)
+                             : launch_timed(kProfAttend, n_seq * a.count, attend_partial_kernel<T, D, false>, grid, dim3(kAttWaves * 64), 0, st, a);
     if (e != hipSuccess || a.n_splits == 1) return e;          // a single split stores the final result itself
     return launch_timed(kProfAttendMerge, n_seq * a.n_q, attend_merge_kernel<T, D>, dim3(a.n_q, (unsigned)n_seq), dim3(kMergeThreads), 0, st,
                         a, n_qg);

@@ -825,6 +825,7 @@ def _verify_sets(bk, oracle, which, p, K, V, res, seq_base, eps, r):
     (torch.float32, 64, 64, 3, 2500, 2, 0.0),
     (torch.bfloat16, 64, 256, 1, 1111, 2, 0.0),
     (torch.bfloat16, 128, 64, 2, 50, 2, 0.0),          # no full block anywhere: nothing is halved
+    (torch.bfloat16, 128, 256, 2, 16384, 8, 0.0),      # the sequences of workload 2 at the largest block the value factor takes
 ])
 def test_balancekv_sets_against_oracle(bk, synth, oracle, dtype, d, b, T, n, n_seq, eps):
     """Alg. 1: bucketed numerator instances (value factor, r_value = 2^i, erase rule) and the keys-only denominator
@@ -873,6 +874,46 @@ def test_balancekv_sets_against_oracle(bk, synth, oracle, dtype, d, b, T, n, n_s
                 ref_lse[s, a, j] = m + math.log(den_sum)
     assert rel_l2(to_f64(out), ref) <= (1e-4 if dtype == torch.float32 else 2e-2)
     np.testing.assert_allclose(lse.cpu().numpy(), ref_lse, atol=1e-3 if dtype == torch.float32 else 2e-2)
+
+
+def test_balancekv_sets_replay_from_a_captured_graph(bk, synth):
+    """Both set builds and the two-set output line are plain kernel launches without host round trips (grids are upper
+    bounds, counts stay on the device): captured once, every replay reproduces the eager result bit for bit."""
+    dtype, d, b, T, n, n_seq = torch.bfloat16, 128, 128, 2, 3000, 3
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=n, d=d, g=2, nq=2, seed=123, device="cpu", dtype=dtype)
+    K, Q = t["K"].cuda().contiguous(), t["Q"].cuda().contiguous()
+    V = _heavy_tailed_values(t["V"], seed=9).cuda().contiguous()
+    p = bk.make_params(d, b, T, dtype, log_c=-62.0, seed=77, center=True)
+
+    def step():
+        num = bk.balancekv_sets(p, bk.BKV_SET_NUMERATOR, K, V, eps=1e-4, r=1.0, max_buckets=12)
+        den = bk.balancekv_sets(p, bk.BKV_SET_DENOMINATOR, K, V)
+        out, lse = bk.attend_sets(p, (num["K"], num["V"], num["w"]), (den["K"], den["w"]), Q)
+        return num, den, out, lse
+
+    num0, den0, out0, lse0 = step()
+    torch.cuda.synchronize()
+    assert int(num0["count"].min()) > 0 and not bool(torch.isnan(out0.float()).any())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        num, den, out, lse = step()
+    other = torch.randn(1 << 20, device="cuda")
+    for rep in range(3):
+        for tns in (num["idx"], num["w"], num["K"], num["count"], den["idx"], den["w"], out, lse):
+            tns.zero_()
+        (other * 2).sum().item()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in ("idx", "w", "K", "V", "count", "slot", "status"):
+            assert torch.equal(num[k], num0[k]), (rep, "numerator", k)
+            assert torch.equal(den[k], den0[k]), (rep, "denominator", k)
+        assert torch.equal(out, out0) and torch.equal(lse, lse0), rep
 
 
 def test_balancekv_sets_equal_the_oracle_stream(bk, synth, oracle):

@@ -46,9 +46,10 @@ extern "C" {
 #define BKV_CENTER_KEYS 1u  /* shift keys by the block mean for the selection (App. B.5 item 1) */
 #define BKV_STRICT_HALF 2u  /* keep exactly block/2 per block (App. B, Implementation Detail); required */
 #define BKV_VALUE_GRAM  4u  /* multiply kernel weights by <v_i,v_j>/r_value^2 (Alg. 2 line 5): the walk then balances
-                             * the numerator instance of Alg. 1.  Built for blocks whose keys and values fit the
+                             * the numerator instance of Alg. 1.  Fast where keys and values of a block fit the
                              * 160 KB of LDS together (d=128: block <= 256 bf16 / 128 fp32; d=64: block <= 512 bf16 /
-                             * 256 fp32); larger blocks: BKV_ESHAPE.  V is required wherever K is.               */
+                             * 256 fp32); larger blocks read the value panels from L2 tile by tile.  V is required
+                             * wherever K is.                                                                    */
 
 /* return codes */
 #define BKV_OK          0
@@ -180,8 +181,7 @@ int bkv_attend_kv(const bkv_params* p, const void* K_c, const void* V_c, const f
  *           instance with the value factor of Alg. 2 line 5 and r_value = 2^i; buckets with
  *           2^i <= eps/(2n) e^{-r^2/sqrt d} max_j |v_j| are erased (line 8; eps <= 0: none).  Rows with
  *           a zero or non-finite norm belong to no bucket.  The result is the union of the buckets'
- *           sets V^l, bucket by bucket in ascending i.  Needs a block for which BKV_VALUE_GRAM is
- *           built (else BKV_ESHAPE); the flag itself need not be set in p.
+ *           sets V^l, bucket by bucket in ascending i.  BKV_VALUE_GRAM need not be set in p.
  *   which = BKV_SET_DENOMINATOR lines 11-12: one keys-only instance per sequence (the sets K^l).
  * Draws: instance q = 512 (seq_base + seq) + slot, slot = 0 for the denominator and 256 + i for bucket
  * i; decision j of the blk-th block reaching level l of instance q draws uniform(seed, 64 q + l,

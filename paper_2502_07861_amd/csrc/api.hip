@@ -27,8 +27,6 @@ int check_params(const bkv_params* p) {
     if (p->rounds < 0 || p->rounds > 30) return BKV_ESHAPE;
     if (p->dtype != BKV_F32 && p->dtype != BKV_BF16) return BKV_ESHAPE;
     if (p->flags & ~(BKV_CENTER_KEYS | BKV_STRICT_HALF | BKV_VALUE_GRAM)) return BKV_EINVAL;
-    // value factor of Alg. 2 line 5: built for blocks whose keys and values are resident in LDS together
-    if ((p->flags & BKV_VALUE_GRAM) && !bkv::compress_value_gram_fits(p->d * (p->dtype == BKV_BF16 ? 2 : 4), p->block)) return BKV_ESHAPE;
     if (!(p->flags & BKV_STRICT_HALF)) return BKV_ESHAPE;      // variable-size output not built
     if (isnan(p->log_c) && !(p->delta > 0.f && p->delta < (float)p->block)) return BKV_EINVAL;
     return BKV_OK;

@@ -151,13 +151,16 @@ struct TileOps {
     // wavefront keeps for all tiles of its column.
     // With DIAG (a diagonal tile, not dumped) the quadrant rows 32..63 x columns 0..31, which the walk never uses, is skipped.
     // With VG the weights carry the value factor of Alg. 2 line 5: the Gram of the value rows of the same two panels
-    // (ldsVA: the 64 rows that match the tile's rows, ldsVB: those that match its columns) is formed first, scaled by
-    // 1 / r_value^2, and multiplies every weight after its exp2.
-    template <bool SUM, bool AREG, bool BREG = false, bool DIAG = false, bool VG = false>
+    // is formed first, scaled by 1 / r_value^2, and multiplies every weight after its exp2.  VG = 1: the value rows are
+    // in LDS in the layout of the keys (vA: the 64 rows that match the tile's rows, vB: those that match its columns).
+    // VG = 2: they are read from global memory; vA / vA1 are THIS LANE's rows n and n + 32 of the row panel, vB / vB1 of
+    // the column panel.
+    template <bool SUM, bool AREG, bool BREG = false, bool DIAG = false, int VG = 0>
     static __device__ __forceinline__ float tile(floatx16 (&acc)[2][2], const Frag (*A)[2], const char* ldsA, const char* ldsB,
                                                  const float* aterm_panel, float alpha, const float* sg, const float* sgn_h,
                                                  const int (&foff)[G::kGroups], int n, int h, const Frag (*Bq)[2] = nullptr,
-                                                 const char* ldsVA = nullptr, const char* ldsVB = nullptr, float inv_rv2 = 0.f) {
+                                                 const char* vA = nullptr, const char* vB = nullptr, float inv_rv2 = 0.f,
+                                                 const char* vA1 = nullptr, const char* vB1 = nullptr) {
         constexpr int KG = G::kGroups;
         constexpr int RPI = 16 / KG;                       // accumulator registers (per column half) finished per k-group
         constexpr int kAhead = KG < 4 ? KG : 4;              // k-groups between the request of a B fragment and its use
@@ -165,16 +168,19 @@ struct TileOps {
         const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         float cs0 = 0.f, cs1 = 0.f;
         floatx16 vg[2][2];                                   // value Gram / r_value^2 (VG only)
-        if constexpr (VG) {
-            const char* va = ldsVA + (size_t)n * G::kLdsRow;
-            const char* vb = ldsVB + (size_t)n * G::kLdsRow;
+        if constexpr (VG != 0) {
+            const char* va = VG == 1 ? vA + (size_t)n * G::kLdsRow : vA;
+            const char* vb = VG == 1 ? vB + (size_t)n * G::kLdsRow : vB;
+            const char* va1 = VG == 1 ? va + (size_t)32 * G::kLdsRow : vA1;
+            const char* vb1 = VG == 1 ? vb + (size_t)32 * G::kLdsRow : vB1;
             vg[0][0] = zero; vg[0][1] = zero; vg[1][0] = zero; vg[1][1] = zero;
 #pragma unroll
             for (int g = 0; g < KG; ++g) {
-                const Frag a0 = *reinterpret_cast<const Frag*>(va + foff[g]);
-                const Frag a1 = *reinterpret_cast<const Frag*>(va + (size_t)32 * G::kLdsRow + foff[g]);
-                const Frag b0 = *reinterpret_cast<const Frag*>(vb + foff[g]);
-                const Frag b1 = *reinterpret_cast<const Frag*>(vb + (size_t)32 * G::kLdsRow + foff[g]);
+                const int off = VG == 1 ? foff[g] : 32 * g + 16 * h;
+                const Frag a0 = *reinterpret_cast<const Frag*>(va + off);
+                const Frag a1 = *reinterpret_cast<const Frag*>(va1 + off);
+                const Frag b0 = *reinterpret_cast<const Frag*>(vb + off);
+                const Frag b1 = *reinterpret_cast<const Frag*>(vb1 + off);
                 Elem<T>::mma(vg[0][0], a0, b0);
                 Elem<T>::mma(vg[0][1], a0, b1);
                 if (!DIAG) Elem<T>::mma(vg[1][0], a1, b0);
@@ -211,7 +217,7 @@ struct TileOps {
         auto finish = [&](int rb, int r) {
             if (!(DIAG && rb == 1)) acc[rb][0][r] = fast_exp2(fmaf(acc[rb][0][r], alpha, at[rb][r >> 2][r & 3]));
             acc[rb][1][r] = fast_exp2(fmaf(acc[rb][1][r], alpha, at[rb][r >> 2][r & 3]));
-            if constexpr (VG) {
+            if constexpr (VG != 0) {
                 if (!(DIAG && rb == 1)) acc[rb][0][r] *= vg[rb][0][r];
                 acc[rb][1][r] *= vg[rb][1][r];
             }
@@ -230,7 +236,7 @@ struct TileOps {
                 } else if (step == 1) {
                     acc[rb][0][r] = fast_exp2(acc[rb][0][r]);
                     acc[rb][1][r] = fast_exp2(acc[rb][1][r]);
-                    if constexpr (VG) { acc[rb][0][r] *= vg[rb][0][r]; acc[rb][1][r] *= vg[rb][1][r]; }
+                    if constexpr (VG != 0) { acc[rb][0][r] *= vg[rb][0][r]; acc[rb][1][r] *= vg[rb][1][r]; }
                 } else if (SUM) {
                     cs0 = fmaf(sq[rb][r >> 2][r & 3], acc[rb][0][r], cs0);
                     cs1 = fmaf(sq[rb][r >> 2][r & 3], acc[rb][1][r], cs1);
@@ -512,11 +518,13 @@ __device__ __forceinline__ float await_and_read(int* counter, int value, const f
 
 // MULTI = false: the launcher guarantees b <= chunk_rows (the block is resident in LDS as one chunk), and the
 // multi-chunk code is compiled out.
-// VG = true (resident blocks only): the kernel weights carry the value factor <v_i,v_j> / r_value^2 of Alg. 2 line 5;
-// the block's value rows are staged in LDS behind the key rows.
-template <typename T, int D, bool EMIT_G, bool MULTI, bool VG = false>
+// VG != 0: the kernel weights carry the value factor <v_i,v_j> / r_value^2 of Alg. 2 line 5.  VG = 1 (resident blocks
+// whose values fit LDS too): the block's value rows are staged in LDS behind the key rows.  VG = 2 (any block): the
+// value panels of every tile are read from global memory (L2) as they are needed.
+template <typename T, int D, bool EMIT_G, bool MULTI, int VG = 0>
 __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a) {
-    static_assert(!VG || (!MULTI && !EMIT_G), "the value factor is built for resident blocks only");
+    static_assert(VG == 0 || !EMIT_G, "the weight dump has no values");
+    static_assert(VG != 1 || !MULTI, "values in LDS: resident blocks only");
     typedef Geo<T, D> G;
     typedef TileOps<T, D> Ops;
     typedef typename Elem<T>::Frag Frag;
@@ -529,7 +537,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     const int b = a.b, nP = b >> 6, CH = a.chunk_rows;
     char* ldsK = smem;
     char* ldsV = smem + (size_t)CH * G::kLdsRow;                   // value rows, same layout as the keys (VG only)
-    float* sigma = reinterpret_cast<float*>(smem + (size_t)(VG ? 2 : 1) * CH * G::kLdsRow);
+    float* sigma = reinterpret_cast<float*>(smem + (size_t)(VG == 1 ? 2 : 1) * CH * G::kLdsRow);
     float* aterm = sigma + b;                                      // -alpha * a_i; column factor = exp2(aterm)
     unsigned long long* etaMask = reinterpret_cast<unsigned long long*>(aterm + b);   // bit j of entry I: eta of token 64 I + j is +1
     float* etaF = reinterpret_cast<float*>(etaMask + 16);          // [8][2][32]: +-1 of the chunk's panel l, entry h*32 + 16*rb + r
@@ -635,24 +643,26 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     // Value factor: the value row of every token of the block -> LDS (the row of token i is the ORIGINAL row of that
     // token, as in the gather at the end); |v_i|^2 on the way when r_value has to be measured.
     float vmax = 0.f;
-    if constexpr (VG) {
-        const char* Vseq = a.V + (size_t)seq * a.v_seq_stride * G::kRowBytes;
+    // this lane's value row of token i of the block (VG = 2: the operand fetches go through these)
+    const char* Vseq = VG != 0 ? a.V + (size_t)seq * a.v_seq_stride * G::kRowBytes : nullptr;
+    auto vrow = [&](int i) -> const char* {
+        const int64_t tok = a.idx_in ? (int64_t)a.idx_in[in_tok0 + i] : a.idx_base + (int64_t)blk * b + i;
+        return Vseq + (size_t)tok * G::kRowBytes;
+    };
+    if (VG == 1 || (VG == 2 && !(rvalue2 > 0.f))) {      // VG = 2 with a given radius: nothing to do here
         constexpr int U = 16;
         for (int i0 = rg; i0 < b; i0 += RG * U) {
             uintx4 raw[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int i = i0 + u * RG;
-                if (i < b) {
-                    const int64_t tok = a.idx_in ? (int64_t)a.idx_in[in_tok0 + i] : a.idx_base + (int64_t)blk * b + i;
-                    raw[u] = *reinterpret_cast<const uintx4*>(Vseq + (size_t)tok * G::kRowBytes + sl * 16);
-                }
+                if (i < b) raw[u] = *reinterpret_cast<const uintx4*>(vrow(i) + sl * 16);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int i = i0 + u * RG;
                 if (i < b) {
-                    *reinterpret_cast<uintx4*>(ldsV + (size_t)i * G::kLdsRow + G::slice_off(i, sl)) = raw[u];
+                    if constexpr (VG == 1) *reinterpret_cast<uintx4*>(ldsV + (size_t)i * G::kLdsRow + G::slice_off(i, sl)) = raw[u];
                     vmax = fmaxf(vmax, group_sum<SL>(Elem<T>::dot(raw[u], raw[u])));
                 }
             }
@@ -805,7 +815,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         } else {
             for (int i = nres + tid; i < b; i += kThreads) aterm[i] = 0.f;
         }
-        if constexpr (VG) {                                     // 1 / r_value^2: given, or the largest |v_i|^2 of the block
+        if constexpr (VG != 0) {                                // 1 / r_value^2: given, or the largest |v_i|^2 of the block
             float r2 = rvalue2;
             if (!(r2 > 0.f)) {
                 r2 = diag[kDiagFloats - 64];
@@ -859,7 +869,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             for (int I = wave; I < p0; I += kWaves) {
                 Frag A[G::kGroups][2];
                 Ops::load_frags(A, Kin + (size_t)(I << 6) * G::kRowBytes, G::kRowBytes, n, h);
-                if constexpr (!EMIT_G) {
+                if constexpr (!EMIT_G && VG == 0) {
                     const bool first_panel = first;
                     Ops::row_sweep(A, ldsK, nJ, aterm + (I << 6), alpha, etaMask[I], foff, n, h, [&](int jj, float cs) {
                         float* slot = partial + (wave * 8 + jj) * 64 + lane;          // this wavefront's own slot
@@ -873,8 +883,11 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     const int J = p0 + jj;
                     const char* ldsB = lds_rows(jj << 6);
                     floatx16 acc[2][2];
-                    const float cs = Ops::template tile<true, true>(acc, A, nullptr, ldsB, aterm + (I << 6), alpha, sg, nullptr, foff, n, h);
-                    {
+                    const float cs = Ops::template tile<true, true, false, false, VG>(
+                        acc, A, nullptr, ldsB, aterm + (I << 6), alpha, sg, nullptr, foff, n, h, nullptr,
+                        VG == 2 ? vrow((I << 6) + n) : nullptr, VG == 2 ? vrow((J << 6) + n) : nullptr, inv_rv2,
+                        VG == 2 ? vrow((I << 6) + 32 + n) : nullptr, VG == 2 ? vrow((J << 6) + 32 + n) : nullptr);
+                    if constexpr (EMIT_G) {
                         const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
 #pragma unroll
                         for (int rb = 0; rb < 2; ++rb)
@@ -979,9 +992,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             auto diagonal = [&](const Frag (&P)[G::kGroups][2], int l) {
                 const int I = p0 + l;
                 floatx16 dv[2][2];
-                const char* vrows = VG ? ldsV + (size_t)(l << 6) * G::kLdsRow : nullptr;
+                const char* vrows = VG == 1 ? ldsV + (size_t)(l << 6) * G::kLdsRow : VG == 2 ? vrow((I << 6) + n) : nullptr;
+                const char* vrows1 = VG == 2 ? vrow((I << 6) + 32 + n) : nullptr;
                 Ops::template tile<false, true, true, !EMIT_G, VG>(dv, P, nullptr, nullptr, aterm + (I << 6), alpha, nullptr, nullptr, foff, n, h, P,
-                                                                   vrows, vrows, inv_rv2);
+                                                                   vrows, vrows, inv_rv2, vrows1, vrows1);
                 const float e0 = fast_exp2(aterm[(I << 6) + n] - row_const), e1 = fast_exp2(aterm[(I << 6) + 32 + n] - row_const);
                 if (EMIT_G) {
 #pragma unroll
@@ -1018,8 +1032,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     const int Ii = p0 + i;
                     floatx16 acc[2][2];
                     Ops::template tile<false, false, true, false, VG>(acc, nullptr, lds_rows(i << 6), nullptr, aterm + (Ii << 6), alpha, nullptr, nullptr, foff, n, h, Bq,
-                                                                      VG ? ldsV + (size_t)(i << 6) * G::kLdsRow : nullptr,
-                                                                      VG ? ldsV + (size_t)(w << 6) * G::kLdsRow : nullptr, inv_rv2);
+                                                                      VG == 1 ? ldsV + (size_t)(i << 6) * G::kLdsRow : VG == 2 ? vrow((Ii << 6) + n) : nullptr,
+                                                                      VG == 1 ? ldsV + (size_t)(w << 6) * G::kLdsRow : VG == 2 ? vrow((J << 6) + n) : nullptr, inv_rv2,
+                                                                      VG == 2 ? vrow((Ii << 6) + 32 + n) : nullptr, VG == 2 ? vrow((J << 6) + 32 + n) : nullptr);
                     if (EMIT_G) {
                         const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
 #pragma unroll
@@ -1209,9 +1224,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
 }
 
 // ------------------------------------------------------------------------------------------------
-template <typename T, int D, bool EMIT_G, bool MULTI, bool VG = false>
+template <typename T, int D, bool EMIT_G, bool MULTI, int VG = 0>
 static hipError_t launch_one(const CompressArgs& a, int64_t n_inst, hipStream_t st) {
-    const size_t lds = compress_lds_bytes(Geo<T, D>::kRowBytes, a.b, VG);
+    const size_t lds = compress_lds_bytes(Geo<T, D>::kRowBytes, a.b, VG == 1);
     auto kern = compress_kernel<T, D, EMIT_G, MULTI, VG>;
     static thread_local size_t configured = 0;
     if (lds > configured) {
@@ -1226,9 +1241,10 @@ static hipError_t launch_one(const CompressArgs& a, int64_t n_inst, hipStream_t 
 hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64_t n_inst, hipStream_t st) {
     const int row_bytes = d * (dtype == BKV_BF16 ? 2 : 4);
     const bool vgram = (a.flags & BKV_VALUE_GRAM) != 0;
-    // value factor: keys and values of a block are resident together, no Gram dump, value rows required
-    if (vgram && (emit_g || !a.V || !compress_value_gram_fits(row_bytes, a.b))) return hipErrorInvalidValue;
-    a.chunk_rows = chunk_rows_for(row_bytes, a.b, vgram);
+    // value factor: no Gram dump, value rows required; the values are staged in LDS when they fit next to the keys
+    if (vgram && (emit_g || !a.V)) return hipErrorInvalidValue;
+    const bool v_lds = vgram && compress_value_gram_fits(row_bytes, a.b);
+    a.chunk_rows = chunk_rows_for(row_bytes, a.b, v_lds);
     if (n_inst <= 0) return hipSuccess;
     {
         // one workgroup per compute unit is resident (LDS); with at least two rounds of workgroups, spread the first
@@ -1253,7 +1269,9 @@ hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64
     if (n_inst > kMaxGrid) return hipErrorInvalidValue;
     const bool multi = a.b > a.chunk_rows;       // the Gram-emitting (test) variant always takes the general code
 #define BKV_DISPATCH(TT, DD)                                                                \
-    return vgram ? launch_one<TT, DD, false, false, true>(a, n_inst, st)                    \
+    return v_lds ? launch_one<TT, DD, false, false, 1>(a, n_inst, st)                       \
+         : vgram ? (multi ? launch_one<TT, DD, false, true, 2>(a, n_inst, st)               \
+                          : launch_one<TT, DD, false, false, 2>(a, n_inst, st))             \
          : emit_g ? launch_one<TT, DD, true, true>(a, n_inst, st)                           \
                   : multi ? launch_one<TT, DD, false, true>(a, n_inst, st)                  \
                           : launch_one<TT, DD, false, false>(a, n_inst, st)

@@ -64,10 +64,9 @@ def test_misuse_is_rejected_before_any_launch(bk):
     assert compress(bk.make_params(128, 2048, 2, bk.BKV_BF16, log_c=0.0)) == bk.BKV_ESHAPE
     assert compress(bk.make_params(128, 512, 2, 7, log_c=0.0)) == bk.BKV_ESHAPE                # dtype
     assert compress(bk.make_params(128, 512, 2, bk.BKV_BF16, log_c=0.0, strict=False)) == bk.BKV_ESHAPE
-    # value factor: only where keys and values of a block fit LDS together; the values must be given
-    assert compress(bk.make_params(128, 512, 2, bk.BKV_BF16, log_c=0.0, value_gram=True)) == bk.BKV_ESHAPE
-    assert compress(bk.make_params(128, 256, 2, bk.BKV_F32, log_c=0.0, value_gram=True)) == bk.BKV_ESHAPE
-    assert compress(bk.make_params(128, 256, 2, bk.BKV_BF16, log_c=0.0, value_gram=True)) == bk.BKV_EINVAL   # V is null
+    # value factor: the values must be given
+    assert compress(bk.make_params(128, 512, 2, bk.BKV_BF16, log_c=0.0, value_gram=True)) == bk.BKV_EINVAL   # V is null
+    assert compress(bk.make_params(128, 256, 2, bk.BKV_BF16, log_c=0.0, value_gram=True)) == bk.BKV_EINVAL
     assert L.bkv_kernel_weights(C.byref(bk.make_params(128, 256, 2, bk.BKV_BF16, log_c=0.0, value_gram=True)), one, 2, one, None) == bk.BKV_ESHAPE
     assert compress(bk.make_params(128, 512, 2, bk.BKV_BF16)) == bk.BKV_EINVAL                 # NaN log_c, no delta
     assert compress(ok, K=None) == bk.BKV_EINVAL
@@ -92,8 +91,7 @@ def test_misuse_is_rejected_before_any_launch(bk):
     small = bk.make_params(128, 128, 2, bk.BKV_BF16, log_c=0.0)
     sets = lambda p, which, V=one, n=1000, ws=None, wsb=0, n_seq=2: L.bkv_balancekv_sets(
         C.byref(p), which, one, V, n_seq, n, 0, 0.0, 0.0, None, None, None, None, 64, None, None, None, None, ws, wsb, None)
-    assert sets(ok, 1) == bk.BKV_ESHAPE                       # block 512 at d=128 bf16: keys and values do not share LDS
-    assert sets(ok, 0) == bk.BKV_EWORKSPACE                   # the denominator instance has no such limit
+    assert sets(ok, 1) == bk.BKV_EWORKSPACE and sets(ok, 0) == bk.BKV_EWORKSPACE
     assert sets(small, 1) == bk.BKV_EWORKSPACE
     assert sets(small, 1, V=None) == bk.BKV_EINVAL
     assert sets(small, 2) == bk.BKV_EINVAL

@@ -146,6 +146,13 @@ VALUE_CASES = [
     (torch.bfloat16, 64, 192, 4, False, 30.0),    # three panels, radius given
     (torch.float32, 64, 256, 3, False, 0.0),
     (torch.float32, 128, 128, 3, True, 25.0),
+    # blocks whose values do not fit LDS next to the keys: value panels read tile by tile
+    (torch.bfloat16, 128, 512, 3, True, 0.0),     # workload 2's block, one chunk of keys
+    (torch.bfloat16, 128, 320, 2, False, 0.0),    # five panels
+    (torch.bfloat16, 128, 1024, 2, True, 0.0),    # workloads 3-5: two chunks of keys
+    (torch.float32, 128, 320, 2, True, 0.0),      # fp32, second chunk of one panel
+    (torch.float32, 64, 512, 2, False, 12.0),     # radius given: no norm pass
+    (torch.bfloat16, 64, 1024, 2, True, 0.0),
 ]
 
 
@@ -182,7 +189,23 @@ def test_compress_block_with_value_factor(bk, synth, oracle, dtype, d, b, n_inst
     assert torch.equal(out["V"], torch.gather(V, 1, gi[..., None].expand(-1, -1, d)))
     stats = out["stats"].cpu().numpy()
     np.testing.assert_allclose(stats[:, 0], np.abs(u - v["res"]["p"]).min(axis=1), atol=2e-5)
-    np.testing.assert_allclose(stats[:, 1], np.abs(v["res"]["sigma"]).max(axis=1), rtol=1e-3, atol=1e-5)
+    smax = np.abs(v["res"]["sigma"]).max(axis=1)
+    inside = smax < 1e25          # beyond: single weights leave the fp32 range the library states as its precondition (decisions still agree)
+    np.testing.assert_allclose(stats[inside, 1], smax[inside], rtol=1e-3, atol=1e-5)
+
+
+def test_merge_reduce_with_value_factor_workload2_blocks(bk, synth, oracle):
+    """The tree with the value factor at workload 2's block size (values read from L2 by original index in round 1)."""
+    from oracle.tuning import tune_log_c
+    dtype, d, b, T, n_seq, n = torch.bfloat16, 128, 512, 2, 2, 4096
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=n, d=d, g=1, nq=1, seed=808, device="cpu")
+    K, V = t["K"].cuda().contiguous(), t["V"].cuda().contiguous()
+    log_c = f32(tune_log_c(to_f64(K[0]).reshape(-1, b, d)[:2], center=True, V_blocks=to_f64(V[0]).reshape(-1, b, d)[:2]))
+    p = bk.make_params(d, b, T, dtype, log_c=log_c, seed=3, center=True, value_gram=True)
+    res = bk.merge_reduce(p, K, V, emit_signs=True)
+    torch.cuda.synchronize()
+    assert not np.any(res["status"].cpu().numpy() & 2)
+    print("value-factor tree, block 512:", _verify_tree(bk, oracle, K, V, p, res))
 
 
 def test_value_factor_with_zero_values_is_a_fair_coin(bk, synth, oracle):

@@ -404,6 +404,46 @@ struct TileOps {
                     *reinterpret_cast<floatx4*>(diag + (32 * cb + n) * kDiagStride + 32 * rb + 8 * q + 4 * h) = t;
                 }
     }
+    // One 32x32 quadrant (rows 32 QR.., columns 32 QC..) of a diagonal tile, from the panel's rows in LDS straight to
+    // the transposed tile buffer: the same arithmetic, in the same order, as tile<DIAG> + mask_diag + store_diag give
+    // that quadrant.  Three wavefronts on three SIMDs form the first tile of a chunk this way, so that the walk starts
+    // after a third of the time one wavefront needs for the whole tile.  QR = QC = 0 also clears the quadrant below
+    // the diagonal.
+    template <int QR, int QC>
+    static __device__ __forceinline__ void diag_quadrant(float* diag, const char* lds_panel, const float* aterm_panel, float alpha,
+                                                         float e_col, const int (&foff)[G::kGroups], int n, int h) {
+        static_assert(QR <= QC, "quadrants on or above the diagonal");
+        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        const char* ap = lds_panel + (size_t)(32 * QR + n) * G::kLdsRow;
+        const char* bp = lds_panel + (size_t)(32 * QC + n) * G::kLdsRow;
+        Frag A[G::kGroups], B[G::kGroups];
+#pragma unroll
+        for (int g = 0; g < G::kGroups; ++g) {
+            A[g] = *reinterpret_cast<const Frag*>(ap + foff[g]);
+            B[g] = *reinterpret_cast<const Frag*>(bp + foff[g]);
+        }
+        floatx4 at[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) at[q] = *reinterpret_cast<const floatx4*>(aterm_panel + 32 * QR + 8 * q + 4 * h);
+        floatx16 acc = zero;
+#pragma unroll
+        for (int g = 0; g < G::kGroups; ++g) Elem<T>::mma(acc, A[g], B[g]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int lrow = 8 * (r >> 2) + 4 * h + (r & 3);
+            const float w = fast_exp2(fmaf(acc[r], alpha, at[r >> 2][r & 3]));
+            acc[r] = (QR != QC || n > lrow) ? w * e_col : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const floatx4 t = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+            *reinterpret_cast<floatx4*>(diag + (32 * QC + n) * kDiagStride + 32 * QR + 8 * q + 4 * h) = t;
+            if (QR == 0 && QC == 0) {
+                const floatx4 z = {0.f, 0.f, 0.f, 0.f};
+                *reinterpret_cast<floatx4*>(diag + n * kDiagStride + 32 + 8 * q + 4 * h) = z;
+            }
+        }
+    }
 };
 
 // One decision of the walk (Alg. 2 lines 5-9 for token j of the panel).  Every lane tests the sign of its sigma
@@ -458,6 +498,14 @@ constexpr int kSpinLimit = 1 << 16;
 // not wait for them here.
 __device__ __forceinline__ void publish(int* counter, int value) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __hip_atomic_store(counter, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+// The same for a hand-over on the walk's critical path, where counter and data are both in LDS and were written by
+// this wavefront just before: LDS serves a wavefront's requests in order, so the counter cannot become visible before
+// the data, and the wavefront need not wait for its own stores to finish first.  (The fence only keeps the compiler
+// from moving the stores.)
+__device__ __forceinline__ void publish_in_order(int* counter, int value) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
     __hip_atomic_store(counter, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 template <bool EAGER = false>
@@ -927,14 +975,18 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         // operand and forms, in row order, the tiles (i, w), i < w (weights need nothing; the signed column sum needs
         // eta_done > i and goes into a register copy of sigma); then, its column being complete just as the walk of
         // panel w starts, the diagonal tile of panel w+2, which it stores when the walker has taken the previous one
-        // (the tiles of panels 0 and 1 come from wavefronts 7 and 6 at start-up, that of panel 2 from wavefront 1).  Every sigma receives
+        // (at start-up the tile of panel 0 comes as three quadrants from wavefronts 1-3 -- as a whole from wavefront 7 in
+        // the instances with a weight dump or the value factor --, that of panel 1 from wavefront 6, that of panel 2 from
+        // wavefront 1).  Every sigma receives
         // its contributions in the same order on every run.  At most one tile per wavefront and walked panel is due,
         // so the walk (wavefront 0) only ever waits for the tile (l-1, l) that depends on its last signs.
         int* eta_done = prog;
         int* diag_ready = prog + 1;
         int* diag_taken = prog + 2;
         int* sync_err = prog + 3;
+        int* first_parts = prog + 4;                  // quadrants of the chunk's first diagonal tile stored so far (three writers)
         int* col = prog + 8;
+        constexpr bool kSplitFirst = !EMIT_G && VG == 0;   // the first tile comes in three quadrants from three wavefronts
         const int nPc = p1 - p0;
         if (wave == 0) {
             unsigned int sign_bit = 0x80000000u;
@@ -947,7 +999,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 // sigma holds (sum of signed weights so far) - (1 - 2 u): eta = +1 <=> u < 1/2 - s/2 <=> sigma < 0; it is
                 // complete when the owner of this column panel says so (col[l] == l)
                 float g[64];
-                await_and_read_tile(diag_ready, l + 1, diag + lane * kDiagStride, g, sync_err);
+                if (kSplitFirst && l == 0) await_and_read_tile(first_parts, 3, diag + lane * kDiagStride, g, sync_err);
+                else await_and_read_tile(diag_ready, l + 1, diag + lane * kDiagStride, g, sync_err);
                 publish(diag_taken, l + 1);                   // the tile is in registers: the buffer may be overwritten
                 float sv = await_and_read(col + l, l, sigma + (I << 6) + lane, sync_err);
                 walk_panel(sv, g, sign_bit);
@@ -958,7 +1011,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     const int row = 32 * (k >> 4) + 8 * ((k & 15) >> 2) + 4 * h + (k & 3);
                     etaF[(l << 6) + lane] = ((m >> row) & 1ull) ? 1.f : -1.f;
                 }
-                publish(eta_done, l + 1);
+                publish_in_order(eta_done, l + 1);
                 sigma[(I << 6) + lane] = sv;                  // decision-time values, read back for the statistics (nobody waits for it)
             }
             __builtin_amdgcn_s_setprio(0);
@@ -1015,9 +1068,20 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 publish(diag_ready, l + 1);
             };
             Frag Bq[G::kGroups][2];
-            // Start-up: the diagonal tiles of panels 0 and 1 come from wavefronts 7 and 6, whose own columns (if any) are
-            // needed last, so that the other wavefronts can start on their columns at once.
-            if (w >= kWaves - 2 && kWaves - 1 - w < nPc) {
+            // Start-up: the diagonal tile of panel 1 (and, where it is not split, that of panel 0) comes from the
+            // wavefronts whose own columns are needed last.
+            if (kSplitFirst && w <= 3) {
+                // the walk cannot start without the first tile: wavefronts 1, 2, 3 (three SIMDs) take a quadrant each
+                __builtin_amdgcn_s_setprio(2);
+                const float* at0 = aterm + (p0 << 6);
+                if (w == 1) Ops::template diag_quadrant<0, 0>(diag, lds_rows(0), at0, alpha, fast_exp2(at0[n] - row_const), foff, n, h);
+                else if (w == 2) Ops::template diag_quadrant<0, 1>(diag, lds_rows(0), at0, alpha, fast_exp2(at0[32 + n] - row_const), foff, n, h);
+                else Ops::template diag_quadrant<1, 1>(diag, lds_rows(0), at0, alpha, fast_exp2(at0[32 + n] - row_const), foff, n, h);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+                if (lane == 0) __hip_atomic_fetch_add(first_parts, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __builtin_amdgcn_s_setprio(0);
+            }
+            if (w >= kWaves - 2 && kWaves - 1 - w < nPc && !(kSplitFirst && w == kWaves - 1)) {
                 if (w == kWaves - 1) __builtin_amdgcn_s_setprio(2);       // the walk cannot start without the first tile
                 Ops::load_panel(Bq, lds_rows((kWaves - 1 - w) << 6), foff, n);
                 diagonal(Bq, kWaves - 1 - w);
@@ -1052,14 +1116,14 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     asm volatile("" : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]));
                     // signs of row panel i (once the walker has published them), signed column sums
                     const bool urgent = i == w - 1;            // the walker is waiting for this one
+                    float sg[32];
                     if (urgent) { __builtin_amdgcn_s_setprio(3); await<true>(eta_done, i + 1, sync_err); }
                     else await(eta_done, i + 1, sync_err);
-                    float sg[32];
                     Ops::signs_from_lds(sg, etaF + (i << 6) + 32 * h);
                     sig = fmaf(Ops::signed_colsum(acc, sg, h), ecol, sig);
                     if (urgent) {
                         sigma[(J << 6) + lane] = sig;
-                        publish(col + w, w);
+                        publish_in_order(col + w, w);
                         __builtin_amdgcn_s_setprio(0);
                     }
                 }

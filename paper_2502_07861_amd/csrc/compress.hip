@@ -750,6 +750,12 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 mumu = fmaf(mcol[hh], mcol[hh], mumu);
             }
             mumu = wave_sum(mumu);
+            // mu goes back to LDS, one copy per wavefront (no barrier needed): the row pass below reads it at uniform
+            // addresses (broadcast reads), which costs the vector unit nothing, unlike a cross-lane read per column
+            float* mu_w = wpart + kWaves * D + wave * D;
+#pragma unroll
+            for (int hh = 0; hh < MH; ++hh) mu_w[64 * hh + lane] = mcol[hh];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
         }
         // general path: every thread forms its own 16-byte slice of mu
         float mloc[MULTI ? EPL : 1];
@@ -791,8 +797,12 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
 #pragma unroll
                 for (int qc = 0; qc < D / MC; ++qc) {
                     float sm[MC];
+                    const float* mu_w = wpart + kWaves * D + wave * D;
 #pragma unroll
-                    for (int jj = 0; jj < MC; ++jj) sm[jj] = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(mcol[(qc * MC) >> 6]), ((qc * MC) & 63) + jj));
+                    for (int jj = 0; jj < MC / 4; ++jj) {
+                        const floatx4 t = *reinterpret_cast<const floatx4*>(mu_w + qc * MC + 4 * jj);
+                        sm[4 * jj] = t[0]; sm[4 * jj + 1] = t[1]; sm[4 * jj + 2] = t[2]; sm[4 * jj + 3] = t[3];
+                    }
                     if (has_row) {
 #pragma unroll
                         for (int ss = 0; ss < SLQ; ++ss) {

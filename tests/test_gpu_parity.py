@@ -983,3 +983,51 @@ def test_balancekv_sets_equal_the_oracle_stream(bk, synth, oracle):
         compared += 1
     print("near-tie decisions per sequence: %s, sequences compared with the oracle stream: %d" % (near.tolist(), compared))
     assert compared >= 2
+
+
+def test_balancekv_sets_degenerate_cases(bk, synth, oracle):
+    """No rounds (everything kept with weight 1: the two-set output line is exact attention, Eq. 1), a capacity below
+    the count (the surplus is not written, the count is still reported), all value rows zero (empty numerator set:
+    the output is zero), and an erase threshold that leaves only the top buckets."""
+    dtype, d, n, n_seq = torch.float32, 64, 700, 2
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=n, d=d, g=2, nq=2, seed=4, device="cpu", dtype=dtype)
+    K, Q = t["K"].cuda().contiguous(), t["Q"].cuda().contiguous()
+    V = _heavy_tailed_values(t["V"], seed=1, zero_rows=5).cuda().contiguous()
+    Kd, Vd, Qd = to_f64(K), to_f64(V), to_f64(Q)
+    # T = 0
+    p0 = bk.make_params(d, 64, 0, dtype, log_c=0.0, seed=1, center=True)
+    num = bk.balancekv_sets(p0, bk.BKV_SET_NUMERATOR, K, V, capacity=n)
+    den = bk.balancekv_sets(p0, bk.BKV_SET_DENOMINATOR, K, V, capacity=n)
+    assert num["count"].tolist() == [n - 5] * n_seq and den["count"].tolist() == [n] * n_seq
+    assert torch.all(num["w"][:, :n - 5] == 1.0) and torch.all(num["w"][:, n - 5:] == 0.0) and torch.all(den["w"] == 1.0)
+    for s in range(n_seq):       # every row with a non-zero value exactly once, bucket by bucket in arrival order
+        idx = num["idx"][s, :n - 5].cpu().numpy()
+        assert sorted(idx.tolist()) == np.flatnonzero((Vd[s] ** 2).sum(-1) > 0).tolist()
+        slot = num["slot"][s].cpu().numpy()
+        assert np.all(np.diff(slot[idx]) >= 0) and np.all(np.diff(idx)[np.diff(slot[idx]) == 0] > 0)
+    out, _ = bk.attend_sets(p0, (num["K"], num["V"], num["w"]), (den["K"], den["w"]), Q)
+    ref = np.stack([[[oracle.exact_attention(Qd[s, a, j], Kd[s], Vd[s]) for j in range(Qd.shape[2])] for a in range(Qd.shape[1])]
+                    for s in range(n_seq)])
+    assert rel_l2(to_f64(out), ref) <= 1e-4
+    # capacity below the count
+    p2 = bk.make_params(d, 64, 2, dtype, log_c=-20.0, seed=1, center=True)
+    full = bk.balancekv_sets(p2, bk.BKV_SET_NUMERATOR, K, V, max_buckets=16)
+    cut = bk.balancekv_sets(p2, bk.BKV_SET_NUMERATOR, K, V, capacity=100)
+    assert torch.equal(cut["count"], full["count"]) and int(full["count"].min()) > 100
+    assert torch.equal(cut["idx"], full["idx"][:, :100]) and torch.equal(cut["K"], full["K"][:, :100])
+    # all values zero: nothing in the numerator, output zero; the denominator is unaffected
+    Vz = torch.zeros_like(V)
+    numz = bk.balancekv_sets(p2, bk.BKV_SET_NUMERATOR, K, Vz, max_buckets=16)
+    assert numz["count"].tolist() == [0] * n_seq and not numz["w"].any() and bool(torch.all(numz["slot"] == 511))
+    den2 = bk.balancekv_sets(p2, bk.BKV_SET_DENOMINATOR, K, Vz)
+    outz, lsez = bk.attend_sets(p2, (numz["K"], numz["V"], numz["w"]), (den2["K"], den2["w"]), Q, count_n=0)
+    assert not outz.any() and bool(torch.isfinite(lsez).all())
+    # an erase threshold just below the largest norm's bucket: only buckets above it survive
+    norms = np.sqrt((Vd ** 2).sum(-1))
+    eps = 2.0 * n * 0.3                      # threshold = 0.3 * v_max with r = 0
+    er = bk.balancekv_sets(p2, bk.BKV_SET_NUMERATOR, K, V, eps=eps, r=0.0, max_buckets=16)
+    for s in range(n_seq):
+        slot = er["slot"][s].cpu().numpy()
+        thr = 0.3 * norms[s].max()
+        kept = slot != 511
+        assert kept.any() and np.all(2.0 ** (slot[kept] - 256) > thr) and np.all(2.0 ** np.ceil(np.log2(norms[s][~kept & (norms[s] > 0)])) <= thr * (1 + 1e-6))

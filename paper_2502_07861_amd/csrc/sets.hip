@@ -87,6 +87,12 @@ __global__ __launch_bounds__(256) void slot_kernel(const float* norm2, const uns
     }
 }
 
+// the keys-only instance: one segment per sequence (slot 0) with all n tokens (the other counts are cleared before)
+__global__ void single_segment_kernel(int32_t* cnt, int64_t n_seq, int32_t n) {
+    const int64_t seq = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (seq < n_seq) cnt[seq * kSlots + kDenSlot] = n;
+}
+
 // exclusive prefix sum over the 64 lanes of a wavefront
 __device__ __forceinline__ int wave_exclusive_sum(int x, int lane) {
     int incl = x;
@@ -371,7 +377,8 @@ hipError_t run_sets(const SetsArgs& q, hipStream_t st) {
         k0 = k_sorted;
     } else {
         // one segment per sequence (slot 0), already in order
-        if ((e = launch_fill_w((float*)cnt, n_seq, kSlots, kDenSlot, 1, __builtin_bit_cast(float, (int32_t)n), st)) != hipSuccess) return e;
+        hipLaunchKernelGGL(single_segment_kernel, dim3(grid_for(n_seq, 64)), dim3(64), 0, st, cnt, n_seq, (int32_t)n);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
         if (q.slot_out && (e = launch_fill_u32(q.slot_out, (uint32_t)kDenSlot, n_seq * n, st)) != hipSuccess) return e;
         hipLaunchKernelGGL(segment_start_kernel, dim3((unsigned)n_seq), dim3(64), 0, st, cnt, start);
         if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -1335,7 +1335,10 @@ hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64
             const double ticks = (40.0e3 + 0.15 * (double)a.b * (double)a.b) * (dtype == BKV_BF16 ? 1.0 : 1.5);
             a.stagger_blocks = n_cu;
             a.stagger_step = (int)(ticks / n_cu);
-            a.prefetch_ahead = n_cu;
+            // Look-ahead touches pay where they are the only second read of a row (blocks resident as one chunk: 2-4 %);
+            // a block of several chunks already reads its rows about three times over and is limited by the traffic
+            // between L2 and the fabric, where one more pass costs 6 %.
+            a.prefetch_ahead = a.b <= a.chunk_rows ? n_cu : 0;
         }
     }
     // grids are one-dimensional; split very large launches

@@ -57,11 +57,14 @@ struct CompressArgs {
     uint32_t flags;
     int32_t stagger_blocks;   // the first stagger_blocks workgroups (one per compute unit) start stagger_step clock
     int32_t stagger_step;     // ticks apart, so that the memory-bound phases of successive blocks do not coincide chip-wide
+    int32_t k_by_idx;         // 1 (resident blocks only): the key rows of the block are read at their ORIGINAL index (idx_in), like
+                              // the value rows, from K [n_seq, v_seq_stride, d]: no copy of the keys in block order is needed
     int32_t prefetch_ahead;   // > 0: while walking, touch the keys of block (this + prefetch_ahead) so that they sit in L2 / MALL
 };
 
 size_t compress_lds_bytes(int row_bytes, int b, bool value_gram = false);
 bool compress_value_gram_fits(int row_bytes, int b);   // keys and values of one block resident in LDS together
+bool compress_block_resident(int row_bytes, int b, bool value_gram);   // the block runs as one resident chunk
 hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64_t n_inst, hipStream_t st);
 hipError_t launch_fill_u32(void* p, uint32_t v, int64_t n, hipStream_t st);
 hipError_t launch_copy_rows(const void* src, void* dst, int64_t n_seq, int64_t src_seq_stride,

@@ -74,6 +74,11 @@ size_t compress_lds_bytes(int row_bytes, int b, bool value_gram) {
 }
 // the value-factor variant keeps keys and values of the whole block in LDS
 bool compress_value_gram_fits(int row_bytes, int b) { return chunk_rows_for(row_bytes, b, true) >= b; }
+// does the launcher run such a block as one resident chunk (the instance without the multi-chunk code)?
+bool compress_block_resident(int row_bytes, int b, bool value_gram) {
+    const bool v_lds = value_gram && compress_value_gram_fits(row_bytes, b);
+    return b <= chunk_rows_for(row_bytes, b, v_lds);
+}
 
 template <typename T, int D>
 struct TileOps {
@@ -672,7 +677,12 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int i = i0 + u * RG;
-                if (i < rows_all) raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)(row0 + i) * G::kRowBytes + sl * 16);
+                if (i < rows_all) {
+                    const char* src = Kin + (size_t)(row0 + i) * G::kRowBytes;
+                    if (!MULTI && a.k_by_idx)      // ragged first round: the block's rows lie scattered in the original tensor
+                        src = a.K + ((size_t)seq * a.v_seq_stride + (size_t)a.idx_in[in_tok0 + row0 + i]) * G::kRowBytes;
+                    raw[u] = *reinterpret_cast<const uintx4*>(src + sl * 16);
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -1317,6 +1327,7 @@ hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64
     const bool vgram = (a.flags & BKV_VALUE_GRAM) != 0;
     // value factor: no Gram dump, value rows required; the values are staged in LDS when they fit next to the keys
     if (vgram && (emit_g || !a.V)) return hipErrorInvalidValue;
+    if (a.k_by_idx && (!a.idx_in || emit_g)) return hipErrorInvalidValue;
     const bool v_lds = vgram && compress_value_gram_fits(row_bytes, a.b);
     a.chunk_rows = chunk_rows_for(row_bytes, a.b, v_lds);
     if (n_inst <= 0) return hipSuccess;
@@ -1345,6 +1356,7 @@ hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64
     const int64_t kMaxGrid = 1ll << 30;
     if (n_inst > kMaxGrid) return hipErrorInvalidValue;
     const bool multi = a.b > a.chunk_rows;       // the Gram-emitting (test) variant always takes the general code
+    if (a.k_by_idx && multi) return hipErrorInvalidValue;      // scattered key rows: resident blocks only
 #define BKV_DISPATCH(TT, DD)                                                                \
     return v_lds ? launch_one<TT, DD, false, false, 1>(a, n_inst, st)                       \
          : vgram ? (multi ? launch_one<TT, DD, false, true, 2>(a, n_inst, st)               \

@@ -50,41 +50,32 @@ __global__ __launch_bounds__(256) void value_norm_kernel(const char* V, int64_t 
 }
 
 // Slot of every token: bucket i = the smallest i with 2^i >= |v| (Alg. 1 line 5), from the exponent of |v|^2;
-// erased (line 8) when 4^i <= erase2 * max |v|^2.  Counts per (sequence, slot).
-__global__ __launch_bounds__(256) void slot_kernel(const float* norm2, const unsigned int* vmax2_bits, int64_t n_seq, int64_t n,
-                                                   float erase2, int32_t* slot, int32_t* cnt) {
-    const int64_t total = n_seq * n;
-    const int lane = threadIdx.x & 63;
-    for (int64_t t0 = ((int64_t)blockIdx.x * 256 + (threadIdx.x & ~63)); t0 < total; t0 += (int64_t)gridDim.x * 256) {
-        const int64_t t = t0 + lane;
-        const bool live = t < total;
+// erased (line 8) when 4^i <= erase2 * max |v|^2.  Counts per (sequence, slot): blockIdx.y = sequence, a histogram per
+// workgroup in LDS, one global atomic per workgroup and occupied slot.
+__global__ __launch_bounds__(256) void slot_kernel(const float* norm2, const unsigned int* vmax2_bits, int64_t n, float erase2,
+                                                   int32_t* slot, int32_t* cnt) {
+    __shared__ int hist[kSlots];
+    const int64_t seq = blockIdx.y;
+    for (int s = threadIdx.x; s < kSlots; s += 256) hist[s] = 0;
+    __syncthreads();
+    const float limit = erase2 > 0.f ? erase2 * __uint_as_float(vmax2_bits[seq]) : 0.f;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < n; t += (int64_t)gridDim.x * 256) {
         int s = kDropSlot;
-        int64_t seq = 0;
-        if (live) {
-            seq = t / n;
-            const float x = norm2[t];
-            if (x > 0.f && x < __builtin_inff()) {
-                int e;
-                const float m = frexpf(x, &e);                    // x = m 2^e, 1/2 <= m < 1
-                const int ee = (m == 0.5f) ? e - 1 : e;           // smallest integer with 2^ee >= x
-                int i = ee >= 0 ? (ee + 1) / 2 : ee / 2;          // ceil(ee / 2): smallest i with 4^i >= x
-                i = min(max(i, kBucketMin), kBucketMax);
-                const float limit = erase2 > 0.f ? erase2 * __uint_as_float(vmax2_bits[seq]) : 0.f;
-                s = (ldexpf(1.f, 2 * i) <= limit) ? kDropSlot : kNumSlot0 + i;
-            }
-            slot[t] = s;
+        const float x = norm2[seq * n + t];
+        if (x > 0.f && x < __builtin_inff()) {
+            int e;
+            const float m = frexpf(x, &e);                    // x = m 2^e, 1/2 <= m < 1
+            const int ee = (m == 0.5f) ? e - 1 : e;           // smallest integer with 2^ee >= x
+            int i = ee >= 0 ? (ee + 1) / 2 : ee / 2;          // ceil(ee / 2): smallest i with 4^i >= x
+            i = min(max(i, kBucketMin), kBucketMax);
+            s = (ldexpf(1.f, 2 * i) <= limit) ? kDropSlot : kNumSlot0 + i;
         }
-        // one atomic per (wavefront, sequence, slot)
-        unsigned long long rem = __ballot(live);
-        while (rem) {
-            const int leader = __ffsll((long long)rem) - 1;
-            const int ls = __shfl(s, leader);
-            const long long lq = __shfl((long long)seq, leader);
-            const unsigned long long same = __ballot(live && s == ls && (long long)seq == lq);
-            if (lane == leader) atomicAdd(cnt + lq * kSlots + ls, (int)__popcll(same));
-            rem &= ~same;
-        }
+        slot[seq * n + t] = s;
+        atomicAdd(&hist[s], 1);
     }
+    __syncthreads();
+    for (int s = threadIdx.x; s < kSlots; s += 256)
+        if (hist[s]) atomicAdd(cnt + seq * kSlots + s, hist[s]);
 }
 
 // the keys-only instance: one segment per sequence (slot 0) with all n tokens (the other counts are cleared before)
@@ -354,7 +345,9 @@ hipError_t run_sets(const SetsArgs& q, hipStream_t st) {
 
     // ---- segments
     if ((e = launch_fill_u32(cnt, 0u, n_seq * kSlots, st)) != hipSuccess) return e;
-    const char* k0;                      // level-0 keys, slot order
+    const char* k0;                      // level-0 keys, slot order (or the original keys, read through perm)
+    bool first_by_idx = false;
+
     if (q.numerator) {
         if ((e = launch_fill_u32(vmax2, 0u, n_seq, st)) != hipSuccess) return e;
         const dim3 g1(grid_for(n, 256 / (rb / 16)) > 256 ? 256 : grid_for(n, 256 / (rb / 16)), (unsigned)n_seq);
@@ -365,16 +358,23 @@ hipError_t run_sets(const SetsArgs& q, hipStream_t st) {
         else if (q.dtype == BKV_F32 && q.d == 64) hipLaunchKernelGGL((value_norm_kernel<float, 64>), g1, dim3(256), 0, st, q.V, n, norm2, vmax_arg);
         else return hipErrorInvalidValue;
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL(slot_kernel, dim3(grid_for(n_seq * n, 256)), dim3(256), 0, st, norm2, vmax2, n_seq, n, q.erase2, slot, cnt);
+        const unsigned gs = grid_for(n, 4096) > 64 ? 64 : grid_for(n, 4096);
+        hipLaunchKernelGGL(slot_kernel, dim3(gs, (unsigned)n_seq), dim3(256), 0, st, norm2, vmax2, n, q.erase2, slot, cnt);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(segment_start_kernel, dim3((unsigned)n_seq), dim3(64), 0, st, cnt, start);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(partition_kernel, dim3((unsigned)n_seq), dim3(kPartThreads), 0, st, slot, cnt, start, n, perm);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL(gather_rows_kernel, dim3(grid_for(n_seq * n * (rb / 16), 256)), dim3(256), 0, st, q.K, perm, k_sorted, n_seq,
-                           n, n, n, n, (const int32_t*)nullptr, rb);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-        k0 = k_sorted;
+        // blocks resident as one chunk read their key rows through perm (no copy in slot order); larger blocks need the copy
+        if (!compress_block_resident(rb, b, true)) {
+            hipLaunchKernelGGL(gather_rows_kernel, dim3(grid_for(n_seq * n * (rb / 16), 256)), dim3(256), 0, st, q.K, perm, k_sorted, n_seq,
+                               n, n, n, n, (const int32_t*)nullptr, rb);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            k0 = k_sorted;
+        } else {
+            k0 = q.K;
+            first_by_idx = true;
+        }
     } else {
         // one segment per sequence (slot 0), already in order
         hipLaunchKernelGGL(single_segment_kernel, dim3(grid_for(n_seq, 64)), dim3(64), 0, st, cnt, n_seq, (int32_t)n);
@@ -406,6 +406,7 @@ hipError_t run_sets(const SetsArgs& q, hipStream_t st) {
         CompressArgs a = q.common;
         a.desc = desc;
         a.K = k_in;
+        a.k_by_idx = (r == 0 && first_by_idx) ? 1 : 0;
         a.K_out = (r == T - 1) ? nullptr : ((r & 1) ? k_b : k_a);      // the last level's keys are gathered from the originals
         a.V = q.numerator ? q.V : nullptr;
         a.V_out = nullptr; a.w_out = nullptr;

@@ -194,7 +194,9 @@ int bkv_attend_kv(const bkv_params* p, const void* K_c, const void* V_c, const f
  * n_seq * sum_{r' < r} (n >> r') in the coordinates of that round's input [n_seq, n >> r]: the segment
  * of slot s that starts at position p of the slot-ordered sequence occupies positions from p >> r.
  * status_out [n_seq, max(rounds,1)] int32 or NULL as in bkv_merge_reduce (cleared here).
- * One host-independent pass: no count travels to the host, grids are upper bounds.                 */
+ * One host-independent pass: no count travels to the host, grids are upper bounds.
+ * Limits: n <= 2^30, n_seq <= 65535 (else BKV_ESHAPE); workspace from
+ * bkv_balancekv_sets_workspace_bytes (BKV_EWORKSPACE if missing or too small).                     */
 #define BKV_SET_NUMERATOR   1
 #define BKV_SET_DENOMINATOR 0
 int64_t bkv_sets_capacity(const bkv_params* p, int64_t n, int32_t max_buckets);

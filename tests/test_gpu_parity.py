@@ -850,6 +850,8 @@ def _verify_sets(bk, oracle, which, p, K, V, res, seq_base, eps, r):
     (torch.bfloat16, 128, 64, 2, 50, 2, 0.0),          # no full block anywhere: nothing is halved
     (torch.bfloat16, 128, 256, 2, 16384, 8, 0.0),      # the sequences of workload 2 at the largest block the value factor takes
     (torch.bfloat16, 64, 64, 2, 333, 300, 0.0),        # many short sequences
+    (torch.bfloat16, 128, 512, 2, 9000, 2, 0.0),       # blocks whose values do not fit LDS: value panels from L2, keys through the permutation
+    (torch.bfloat16, 128, 1024, 1, 20000, 2, 0.0),     # multi-chunk blocks: keys copied into slot order first
 ])
 def test_balancekv_sets_against_oracle(bk, synth, oracle, dtype, d, b, T, n, n_seq, eps):
     """Alg. 1: bucketed numerator instances (value factor, r_value = 2^i, erase rule) and the keys-only denominator

@@ -1034,3 +1034,12 @@ def test_balancekv_sets_degenerate_cases(bk, synth, oracle):
         thr = 0.3 * norms[s].max()
         kept = slot != 511
         assert kept.any() and np.all(2.0 ** (slot[kept] - 256) > thr) and np.all(2.0 ** np.ceil(np.log2(norms[s][~kept & (norms[s] > 0)])) <= thr * (1 + 1e-6))
+
+
+def test_decode_workload_one_session(bk):
+    """The streaming-decode workload at its real per-sequence size (32768-token prefill, 1024 appended tokens, carries
+    after every 512th, GQA-4 attends) for one session = 256 KV sequences: the module checks at nine points of the stream
+    that the weights of every sequence add up to the tokens seen, that nothing beyond the count carries weight, that the
+    attend output is finite, and at the end the number of halvings and the stored count."""
+    from paper_2502_07861_amd import decode_workload
+    assert decode_workload.main(["--sessions", "1"]) == 0

@@ -26,7 +26,8 @@
  *    (session, layer, KV head) stream; sequences are independent.
  *  - Supported: d in {64,128}; block in {64,128,...,1024} (multiple of 64);
  *    dtype BKV_F32 or BKV_BF16 (inputs, outputs and queries share it; all
- *    accumulation is fp32).  Strict halving only (exactly block/2 survivors).
+ *    accumulation is fp32; the one narrowing is stated at bkv_attend_kv).
+ *    Strict halving only (exactly block/2 survivors).
  */
 #ifndef BALANCEKV_H
 #define BALANCEKV_H
@@ -163,7 +164,11 @@ int bkv_merge_reduce_protected(const bkv_params* p, const void* K, const void* V
  * out           [n_seq, g, nq, d] (dtype as params);  lse_out [n_seq, g, nq] fp32 or NULL: natural
  *               log of the estimator's denominator, so partial results over disjoint token ranges
  *               can be merged.  out = sum_i w_i e^{<k_i,q>/sqrt d} v_i / sum_i w_i e^{<k_i,q>/sqrt d}.
- * count == 0 writes zeros and lse = -inf.                                                          */
+ * count == 0 writes zeros and lse = -inf.
+ * Precision: logits, running maximum, numerator and denominator sums are fp32.  With BKV_BF16 every softmax weight
+ * 2^(logit - max) is rounded to bf16 (to nearest even) before it multiplies its value row, and the denominator adds
+ * the same rounded weights (relative error of a weight <= 2^-9, unbiased); with BKV_F32 the weights stay fp32.
+ * Limits: n_seq <= 65535 and g * nq <= 262140 (else BKV_ESHAPE).                                    */
 size_t bkv_attend_workspace_bytes(const bkv_params* p, int64_t n_seq, int64_t count, int32_t g,
                                   int32_t nq);   /* an upper bound valid for any smaller count too */
 int bkv_attend_kv(const bkv_params* p, const void* K_c, const void* V_c, const float* w,
@@ -250,13 +255,19 @@ int bkv_cache_views(const bkv_cache* c, void** K, void** V, float** w);
 /* One streaming step: k, v [n_seq, d] (one new token per sequence) go to the tail with weight 1;
  * after every block-th token the carry loop of Alg. 3 runs (up to T halvings of the last `block`
  * tokens).  Returns the number of halvings performed (>= 0) or a negative code.
- * status_out [n_seq, T] int32 or NULL is OR-ed/added to as in bkv_merge_reduce (never cleared here). */
+ * status_out [n_seq, T] int32 or NULL is OR-ed/added to as in bkv_merge_reduce (never cleared here).
+ * Decision-level hooks, as in bkv_compress_block (both may be NULL):
+ * uniforms   [T, n_seq, block] fp32 device: the halving of level i that this step runs takes u_j from
+ *            uniforms[i][seq][j] instead of the generator (test hook);
+ * signs_out  [T, n_seq, block] int8 device: eta of the halving of level i (its block in stored order,
+ *            older half first) goes to signs_out[i]; slices of levels that did not carry are not written. */
 size_t bkv_append_workspace_bytes(const bkv_cache* c);
 int bkv_append_token(bkv_cache* c, const void* k, const void* v, int32_t* status_out,
+                     const float* uniforms, int8_t* signs_out,
                      void* workspace, size_t ws_bytes, void* hip_stream);
 
 /* Alg. 1 output line over everything the cache holds (all levels, weights 2^level).
- * Q, out, lse_out as in bkv_attend_kv.                                                              */
+ * Q, out, lse_out, precision and limits as in bkv_attend_kv (a cache holds at most 65535 sequences).  */
 size_t bkv_cache_attend_workspace_bytes(const bkv_cache* c, int32_t g, int32_t nq);
 int bkv_attend(const bkv_cache* c, const void* Q, int32_t g, int32_t nq, void* out, float* lse_out,
                void* workspace, size_t ws_bytes, void* hip_stream);

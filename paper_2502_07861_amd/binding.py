@@ -68,7 +68,7 @@ _SIGNATURES = {
     "bkv_cache_tokens_seen": (_i64, [_vp]),
     "bkv_cache_views": (C.c_int, [_vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_vp)]),
     "bkv_append_workspace_bytes": (_sz, [_vp]),
-    "bkv_append_token": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bkv_append_token": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bkv_cache_attend_workspace_bytes": (_sz, [_vp, _i32, _i32]),
     "bkv_attend": (C.c_int, [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
     "bkv_profile_enable": (C.c_int, [_i32]),
@@ -358,9 +358,11 @@ class Cache:
         _check(lib().bkv_cache_prefill(self.h, C.byref(pre), _ptr(K, dt, "K"), _ptr(V, dt, "V"), n, _ptr(status),
                                        _ptr(workspace), workspace.numel(), _stream()), "bkv_cache_prefill")
 
-    def append_token(self, k, v, status=None):
+    def append_token(self, k, v, status=None, uniforms=None, signs=None):
+        """bkv_append_token; uniforms / signs [T, n_seq, block] (fp32 / int8) are the decision-level hooks."""
         dt = _torch_dtype(self.p)
         return _check(lib().bkv_append_token(self.h, _ptr(k, dt, "k"), _ptr(v, dt, "v"), _ptr(status),
+                                             _ptr(uniforms, torch.float32, "uniforms"), _ptr(signs, torch.int8, "signs"),
                                              _ptr(self._append_ws), self._append_ws.numel(), _stream()),
                       "bkv_append_token")
 
@@ -380,15 +382,20 @@ class Cache:
         return out, lse_t
 
     def views(self):
-        """Device views K, V [n_seq, cap, d], w [n_seq, cap] of the storage (no copy)."""
+        """Device views K, V [n_seq, cap, d], w [n_seq, cap] of the storage (no copy): the pointers come from
+        bkv_cache_views, the layout of the storage stays the library's business."""
         dt = _torch_dtype(self.p)
         es = 2 if self.p.dtype == BKV_BF16 else 4
-        kv = (self.n_seq * self.cap * self.p.d * es + 255) // 256 * 256
-        off = self._base - self.storage.data_ptr()
-        K = self.storage[off:off + self.n_seq * self.cap * self.p.d * es].view(dt).view(self.n_seq, self.cap, self.p.d)
-        V = self.storage[off + kv:off + kv + self.n_seq * self.cap * self.p.d * es].view(dt).view(self.n_seq, self.cap, self.p.d)
-        w = self.storage[off + 2 * kv:off + 2 * kv + self.n_seq * self.cap * 4].view(torch.float32).view(self.n_seq, self.cap)
-        return K, V, w
+        Kp, Vp, wp = C.c_void_p(), C.c_void_p(), C.c_void_p()
+        _check(lib().bkv_cache_views(self.h, C.byref(Kp), C.byref(Vp), C.byref(wp)), "bkv_cache_views")
+        base = self.storage.data_ptr()
+        def view(ptr, nbytes, dtype, shape):
+            off = ptr.value - base
+            assert 0 <= off and off + nbytes <= self.storage.numel()
+            return self.storage[off:off + nbytes].view(dtype).view(*shape)
+        kv_bytes = self.n_seq * self.cap * self.p.d * es
+        return (view(Kp, kv_bytes, dt, (self.n_seq, self.cap, self.p.d)), view(Vp, kv_bytes, dt, (self.n_seq, self.cap, self.p.d)),
+                view(wp, self.n_seq * self.cap * 4, torch.float32, (self.n_seq, self.cap)))
 
 
 def profile_enable(n: int):

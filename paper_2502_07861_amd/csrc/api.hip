@@ -296,9 +296,11 @@ size_t bkv_attend_workspace_bytes(const bkv_params* p, int64_t n_seq, int64_t co
     return bkv::attend_workspace_bytes(p->d, n_seq, g * nq);
 }
 
-int bkv_attend_kv(const bkv_params* p, const void* K_c, const void* V_c, const float* w, int64_t n_seq,
-                  int64_t count, int64_t stride_tokens, const void* Q, int32_t g, int32_t nq, void* out,
-                  float* lse_out, void* workspace, size_t ws_bytes, void* hip_stream) {
+}  // extern "C"
+
+static int attend_kv_impl(const bkv_params* p, const void* K_c, const void* V_c, const float* w, int64_t n_seq,
+                          int64_t count, int64_t stride_tokens, const void* Q, int32_t g, int32_t nq, void* out,
+                          float* lse_out, void* workspace, size_t ws_bytes, void* hip_stream) {
     int rc = check_params(p);
     if (rc) return rc;
     if (n_seq < 0 || count < 0 || stride_tokens < count || g <= 0 || nq <= 0) return BKV_EINVAL;
@@ -324,6 +326,15 @@ int bkv_attend_kv(const bkv_params* p, const void* K_c, const void* V_c, const f
     a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)p->d));
     e = bkv::launch_attend(p->dtype, p->d, a, n_seq, workspace, st);
     return e == hipSuccess ? BKV_OK : hip_fail(e);
+}
+
+extern "C" {
+
+int bkv_attend_kv(const bkv_params* p, const void* K_c, const void* V_c, const float* w, int64_t n_seq,
+                  int64_t count, int64_t stride_tokens, const void* Q, int32_t g, int32_t nq, void* out,
+                  float* lse_out, void* workspace, size_t ws_bytes, void* hip_stream) {
+    return attend_kv_impl(p, K_c, V_c, w, n_seq, count, stride_tokens, Q, g, nq, out, lse_out, workspace, ws_bytes,
+                          hip_stream);
 }
 
 // ------------------------------------------------------------------------------------------ Alg. 1: buckets, two instances
@@ -523,8 +534,8 @@ size_t bkv_append_workspace_bytes(const bkv_cache* c) {
     return 2 * align_up((size_t)c->n_seq * (c->p.block / 2) * row_bytes(&c->p), 256) + 256;
 }
 
-int bkv_append_token(bkv_cache* c, const void* k, const void* v, int32_t* status_out, void* workspace,
-                     size_t ws_bytes, void* hip_stream) {
+int bkv_append_token(bkv_cache* c, const void* k, const void* v, int32_t* status_out, const float* uniforms,
+                     int8_t* signs_out, void* workspace, size_t ws_bytes, void* hip_stream) {
     if (!c || !k || !v || !aligned16(k) || !aligned16(v)) return BKV_EINVAL;
     if (c->count + 1 > c->cap) return BKV_ECAPACITY;
     const int b = c->p.block, T = c->p.rounds;
@@ -554,6 +565,9 @@ int bkv_append_token(bkv_cache* c, const void* k, const void* v, int32_t* status
         a.K = c->K + (size_t)first * rb; a.V = c->V + (size_t)first * rb;
         a.K_out = tmpK; a.V_out = tmpV;
         a.status_out = status_out; a.status_stride = T;
+        // decision-level hooks: the halving of level i reads / writes slice i of [T, n_seq, block]
+        a.uniforms = uniforms ? uniforms + (size_t)i * c->n_seq * b : nullptr;
+        a.signs_out = signs_out ? signs_out + (size_t)i * c->n_seq * b : nullptr;
         a.in_seq_stride = a.v_seq_stride = c->cap; a.out_seq_stride = a.idx_out_seq_stride = b / 2; a.blocks_per_seq = 1;
         a.tree_mode = 1; a.round = i; a.seq_base = 0;
         a.blk_base = (j / b) / (1ll << i) - 1;           // how many blocks reached level i before this one

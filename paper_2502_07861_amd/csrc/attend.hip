@@ -104,12 +104,14 @@ __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const At
             }
         }
         if constexpr (sizeof(T) == 2) {
-            // bf16 values: two rows at a time on the packed dot product.  The weights p are cut to bf16 (the
-            // denominator adds the same cut values, so numerator and denominator stay one estimator); element e of
-            // rows a and b is paired by byte permutes, and o[e] += p_a v_a[e] + p_b v_b[e] is one v_dot2c_f32_bf16
-            // (exact products, fp32 sum) instead of two conversions and two multiply-adds.
+            // bf16 values: two rows at a time on the packed dot product.  The weights p of the two rows are rounded to
+            // bf16 (to nearest even, both in one v_cvt_pk_bf16_f32) and the denominator adds the same rounded values,
+            // so numerator and denominator stay one estimator and the rounding errors carry no bias; element e of rows
+            // a and b is paired by byte permutes, and o[e] += p_a v_a[e] + p_b v_b[e] is one v_dot2c_f32_bf16 (exact
+            // products, fp32 sum) instead of two conversions and two multiply-adds.
             typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
             static_assert(kUnroll % 2 == 0, "rows are consumed in pairs");
+            const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
             for (int u = 0; u < kUnroll; u += 2) {
                 bf16x2_t vp[EPL];
@@ -122,11 +124,11 @@ __global__ __launch_bounds__(kAttWaves * 64) void attend_partial_kernel(const At
                 }
 #pragma unroll
                 for (int qi = 0; qi < kQT; ++qi) {
-                    const unsigned int pa = __float_as_uint(fast_exp2(lg2[u][qi] - m[qi]));        // dead rows: 2^(2 kNeg - m) = 0, m >= kNeg
-                    const unsigned int pb = __float_as_uint(fast_exp2(lg2[u + 1][qi] - m[qi]));
-                    l[qi] += __uint_as_float(pa & 0xffff0000u) + __uint_as_float(pb & 0xffff0000u);
+                    const floatx2 pf = {fast_exp2(lg2[u][qi] - m[qi]),            // dead rows: 2^(2 kNeg - m) = 0, m >= kNeg
+                                        fast_exp2(lg2[u + 1][qi] - m[qi])};
+                    const bf16x2_t pp = __builtin_convertvector(pf, bf16x2_t);     // (p_a, p_b)
+                    l[qi] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l[qi], false);
                     if constexpr (HASV) {
-                        const bf16x2_t pp = __builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(pb, pa, 0x07060302u));
 #pragma unroll
                         for (int e = 0; e < EPL; ++e) o[qi][e] = __builtin_amdgcn_fdot2_f32_bf16(pp, vp[e], o[qi][e], false);
                     }

@@ -40,8 +40,10 @@ def single_head_fp32(n=1024, d=64, nq=16, *, seed=0x250207861001, device="cpu", 
 
 
 def gqa_layer_bf16(n_seq=8, n=16384, d=128, g=4, nq=64, *, seed=0x250207861002, device="cpu",
-                   dtype=torch.bfloat16, outlier=8.0, n_outlier=4, mu_norm=2.0, chunk=16):
-    """K,V [n_seq,n,d], Q [n_seq,g,nq,d] in ``dtype``; n_seq = layers x KV heads."""
+                   dtype=torch.bfloat16, outlier=8.0, n_outlier=4, mu_norm=2.0, chunk=16, tail=0):
+    """K,V [n_seq,n,d], Q [n_seq,g,nq,d] in ``dtype``; n_seq = layers x KV heads.  ``tail`` > 0 adds K_tail, V_tail
+    [n_seq,tail,d]: further tokens of the same sequences (same means and outlier channels), drawn after everything else,
+    so that K, V and Q do not depend on it."""
     gen = _gen(seed, device)
     mu = torch.randn(n_seq, d, generator=gen, device=device, dtype=torch.float32)
     mu = mu_norm * mu / mu.norm(dim=1, keepdim=True)
@@ -59,7 +61,12 @@ def gqa_layer_bf16(n_seq=8, n=16384, d=128, g=4, nq=64, *, seed=0x250207861002, 
         del z
     zq = torch.randn(n_seq, g, nq, d, generator=gen, device=device, dtype=torch.float32)
     Q = (mu[:, None, None, :] + zq).to(dtype)
-    return dict(K=K, V=V, Q=Q)
+    res = dict(K=K, V=V, Q=Q)
+    if tail > 0:
+        z = torch.randn(n_seq, tail, d, generator=gen, device=device, dtype=torch.float32)
+        res["K_tail"] = ((mu[:, None, :] + z) * scale[:, None, :]).to(dtype)
+        res["V_tail"] = torch.randn(n_seq, tail, d, generator=gen, device=device, dtype=torch.float32).to(dtype)
+    return res
 
 
 # The five workloads named by the benchmark description; n_seq = sessions*layers*KV heads.
@@ -86,6 +93,6 @@ def make_workload(name: str, device="cpu", **over):
         t = single_head_fp32(cfg["n"], cfg["d"], cfg["nq"], seed=cfg["seed"], device=device)
     else:
         t = gqa_layer_bf16(cfg["n_seq"], cfg["n"], cfg["d"], cfg["g"], cfg["nq"], seed=cfg["seed"],
-                           device=device)
+                           device=device, tail=cfg.get("tail", 0))
     t["cfg"] = cfg
     return t

@@ -465,6 +465,31 @@ def test_merge_reduce_workload3_sampled(bk, synth, oracle):
     tot = _verify_tree(bk, oracle, K, V, p, res, sample=64, rng=np.random.default_rng(0))
     print("workload 3 sampled: %s" % tot)
     assert res["K"].shape == (256, 8192, 128)
+    assert not np.any(res["status"].cpu().numpy() & 2)          # no pipeline time-out on any of the 12288 blocks
+    # Determinism under load: the same launches once more give the same bytes (the panel pipeline hands data over
+    # through counters without barriers; its results must not depend on timing).
+    again = bk.merge_reduce(p, K, V, emit_signs=True)
+    torch.cuda.synchronize()
+    for r in range(2):
+        assert torch.equal(again["signs"][r], res["signs"][r])
+    assert torch.equal(again["idx"], res["idx"]) and torch.equal(again["status"], res["status"])
+    assert torch.equal(again["K"], res["K"]) and torch.equal(again["V"], res["V"])
+
+
+def test_merge_reduce_workload4_sampled(bk, synth, oracle):
+    """64 layers x 8 KV heads, n=131072, d=128 bf16, b=1024, T=3 (the benchmark's default workload, in its launch
+    configuration: grids of 65536 / 32768 / 16384 blocks, staggered start): 64 sampled instances per round are
+    teacher-forced against the oracle, the survivor bookkeeping is checked on every block."""
+    cfg = dict(synth.WORKLOADS["cfg4"])
+    t = synth.gqa_layer_bf16(cfg["n_seq"], cfg["n"], cfg["d"], cfg["g"], 1, seed=cfg["seed"], device="cuda")
+    K, V = t["K"], t["V"]
+    p = bk.make_params(128, 1024, 3, torch.bfloat16, log_c=-82.5617, seed=cfg["seed"], center=True)   # bench.py's ln c
+    res = bk.merge_reduce(p, K, V, emit_signs=True)
+    torch.cuda.synchronize()
+    tot = _verify_tree(bk, oracle, K, V, p, res, sample=64, rng=np.random.default_rng(4))
+    print("workload 4 sampled: %s" % tot)
+    assert res["K"].shape == (512, 16384, 128)
+    assert not np.any(res["status"].cpu().numpy() & 2)
 
 
 # ------------------------------------------------------------------------------------------ a10: estimator
@@ -511,6 +536,26 @@ def test_attend_matches_oracle(bk, synth, oracle, dtype, d, n_seq, count, stride
     out2, _ = bk.attend_kv(p, K, V, torch.full_like(w, 4.0), Q, count=count)
     out1, _ = bk.attend_kv(p, K, V, torch.ones_like(w), Q, count=count)
     assert rel_l2(to_f64(out2), to_f64(out1)) <= (1e-6 if dtype == torch.float32 else 1e-2)
+
+
+def test_attend_bf16_weight_rounding_is_bounded(bk, synth):
+    """The bf16 path rounds every softmax weight to bf16 (to nearest even) before the value accumulation and the
+    denominator; the fp32 path keeps them in fp32.  The same bf16 values through both paths: the outputs differ by
+    the rounding of the output itself (2^-9 relative per element) plus an unbiased 2^-9 per weight, and the
+    log-denominator shows no bias (a truncation would shift it by about -2^-9 = -0.002)."""
+    n_seq, count, d, g = 3, 8192, 128, 4
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=count, d=d, g=g, nq=1, seed=404, device="cpu")
+    K, V, Q = t["K"].cuda(), t["V"].cuda(), t["Q"].cuda()
+    gen = torch.Generator().manual_seed(3)
+    w = (2.0 ** torch.randint(0, 4, (n_seq, count), generator=gen)).float().cuda()
+    out_b, lse_b = bk.attend_kv(bk.make_params(d, 64, 1, torch.bfloat16, log_c=0.0), K, V, w, Q)
+    out_f, lse_f = bk.attend_kv(bk.make_params(d, 64, 1, torch.float32, log_c=0.0), K.float(), V.float(), w, Q.float())
+    torch.cuda.synchronize()
+    err = rel_l2(to_f64(out_b), to_f64(out_f))
+    dl = (lse_b - lse_f).cpu().numpy()
+    print("bf16-weight path vs fp32-weight path: rel-L2 %.3e, lse difference mean %.2e max %.2e" % (err, dl.mean(), np.abs(dl).max()))
+    assert err <= 4e-3
+    assert np.abs(dl).max() <= 1e-3 and abs(dl.mean()) <= 3e-4
 
 
 def test_attend_empty_cache(bk, synth):
@@ -615,6 +660,124 @@ def test_streaming_cache_equals_offline_tree_and_oracle(bk, synth, oracle, value
     ref, ref_lse = _attend_ref(oracle, Kv, Vv, wv, Q, cnt)
     assert rel_l2(to_f64(out), ref) <= 1e-4
     np.testing.assert_allclose(lse.cpu().numpy(), ref_lse, atol=1e-4)
+    cache.close()
+
+
+def test_append_token_uniforms_hook_equals_generator(bk, synth, oracle):
+    """The decision-level hooks of bkv_append_token: draws passed in as `uniforms` give the same signs, survivors and
+    weights as the generator with the same seed; `signs` carries eta of every carry."""
+    d, b, T, n_seq = 64, 64, 2, 2
+    n = b * 4
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=n, d=d, g=1, nq=1, seed=78, device="cpu")
+    K, V = t["K"].cuda(), t["V"].cuda()
+    p = bk.make_params(d, b, T, torch.bfloat16, log_c=-20.0, seed=99, center=True)
+    caches = [bk.Cache(p, n_seq, max_tokens=2 * n) for _ in range(2)]
+    for j in range(n):
+        k, v = K[:, j].contiguous(), V[:, j].contiguous()
+        carry = (j + 1) % b == 0
+        sg = [torch.zeros(T, n_seq, b, dtype=torch.int8, device="cuda") for _ in range(2)] if carry else [None, None]
+        u = None
+        if carry:      # what the generator would draw: level i, block number (j+1)/b/2^i - 1
+            u = torch.zeros(T, n_seq, b, dtype=torch.float32)
+            for i in range(T):
+                if ((j + 1) // b) % (1 << i) == 0:
+                    for s in range(n_seq):
+                        u[i, s] = torch.from_numpy(oracle.uniform_fill(99, 64 * s + i, ((j + 1) // b // (1 << i) - 1) * b, b)).float()
+            u = u.cuda()
+        h0 = caches[0].append_token(k, v, signs=sg[0])
+        h1 = caches[1].append_token(k, v, uniforms=u, signs=sg[1])
+        assert h0 == h1
+        if carry:
+            assert torch.equal(sg[0][:h0], sg[1][:h0]) and bool(torch.all(sg[0][:h0].abs() == 1))
+            assert bool(torch.all(sg[0][h0:] == 0))                     # levels that did not carry are not written
+    v0, v1 = caches[0].views(), caches[1].views()
+    for a, c in zip(v0, v1):
+        assert torch.equal(a, c)
+    for c in caches:
+        c.close()
+
+
+def test_decode_workload_carries_teacher_forced(bk, synth, oracle):
+    """The streaming-decode workload at its real per-sequence size, one session (256 KV sequences, d=128 bf16): a
+    32768-token prefill (block 1024, two rounds) straight into the cache, then 1024 appended tokens with block 512
+    and two levels.  On 64 sampled sequences every carry (two at level 0, one at level 1) is teacher-forced against
+    the oracle from the device's own signs, the region behind the prefill's survivors must hold exactly the rows
+    and weights that follow from those signs, the free-running oracle stream must agree where the device reported no
+    margin decision, and the decode attend is compared with the oracle's estimator on the device's own cache."""
+    from oracle.merge_reduce import MergeAndReduceStream
+    n_seq, n, d, bd, n_dec = 256, 32768, 128, 512, 1024
+    cfg = dict(synth.WORKLOADS["cfg5"])
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=n, d=d, g=4, nq=1, seed=cfg["seed"], device="cuda", tail=n_dec)
+    K, V, Q = t["K"], t["V"], t["Q"].contiguous()
+    Kt, Vt = t["K_tail"], t["V_tail"]
+    log_c_pre, log_c_dec, seed_dec = -82.5617, -73.5768, 2
+    pre = bk.make_params(d, 1024, 2, torch.bfloat16, log_c=log_c_pre, seed=1, center=True)
+    dec = bk.make_params(d, bd, 2, torch.bfloat16, log_c=log_c_dec, seed=seed_dec, center=True)
+    cache = bk.Cache(dec, n_seq, max_tokens=(n >> 2) + n_dec + bd)
+    st_pre = torch.zeros(n_seq, 2, dtype=torch.int32, device="cuda")
+    cache.prefill(pre, K, V, status=st_pre)
+    base = cache.count
+    assert base == n >> 2
+    del K, V
+    status = torch.zeros(n_seq, 2, dtype=torch.int32, device="cuda")
+    signs = {}
+    kt, vt = Kt.transpose(0, 1).contiguous(), Vt.transpose(0, 1).contiguous()
+    for j in range(n_dec):
+        sg = torch.zeros(2, n_seq, bd, dtype=torch.int8, device="cuda") if (j + 1) % bd == 0 else None
+        h = cache.append_token(kt[j], vt[j], status, signs=sg)
+        if sg is not None:
+            signs[j + 1] = (h, sg)
+    out, lse = cache.attend(Q)
+    torch.cuda.synchronize()
+    assert signs[512][0] == 1 and signs[1024][0] == 2 and cache.count == base + 256
+    assert int((st_pre & 2).sum()) == 0 and int((status & 2).sum()) == 0          # no pipeline time-outs
+    Kv, Vv, wv = cache.views()
+    assert bool(torch.all(wv[:, :base] == 4.0)) and bool(torch.all(wv[:, base:base + 256] == 4.0))
+    assert bool(torch.all(wv[:, base + 256:] == 0.0))
+    rng = np.random.default_rng(5)
+    picks = np.sort(rng.choice(n_seq, size=64, replace=False))
+    sel = torch.from_numpy(picks).cuda()
+    Ktd, Vtd = to_f64(Kt[sel]), to_f64(Vt[sel])                                   # [64, 1024, d]
+    sa = signs[512][1][0][sel].cpu().numpy()
+    sb0 = signs[1024][1][0][sel].cpu().numpy()
+    sb1 = signs[1024][1][1][sel].cpu().numpy()
+    st = status[sel].cpu().numpy()
+    tot = dict(hard=0, margin=0, n=0, near=0)
+    def check(Kb, u, sg):
+        v = verify_halving(oracle, Kb, u, sg, log_c=log_c_dec, center=True)
+        for k in tot:
+            tot[k] += v[k]
+    # level 0, blocks 0 and 1 of each sequence's stream
+    check(Ktd[:, :bd], np.stack([oracle.uniform_fill(seed_dec, 64 * int(s), 0, bd) for s in picks]), sa)
+    check(Ktd[:, bd:], np.stack([oracle.uniform_fill(seed_dec, 64 * int(s), bd, bd) for s in picks]), sb0)
+    keep_a, keep_b = expected_survivors(oracle, sa), expected_survivors(oracle, sb0)
+    lvl1 = np.concatenate([keep_a, bd + keep_b], axis=1)                          # [64, 512] positions in the tail, older half first
+    check(np.stack([Ktd[i][lvl1[i]] for i in range(64)]),
+          np.stack([oracle.uniform_fill(seed_dec, 64 * int(s) + 1, 0, bd) for s in picks]), sb1)
+    assert tot["hard"] == 0, tot
+    keep_1 = expected_survivors(oracle, sb1)
+    final = np.stack([lvl1[i][keep_1[i]] for i in range(64)])                     # [64, 256]
+    Kc, Vc = to_f64(Kv[sel, base:base + 256]), to_f64(Vv[sel, base:base + 256])
+    free = 0
+    for i in range(64):
+        np.testing.assert_array_equal(Kc[i], Ktd[i][final[i]])
+        np.testing.assert_array_equal(Vc[i], Vtd[i][final[i]])
+        if int((st[i] >> 8).sum()) == 0:       # no margin decision: the oracle's own stream keeps the same tokens
+            stream = MergeAndReduceStream(d, d, t=bd, T=2, seed=seed_dec, seq=int(picks[i]), log_c=log_c_dec, center=True)
+            for j in range(n_dec):
+                stream.append(Ktd[i, j], Vtd[i, j])
+            idx, w = stream.flat()
+            np.testing.assert_array_equal(idx, final[i])
+            assert np.all(w == 4.0)
+            free += 1
+    print("decode workload, 64 sampled sequences: %s, free-running oracle stream compared on %d of them" % (tot, free))
+    # the decode attend over the device's own cache (prefill survivors + the streamed region), 64 sequences x 4 heads
+    cnt = cache.count
+    ref, ref_lse = _attend_ref(oracle, Kv[sel], Vv[sel], wv[sel], Q[sel], cnt)
+    err = rel_l2(to_f64(out[sel]), ref)
+    print("decode attend rel-L2 = %.3e" % err)
+    assert err <= 2e-2
+    np.testing.assert_allclose(lse[sel].cpu().numpy(), ref_lse, atol=2e-3)
     cache.close()
 
 

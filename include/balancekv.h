@@ -176,6 +176,20 @@ int bkv_attend_kv(const bkv_params* p, const void* K_c, const void* V_c, const f
                   int32_t nq, void* out, float* lse_out, void* workspace, size_t ws_bytes,
                   void* hip_stream);
 
+/* The same call for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Arguments, results and error codes as
+ * bkv_attend_kv, without `workspace`: the partial sums of a split token range go to a static device array inside the
+ * library (bkv_attend_kv_static_max_bytes() bytes, 2.25 MiB, held by every GPU the library runs on until the process
+ * ends).  The call allocates nothing and frees nothing.  A launch whose partials would not fit the array returns
+ * BKV_EWORKSPACE (with today's launch plan -- at most 1023 (workgroup, split) pairs of 4 x (d + 2) floats whenever the
+ * range is split -- every shape that bkv_attend_kv accepts fits).  All calls on one GPU share the array: calls that
+ * overlap in time on the same GPU (different streams, different threads) race; calls on one stream do not.  The
+ * array keeps the last call's partials; every launch writes all partials it later reads, nothing needs clearing.  */
+size_t bkv_attend_kv_static_max_bytes(void);
+int bkv_attend_kv_static(const bkv_params* p, const void* K_c, const void* V_c, const float* w,
+                         int64_t n_seq, int64_t count, int64_t stride_tokens, const void* Q, int32_t g,
+                         int32_t nq, void* out, float* lse_out, void* hip_stream);
+
 /* ---- Alg. 1 as listed: value-norm buckets, MR-Numerator_i per bucket, MR-Denominator ---------------
  * Offline form on K, V [n_seq, n, d] (any n >= 0): every instance is brought to the state Alg. 3
  * (MergeAndReduce) holds after its last token -- full blocks halved level by level, at most one half

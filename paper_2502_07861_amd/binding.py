@@ -51,6 +51,8 @@ _SIGNATURES = {
     "bkv_merge_reduce_protected": (C.c_int, [_PP, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bkv_attend_workspace_bytes": (_sz, [_PP, _i64, _i64, _i32, _i32]),
     "bkv_attend_kv": (C.c_int, [_PP, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
+    "bkv_attend_kv_static_max_bytes": (_sz, []),
+    "bkv_attend_kv_static": (C.c_int, [_PP, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _i32, _i32, _vp, _vp, _vp]),
     "bkv_sets_capacity": (_i64, [_PP, _i64, _i32]),
     "bkv_balancekv_sets_workspace_bytes": (_sz, [_PP, _i64, _i64, _i64]),
     "bkv_balancekv_sets": (C.c_int, [_PP, _i32, _vp, _vp, _i64, _i64, _i64, C.c_float, C.c_float, _vp, _vp, _vp, _vp, _i64,
@@ -244,6 +246,20 @@ def attend_kv(p, K_c, V_c, w, Q, *, count=None, workspace=None, out=None, lse=Tr
                              workspace.numel(), _stream())
     _check(rc, "bkv_attend_kv")
     return out, lse_t
+
+
+def attend_kv_static(p, K_c, V_c, w, Q, out, lse=None, *, count=None):
+    """bkv_attend_kv_static: as attend_kv with caller-provided outputs; the call itself allocates nothing."""
+    dt = _torch_dtype(p)
+    n_seq, stride, d = K_c.shape
+    _, g, nq, _ = Q.shape
+    if count is None:
+        count = stride
+    rc = lib().bkv_attend_kv_static(C.byref(p), _ptr(K_c, dt, "K_c"), _ptr(V_c, dt, "V_c"), _ptr(w, torch.float32, "w"),
+                                    n_seq, count, stride, _ptr(Q, dt, "Q"), g, nq, _ptr(out, dt, "out"),
+                                    _ptr(lse, torch.float32, "lse"), _stream())
+    _check(rc, "bkv_attend_kv_static")
+    return out, lse
 
 
 # ------------------------------------------------------------------------------------------ Alg. 1: buckets, two instances

@@ -298,9 +298,10 @@ size_t bkv_attend_workspace_bytes(const bkv_params* p, int64_t n_seq, int64_t co
 
 }  // extern "C"
 
+// exact_need: the workspace need only hold what this very launch writes (else: the public, count-independent bound)
 static int attend_kv_impl(const bkv_params* p, const void* K_c, const void* V_c, const float* w, int64_t n_seq,
                           int64_t count, int64_t stride_tokens, const void* Q, int32_t g, int32_t nq, void* out,
-                          float* lse_out, void* workspace, size_t ws_bytes, void* hip_stream) {
+                          float* lse_out, void* workspace, size_t ws_bytes, bool exact_need, void* hip_stream) {
     int rc = check_params(p);
     if (rc) return rc;
     if (n_seq < 0 || count < 0 || stride_tokens < count || g <= 0 || nq <= 0) return BKV_EINVAL;
@@ -317,7 +318,8 @@ static int attend_kv_impl(const bkv_params* p, const void* K_c, const void* V_c,
         return BKV_OK;
     }
     if (!K_c || !V_c || !w || !aligned16(K_c) || !aligned16(V_c)) return BKV_EINVAL;
-    const size_t need = bkv::attend_workspace_bytes(p->d, n_seq, n_q);
+    const size_t need = exact_need ? bkv::attend_partial_bytes(p->dtype, p->d, n_seq, count, n_q)
+                                   : bkv::attend_workspace_bytes(p->d, n_seq, n_q);
     if (!workspace || ws_bytes < need || !aligned16(workspace)) return BKV_EWORKSPACE;
     bkv::AttendArgs a;
     memset(&a, 0, sizeof(a));
@@ -333,8 +335,28 @@ extern "C" {
 int bkv_attend_kv(const bkv_params* p, const void* K_c, const void* V_c, const float* w, int64_t n_seq,
                   int64_t count, int64_t stride_tokens, const void* Q, int32_t g, int32_t nq, void* out,
                   float* lse_out, void* workspace, size_t ws_bytes, void* hip_stream) {
-    return attend_kv_impl(p, K_c, V_c, w, n_seq, count, stride_tokens, Q, g, nq, out, lse_out, workspace, ws_bytes,
+    return attend_kv_impl(p, K_c, V_c, w, n_seq, count, stride_tokens, Q, g, nq, out, lse_out, workspace, ws_bytes, false,
                           hip_stream);
+}
+
+size_t bkv_attend_kv_static_max_bytes(void) { return bkv::kAttendStaticScratchBytes; }
+
+int bkv_attend_kv_static(const bkv_params* p, const void* K_c, const void* V_c, const float* w, int64_t n_seq,
+                         int64_t count, int64_t stride_tokens, const void* Q, int32_t g, int32_t nq, void* out,
+                         float* lse_out, void* hip_stream) {
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (n_seq < 0 || count < 0 || g <= 0 || nq <= 0) return BKV_EINVAL;
+    if (n_seq > 65535 || (int64_t)g * nq > 4 * 65535) return BKV_ESHAPE;
+    // what this launch would write into the partial buffer must fit the library's static array
+    if (bkv::attend_partial_bytes(p->dtype, p->d, n_seq, count, g * nq) > bkv::kAttendStaticScratchBytes) return BKV_EWORKSPACE;
+    void* ws = nullptr;
+    const hipError_t e = bkv::attend_static_scratch(&ws);
+    if (e != hipSuccess) return hip_fail(e);
+    // The partials of a launch are written in full before its merge reads them, so nothing has to be cleared between
+    // calls; two calls in flight on one GPU at the same time would share the array and race.
+    return attend_kv_impl(p, K_c, V_c, w, n_seq, count, stride_tokens, Q, g, nq, out, lse_out, ws,
+                          bkv::kAttendStaticScratchBytes, true, hip_stream);
 }
 
 // ------------------------------------------------------------------------------------------ Alg. 1: buckets, two instances

@@ -348,6 +348,40 @@ static hipError_t launch_attend_t(AttendArgs& a, int64_t n_seq, int n_qg, hipStr
                         a, n_qg);
 }
 
+// Bytes of split partials that a launch with this shape writes (0 when the token range is a single split: the
+// streaming pass then stores the result itself).
+size_t attend_partial_bytes(int dtype, int d, int64_t n_seq, int64_t count, int n_q) {
+    if (n_seq <= 0 || n_q <= 0) return 0;
+    int n_qg, ns, rps;
+    attend_plan(d, dtype == BKV_BF16 ? 2 : 4, n_seq, count, n_q, &n_qg, &ns, &rps);
+    if (ns <= 1) return 0;
+    return (size_t)n_seq * n_qg * ns * kQT * (d + 2) * sizeof(float);
+}
+
+// Scratch of the entry point that allocates nothing: the split partials live in this array instead of a caller's
+// workspace.  Every GPU holds its own copy at its own address; host code uses the address that
+// hipGetSymbolAddress returns for the current device, never the array's name.
+static __device__ __align__(256) unsigned char scratch[kAttendStaticScratchBytes];
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];           // per device, filled at the first call on that device
+}
+hipError_t attend_static_scratch(void** ptr) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
 hipError_t launch_attend(int dtype, int d, AttendArgs& a, int64_t n_seq, void* workspace, hipStream_t st) {
     if (n_seq <= 0 || a.n_q <= 0) return hipSuccess;
     if (n_seq > 65535) return hipErrorInvalidValue;

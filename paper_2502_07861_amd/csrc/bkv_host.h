@@ -135,5 +135,10 @@ struct AttendArgs {
 };
 size_t attend_workspace_bytes(int d, int64_t n_seq, int n_q);
 hipError_t launch_attend(int dtype, int d, AttendArgs& a, int64_t n_seq, void* workspace, hipStream_t st);
+// the entry point without allocations: what a launch of this shape writes into the partial buffer, and the
+// library's own buffer for it (a file-scope device array; address of the current device's copy)
+constexpr size_t kAttendStaticScratchBytes = 2304 * 1024;
+size_t attend_partial_bytes(int dtype, int d, int64_t n_seq, int64_t count, int n_q);
+hipError_t attend_static_scratch(void** ptr);
 
 }  // namespace bkv

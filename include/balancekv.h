@@ -46,7 +46,7 @@ extern "C" {
 /* flags */
 #define BKV_CENTER_KEYS 1u  /* shift keys by the block mean for the selection (App. B.5 item 1) */
 #define BKV_STRICT_HALF 2u  /* keep exactly block/2 per block (App. B, Implementation Detail); required */
-#define BKV_VALUE_GRAM  4u  /* multiply kernel weights by <v_i,v_j>/r_value^2 (Alg. 2 line 5): the walk then balances
+#define BKV_VALUE_GRAM  4u  /* multiply kernel weights by <v_i,v_j>/r_value^2 (Alg. 2 line 6): the walk then balances
                              * the numerator instance of Alg. 1.  Fast where keys and values of a block fit the
                              * 160 KB of LDS together (d=128: block <= 256 bf16 / 128 fp32; d=64: block <= 512 bf16 /
                              * 256 fp32); larger blocks read the value panels from L2 tile by tile.  V is required
@@ -62,9 +62,10 @@ extern "C" {
 #define BKV_ECAPACITY  -5   /* the streaming cache is full                                     */
 
 /* status word written per instance (bkv_compress_block) */
-#define BKV_STATUS_FAIL 1   /* bit 0: |y^T eta| > c R^2 happened (Alg. 2 line 6); p was clamped */
+#define BKV_STATUS_FAIL 1   /* bit 0: |y^T eta| > c R^2 happened (Alg. 2 line 7); p was clamped */
 #define BKV_STATUS_INTERNAL 2 /* bit 1: the kernel's internal pipeline timed out; the instance's outputs are invalid (never expected) */
-/* bits 8..31: number of decisions whose margin |u_j - p_j| was below 1e-4 */
+/* bits 8..30: number of decisions whose margin |u_j - p_j| was below 1e-4 (per-sequence words of the tree calls
+ * add the counts of their blocks and saturate at 2^23 - 1); bit 31 is never set */
 
 typedef struct bkv_params {
     int32_t  d;        /* head dimension                                                       */
@@ -87,7 +88,7 @@ int         bkv_last_hip_error(void);          /* hipError_t of the last BKV_EHI
 
 /* The uniform draw of decision `ctr` in stream `stream`: top 24 bits of two rounds of the
  * SplitMix64 mixer over (seed, stream, ctr); u = bits * 2^-24 in [0,1).  Host function, same
- * integers as the device code.  Alg. 2 line 8 sets eta_j = +1 iff u_j < p_j.                    */
+ * integers as the device code.  Alg. 2 line 9 sets eta_j = +1 iff u_j < p_j.                    */
 uint32_t bkv_uniform_bits(uint64_t seed, uint64_t stream, uint64_t ctr);
 
 /* ---- Alg. 2: one halving of n_inst independent blocks ---------------------------------------
@@ -103,7 +104,7 @@ uint32_t bkv_uniform_bits(uint64_t seed, uint64_t stream, uint64_t ctr);
  * status_out    [n_inst] int32 or NULL (BKV_STATUS_*).
  * stats_out     [n_inst, 2] fp32 or NULL: {min_j |u_j - p_j|, max_j |y^T eta|/(c R^2)}.
  * workspace     bkv_compress_workspace_bytes() bytes (may be 0 => NULL allowed).
- * Kernel weights are exp((<k_i,k_j> - r_key^2)/sqrt(d) - ln c) (Alg. 2 lines 2-7 divided
+ * Kernel weights are exp((<k_i,k_j> - r_key^2)/sqrt(d) - ln c) (Alg. 2 lines 2-8 divided
  * through by c R^2), keys optionally centred by the block mean, times <v_i,v_j>/r_value^2 with
  * BKV_VALUE_GRAM (V then must be given; a block of all-zero values has weight 0 everywhere);
  * n_inst == 0 is a no-op.                                                                        */
@@ -115,7 +116,7 @@ int bkv_compress_block(const bkv_params* p, const void* K, const void* V, int64_
                        void* workspace, size_t ws_bytes, void* hip_stream);
 
 /* The kernel-weight matrix itself, for inspection: G_out [n_inst, block, block] fp32, entry
- * (i,j) = exp((<k_i,k_j> - r_key^2)/sqrt(d) - ln c) as the walk sees it (Alg. 2 line 5, v = 1).
+ * (i,j) = exp((<k_i,k_j> - r_key^2)/sqrt(d) - ln c) as the walk sees it (Alg. 2 line 6, v = 1).
  * Symmetric; produced by the same tile code as the walk.  BKV_VALUE_GRAM: BKV_ESHAPE (no values
  * are passed here).                                                                              */
 int bkv_kernel_weights(const bkv_params* p, const void* K, int64_t n_inst, float* G_out,
@@ -197,7 +198,7 @@ int bkv_attend_kv_static(const bkv_params* p, const void* K_c, const void* V_c, 
  * than `block` tokens (weight 1).
  *   which = BKV_SET_NUMERATOR   Alg. 1 lines 5-10: token j goes to bucket i, the smallest i with
  *           2^i >= |v_j| (|v_j|^2 accumulated in fp32; i is clamped to [-60, 60]); every bucket is an
- *           instance with the value factor of Alg. 2 line 5 and r_value = 2^i; buckets with
+ *           instance with the value factor of Alg. 2 line 6 and r_value = 2^i; buckets with
  *           2^i <= eps/(2n) e^{-r^2/sqrt d} max_j |v_j| are erased (line 8; eps <= 0: none).  Rows with
  *           a zero or non-finite norm belong to no bucket.  The result is the union of the buckets'
  *           sets V^l, bucket by bucket in ascending i.  BKV_VALUE_GRAM need not be set in p.
@@ -265,6 +266,11 @@ int64_t bkv_cache_count(const bkv_cache* c);           /* stored tokens per sequ
 int64_t bkv_cache_tokens_seen(const bkv_cache* c);     /* tokens appended since init / load (j)     */
 /* Device views of the storage: K, V [n_seq, max_tokens, d], w [n_seq, max_tokens].                  */
 int bkv_cache_views(const bkv_cache* c, void** K, void** V, float** w);
+/* One int32 in the cache's device storage, cleared by bkv_cache_init: every halving that runs for this cache
+ * (bkv_cache_prefill, the carries of bkv_append_token) ORs BKV_STATUS_INTERNAL into it if its pipeline timed out,
+ * whether or not the call was given a status array.  Non-zero: survivors written since the last init are not to be
+ * trusted.  The pointer is a device pointer; read it in stream order (no call here synchronises).       */
+int bkv_cache_error_word(const bkv_cache* c, const int32_t** device_word);
 
 /* One streaming step: k, v [n_seq, d] (one new token per sequence) go to the tail with weight 1;
  * after every block-th token the carry loop of Alg. 3 runs (up to T halvings of the last `block`
@@ -296,6 +302,24 @@ int bkv_attend(const bkv_cache* c, const void* Q, int32_t g, int32_t nq, void* o
  * bkv_profile_enable(0) turns it off.  Not thread-safe; off by default.                             */
 int bkv_profile_enable(int32_t max_records);
 int bkv_profile_read(int32_t* kind, float* ms, int64_t* units, int32_t cap);
+
+/* ---- diagnostics: measured peaks of this GPU --------------------------------------------------------
+ * Micro-benchmarks that give the roofline fractions a measured denominator next to the vendor's:
+ *   BKV_PEAK_MFMA_BF16    every wavefront of every compute unit issues 32x32x16 bf16 MFMAs back to back  -> FLOP/s
+ *   BKV_PEAK_TILE_BF16    the halving kernel's tile routine alone on all compute units: 64x64 Gram tiles of bf16
+ *                         rows (d = 128) from LDS, kernel weights exp2(alpha S + row term), signed column sums; no
+ *                         walk, no waits, no HBM traffic                                -> FLOP/s of executed MFMA work
+ *   BKV_PEAK_STREAM_READ  one pass of 16-byte loads over the workspace                                  -> bytes/s
+ *   BKV_PEAK_STREAM_COPY  first half of the workspace copied to the second half                 -> bytes/s (read + written)
+ * Runs the kernel `launches` times between two events, waits for them (this call synchronises) and reports the rate
+ * and the time of one launch.  workspace: device memory, >= 8 MiB; the streaming kinds move all of it (use >= 1 GiB
+ * to get past the caches).                                                                            */
+#define BKV_PEAK_MFMA_BF16   0
+#define BKV_PEAK_TILE_BF16   1
+#define BKV_PEAK_STREAM_READ 2
+#define BKV_PEAK_STREAM_COPY 3
+int bkv_measure_peak(int32_t kind, int32_t launches, void* workspace, size_t ws_bytes, void* hip_stream,
+                     double* per_second, double* ms_per_launch);
 
 #ifdef __cplusplus
 }

@@ -16,7 +16,7 @@ The inputs are synthetic stand-ins (synth.gqa_layer_bf16, one layer of 8 KV head
 per head); the paper's tables are on Llama-3.1-8B / TriviaQA activations, so only the shape of the study carries over.
 ln c per block size was bisected once on the CPU oracle (oracle/tuning.py, mean |2p - 1| = 0.25 on the first two
 sequences) so that the walk's decisions depend on the kernel weights.  --value-factor: the walk's weights carry the
-value factor <v_i,v_j>/r_value^2 of Alg. 2 line 5 (the numerator instance of Alg. 1 selects the kept set), with its own
+value factor <v_i,v_j>/r_value^2 of Alg. 2 line 6 (the numerator instance of Alg. 1 selects the kept set), with its own
 ln c per block size found the same way.
 """
 from __future__ import annotations
@@ -73,7 +73,7 @@ def normaliser_error(lse, lse_exact):
 
 def run(seeds=10, blocks=BLOCKS, rounds=ROUNDS, n_mid=N_MID, n_seq=8, device="cuda", nq=64, keep_outputs=False,
         value_gram=False):
-    """The grid.  value_gram: kernel weights with the value factor of Alg. 2 line 5.  keep_outputs: every cell also carries the tensors of its first counted seed (kept indices, weights,
+    """The grid.  value_gram: kernel weights with the value factor of Alg. 2 line 6.  keep_outputs: every cell also carries the tensors of its first counted seed (kept indices, weights,
     both estimates, the uniform comparator's indices) and the result the inputs, for checking against a reference."""
     K, V, Q = make_inputs(device, n_seq=n_seq, n_mid=n_mid, nq=nq)
     n, d = K.shape[1], K.shape[2]
@@ -198,7 +198,7 @@ def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--seeds", type=int, default=10)
     ap.add_argument("--json", action="store_true", help="print one JSON line instead of the table")
-    ap.add_argument("--value-factor", action="store_true", help="kernel weights times <v_i,v_j>/r_value^2 (Alg. 2 line 5)")
+    ap.add_argument("--value-factor", action="store_true", help="kernel weights times <v_i,v_j>/r_value^2 (Alg. 2 line 6)")
     ap.add_argument("--alg1", action="store_true", help="Alg. 1 as listed (buckets, two kept sets) on heavy-tailed value norms")
     args = ap.parse_args(argv)
     if not torch.cuda.is_available():

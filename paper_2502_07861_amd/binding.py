@@ -69,10 +69,12 @@ _SIGNATURES = {
     "bkv_cache_count": (_i64, [_vp]),
     "bkv_cache_tokens_seen": (_i64, [_vp]),
     "bkv_cache_views": (C.c_int, [_vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_vp)]),
+    "bkv_cache_error_word": (C.c_int, [_vp, C.POINTER(_vp)]),
     "bkv_append_workspace_bytes": (_sz, [_vp]),
     "bkv_append_token": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bkv_cache_attend_workspace_bytes": (_sz, [_vp, _i32, _i32]),
     "bkv_attend": (C.c_int, [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
+    "bkv_measure_peak": (C.c_int, [_i32, _i32, _vp, _sz, _vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "bkv_profile_enable": (C.c_int, [_i32]),
     "bkv_profile_read": (C.c_int, [_vp, _vp, _vp, _i32]),
 }
@@ -397,6 +399,15 @@ class Cache:
                                 _stream()), "bkv_attend")
         return out, lse_t
 
+    def error_word(self) -> int:
+        """The cache's sticky error word (bkv_cache_error_word), read after a synchronisation of the current stream."""
+        ptr = C.c_void_p()
+        _check(lib().bkv_cache_error_word(self.h, C.byref(ptr)), "bkv_cache_error_word")
+        off = ptr.value - self.storage.data_ptr()
+        assert 0 <= off and off + 4 <= self.storage.numel()
+        torch.cuda.current_stream().synchronize()
+        return int(self.storage[off:off + 4].view(torch.int32).item())
+
     def views(self):
         """Device views K, V [n_seq, cap, d], w [n_seq, cap] of the storage (no copy): the pointers come from
         bkv_cache_views, the layout of the storage stays the library's business."""
@@ -425,6 +436,18 @@ def profile_read(cap: int = 4096):
     units = (C.c_int64 * cap)()
     n = _check(lib().bkv_profile_read(kind, ms, units, cap), "bkv_profile_read")
     return [(int(kind[i]), float(ms[i]), int(units[i])) for i in range(n)]
+
+
+def peaks(stream_bytes: int = 4 << 30, launches: int = 10):
+    """bkv_measure_peak for the four kinds: {name: {"per_second": ..., "ms_per_launch": ...}} (FLOP/s or bytes/s)."""
+    ws = torch.empty(stream_bytes, device="cuda", dtype=torch.uint8)
+    ws.view(torch.int32).random_()
+    res = {}
+    for kind, name in enumerate(("mfma_bf16_flops", "tile_bf16_flops", "stream_read_bytes", "stream_copy_bytes")):
+        rate, ms = C.c_double(), C.c_double()
+        _check(lib().bkv_measure_peak(kind, launches, _ptr(ws), ws.numel(), _stream(), C.byref(rate), C.byref(ms)), "bkv_measure_peak")
+        res[name] = {"per_second": rate.value, "ms_per_launch": ms.value}
+    return res
 
 
 def literal_log_c(block: int, delta: float) -> float:

@@ -62,6 +62,7 @@ struct bkv_cache {
     int64_t count;        // stored tokens per sequence
     int64_t base_count;   // adopted survivors (never touched by carries)
     int64_t stream_j;     // tokens appended since init/load (the j of Alg. 3)
+    int32_t* err;         // device word behind the weights: sticky BKV_STATUS_INTERNAL of every halving run for this cache
 };
 
 extern "C" {
@@ -155,7 +156,8 @@ struct TreeWindow { int64_t k_stride, v_stride, idx_base, idx_out_stride; };
 static int merge_reduce_impl(const bkv_params* p, const void* K, const void* V, int64_t n_seq, int64_t n,
                              int64_t seq_base, void* K_out, void* V_out, float* w_out, int64_t out_stride,
                              int32_t* idx_out, int8_t* signs_out, int32_t* status_out, void* workspace,
-                             size_t ws_bytes, void* hip_stream, const TreeWindow* win = nullptr) {
+                             size_t ws_bytes, void* hip_stream, const TreeWindow* win = nullptr,
+                             int32_t* sticky_err = nullptr) {
     const int64_t k_stride = win && win->k_stride ? win->k_stride : n;
     const int64_t v_stride = win && win->v_stride ? win->v_stride : n;
     const int64_t idx_base = win ? win->idx_base : 0;
@@ -218,7 +220,7 @@ static int merge_reduce_impl(const bkv_params* p, const void* K, const void* V, 
         a.idx_in = i_in;
         a.idx_out = last ? idx_final : ibuf[r & 1];
         a.signs_out = signs_out ? signs_out + (size_t)n_seq * (size_t)(2 * n - ((2 * n) >> r)) : nullptr;
-        a.status_out = status_out; a.status_stride = T;
+        a.status_out = status_out; a.status_stride = T; a.sticky_err = sticky_err;
         a.in_seq_stride = r == 0 ? k_stride : m; a.out_seq_stride = last ? out_stride : m / 2;
         a.idx_out_seq_stride = (last && idx_out && win && win->idx_out_stride) ? win->idx_out_stride : m / 2;
         a.blocks_per_seq = (int32_t)(m / b);
@@ -288,6 +290,14 @@ int bkv_profile_enable(int32_t max_records) { return bkv::prof_enable(max_record
 int bkv_profile_read(int32_t* kind, float* ms, int64_t* units, int32_t cap) {
     if (!kind || !ms || !units || cap < 0) return BKV_EINVAL;
     return bkv::prof_read(kind, ms, units, cap);
+}
+
+int bkv_measure_peak(int32_t kind, int32_t launches, void* workspace, size_t ws_bytes, void* hip_stream,
+                     double* per_second, double* ms_per_launch) {
+    if (kind < BKV_PEAK_MFMA_BF16 || kind > BKV_PEAK_STREAM_COPY || launches <= 0 || !per_second || !ms_per_launch) return BKV_EINVAL;
+    if (!workspace || !aligned16(workspace) || ws_bytes < ((size_t)8 << 20)) return BKV_EWORKSPACE;
+    const hipError_t e = bkv::measure_peak(kind, launches, workspace, ws_bytes, (hipStream_t)hip_stream, per_second, ms_per_launch);
+    return e == hipSuccess ? BKV_OK : hip_fail(e);
 }
 
 // ------------------------------------------------------------------------------------------ estimator
@@ -471,7 +481,7 @@ int bkv_attend_sets(const bkv_params* p, const void* K_n, const void* V_n, const
 size_t bkv_cache_bytes(const bkv_params* p, int64_t n_seq, int64_t max_tokens) {
     if (check_params(p) || n_seq <= 0 || max_tokens < p->block) return 0;
     const size_t rb = (size_t)row_bytes(p);
-    return 2 * align_up((size_t)n_seq * max_tokens * rb, 256) + align_up((size_t)n_seq * max_tokens * 4, 256);
+    return 2 * align_up((size_t)n_seq * max_tokens * rb, 256) + align_up((size_t)n_seq * max_tokens * 4, 256) + 256;
 }
 
 int bkv_cache_init(bkv_cache** out, const bkv_params* p, int64_t n_seq, int64_t max_tokens, void* device_storage,
@@ -489,6 +499,7 @@ int bkv_cache_init(bkv_cache** out, const bkv_params* p, int64_t n_seq, int64_t 
     const size_t rb = (size_t)row_bytes(p);
     const size_t kv = align_up((size_t)n_seq * max_tokens * rb, 256);
     c->K = (char*)device_storage; c->V = c->K + kv; c->w = (float*)(c->V + kv);
+    c->err = (int32_t*)((char*)c->w + align_up((size_t)n_seq * max_tokens * 4, 256));
     c->count = c->base_count = c->stream_j = 0;
     // weights start at 0 (= absent); K, V start finite so that masked lanes never meet NaN payloads
     hipError_t e = bkv::launch_fill_u32(device_storage, 0u, (int64_t)(need / 4), (hipStream_t)hip_stream);
@@ -526,7 +537,7 @@ int bkv_cache_prefill(bkv_cache* c, const bkv_params* p, const void* K, const vo
     if (p->d != c->p.d || p->dtype != c->p.dtype) return BKV_ESHAPE;
     if (n < 0 || (n >> p->rounds) > c->cap) return BKV_ECAPACITY;
     rc = merge_reduce_impl(p, K, V, c->n_seq, n, 0, c->K, c->V, c->w, c->cap, nullptr, nullptr, status_out, workspace,
-                           ws_bytes, hip_stream);
+                           ws_bytes, hip_stream, nullptr, c->err);
     if (rc) return rc;
     c->count = c->base_count = n >> p->rounds;
     c->stream_j = 0;
@@ -547,6 +558,12 @@ int bkv_cache_views(const bkv_cache* c, void** K, void** V, float** w) {
     if (K) *K = c->K;
     if (V) *V = c->V;
     if (w) *w = c->w;
+    return BKV_OK;
+}
+
+int bkv_cache_error_word(const bkv_cache* c, const int32_t** device_word) {
+    if (!c || !device_word) return BKV_EINVAL;
+    *device_word = c->err;
     return BKV_OK;
 }
 
@@ -586,7 +603,7 @@ int bkv_append_token(bkv_cache* c, const void* k, const void* v, int32_t* status
         fill_common(a, &c->p);
         a.K = c->K + (size_t)first * rb; a.V = c->V + (size_t)first * rb;
         a.K_out = tmpK; a.V_out = tmpV;
-        a.status_out = status_out; a.status_stride = T;
+        a.status_out = status_out; a.status_stride = T; a.sticky_err = c->err;
         // decision-level hooks: the halving of level i reads / writes slice i of [T, n_seq, block]
         a.uniforms = uniforms ? uniforms + (size_t)i * c->n_seq * b : nullptr;
         a.signs_out = signs_out ? signs_out + (size_t)i * c->n_seq * b : nullptr;

@@ -14,7 +14,7 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 
 // ---------------------------------------------------------------------------------------------
-// Counter-based draws for "eta_j = +1 with probability p_j" (Alg. 2 line 8): two rounds of the
+// Counter-based draws for "eta_j = +1 with probability p_j" (Alg. 2 line 9): two rounds of the
 // SplitMix64 output mixer over (seed, stream, counter); the top 24 bits give u = bits * 2^-24.
 // Integer-only, so host and device agree bit for bit.
 // ---------------------------------------------------------------------------------------------

@@ -31,6 +31,7 @@ struct CompressArgs {
     int8_t* signs_out;
     int32_t* status_out;
     float* stats_out;
+    int32_t* sticky_err;      // or null: one word that collects BKV_STATUS_INTERNAL of every instance (never cleared by the kernel)
     const uint64_t* inst_ids;
     const float* uniforms;
     const InstDesc* desc;     // ragged launches: per-instance coordinates (then blocks_per_seq, strides and bases are not read)
@@ -94,6 +95,9 @@ inline hipError_t launch_timed(int kind, int64_t units, Kern kern, dim3 grid, di
     else hipLaunchKernelGGL(kern, grid, block, lds, st, args...);
     return hipGetLastError();
 }
+
+// peak micro-benchmarks (diagnostics): kind 0 bare bf16 MFMA loop, 1 the tile routine alone, 2 streaming read, 3 streaming copy
+hipError_t measure_peak(int kind, int launches, void* workspace, size_t ws_bytes, hipStream_t st, double* per_second, double* ms_per_launch);
 
 // Alg. 1's kept sets (sets.hip): value-norm buckets with one MergeAndReduce instance each (numerator = 1), or the
 // keys-only instance over the whole sequence (numerator = 0), brought to the state Alg. 3 reaches after the last token.

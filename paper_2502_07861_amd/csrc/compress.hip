@@ -61,7 +61,7 @@ static inline size_t lds_fixed_bytes(int b) {
            + 128;                        // progress counters of the panel pipeline
 }
 // rows of the block staged in LDS at a time: as many 64-row panels as fit, at most 8
-// (with the value factor of Alg. 2 line 5 the value rows are staged next to the key rows: twice the bytes per row)
+// (with the value factor of Alg. 2 line 6 the value rows are staged next to the key rows: twice the bytes per row)
 static inline int chunk_rows_for(int row_bytes, int b, bool value_gram = false) {
     const int rb = value_gram ? 2 * row_bytes : row_bytes;
     int rows = 512;
@@ -155,7 +155,7 @@ struct TileOps {
     // With BREG the column panel's fragments come from the caller's registers too (Bq), e.g. a panel that a
     // wavefront keeps for all tiles of its column.
     // With DIAG (a diagonal tile, not dumped) the quadrant rows 32..63 x columns 0..31, which the walk never uses, is skipped.
-    // With VG the weights carry the value factor of Alg. 2 line 5: the Gram of the value rows of the same two panels
+    // With VG the weights carry the value factor of Alg. 2 line 6: the Gram of the value rows of the same two panels
     // is formed first, scaled by 1 / r_value^2, and multiplies every weight after its exp2.  VG = 1: the value rows are
     // in LDS in the layout of the keys (vA: the 64 rows that match the tile's rows, vB: those that match its columns).
     // VG = 2: they are read from global memory; vA / vA1 are THIS LANE's rows n and n + 32 of the row panel, vB / vB1 of
@@ -451,7 +451,7 @@ struct TileOps {
     }
 };
 
-// One decision of the walk (Alg. 2 lines 5-9 for token j of the panel).  Every lane tests the sign of its sigma
+// One decision of the walk (Alg. 2 lines 6-9 for token j of the panel).  Every lane tests the sign of its sigma
 // (which carries the threshold, see the kernel); the compare mask is then read back as data by the vector unit:
 // bit j of it, sign-extended, becomes the -1/+1 that multiplies row j of the diagonal tile.  No scalar-unit hop
 // on the chain: four dependent vector instructions per step.  A vector instruction that reads a scalar register
@@ -571,7 +571,7 @@ __device__ __forceinline__ float await_and_read(int* counter, int value, const f
 
 // MULTI = false: the launcher guarantees b <= chunk_rows (the block is resident in LDS as one chunk), and the
 // multi-chunk code is compiled out.
-// VG != 0: the kernel weights carry the value factor <v_i,v_j> / r_value^2 of Alg. 2 line 5.  VG = 1 (resident blocks
+// VG != 0: the kernel weights carry the value factor <v_i,v_j> / r_value^2 of Alg. 2 line 6.  VG = 1 (resident blocks
 // whose values fit LDS too): the block's value rows are staged in LDS behind the key rows.  VG = 2 (any block): the
 // value panels of every tile are read from global memory (L2) as they are needed.
 template <typename T, int D, bool EMIT_G, bool MULTI, int VG = 0>
@@ -1014,7 +1014,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             __builtin_amdgcn_s_setprio(3);                    // the serial chain goes first on its SIMD
             for (int l = 0; l < nPc; ++l) {
                 const int I = p0 + l;
-                // ------------------------------------------------ the walk over panel I (Alg. 2 lines 4-10)
+                // ------------------------------------------------ the walk over panel I (Alg. 2 lines 4-11)
                 // this lane's column of the diagonal tile: g[j] = g_{j,lane} for j < lane, else 0
                 // sigma holds (sum of signed weights so far) - (1 - 2 u): eta = +1 <=> u < 1/2 - s/2 <=> sigma < 0; it is
                 // complete when the owner of this column panel says so (col[l] == l)
@@ -1205,7 +1205,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             for (int p = 0; p < nP; ++p)
                 a.signs_out[(size_t)signs0 + (p << 6) + lane] = ((etaMask[p] >> lane) & 1ull) ? 1 : -1;
     } else if (wave == 2 && (a.status_out || a.stats_out)) {
-        // walk statistics from the decision-time values: FAIL events (Alg. 2 line 6), near-tie decisions
+        // walk statistics from the decision-time values: FAIL events (Alg. 2 line 7), near-tie decisions
         int n_margin = 0, any_fail = 0;
         float min_margin = 3.0e38f, max_sigma = 0.f;
         for (int p = 0; p < nP; ++p) {
@@ -1227,7 +1227,19 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     int* dst = a.status_out + seq * a.status_stride + a.round;
                     if (any_fail) atomicOr(dst, BKV_STATUS_FAIL);
                     if (sync_failed) atomicOr(dst, BKV_STATUS_INTERNAL);
-                    if (n_margin) atomicAdd(dst, n_margin << 8);
+                    if (n_margin) {
+                        // the count lives in bits 8..30 and saturates there: bit 31 is never set.  Margin decisions
+                        // are rare, so the compare-and-swap loop (it ends when no other block updates the word in
+                        // between) is next to never entered twice.
+                        int seen = __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        for (;;) {
+                            const int cnt = min((seen >> 8) + n_margin, 0x7fffff);
+                            const int want = (seen & 0xff) | (cnt << 8);
+                            const int prev = atomicCAS(dst, seen, want);
+                            if (prev == seen) break;
+                            seen = prev;
+                        }
+                    }
                 } else {
                     a.status_out[inst] = word;
                 }
@@ -1238,6 +1250,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             }
         }
     }
+    // a pipeline time-out also goes to the caller's sticky word (a streaming cache has one), whether or not a status
+    // array was passed
+    if (a.sticky_err && tid == 0 && prog[3]) atomicOr(a.sticky_err, BKV_STATUS_INTERNAL);
     const int half = b >> 1;
     // survivors: rows of the ORIGINAL keys / values, ascending index (16-byte slices, several rows in flight)
     auto src_token = [&](int r) -> int64_t {      // token of survivor r within its sequence, in the value tensor's frame
@@ -1488,6 +1503,149 @@ hipError_t launch_fill_iota(int32_t* idx, int64_t n_seq, int64_t seq_stride, int
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(fill_iota_kernel, dim3((unsigned)blocks), dim3(256), 0, st, idx, seq_stride, off, rows, first, total);
     return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Peak micro-benchmarks (diagnostics): what this GPU reaches on the two units the halving kernel is measured against,
+// with nothing else in the way.  They give the denominators of "fraction of the measured peak" next to the vendor's.
+// ------------------------------------------------------------------------------------------------
+// (1) The matrix pipe alone: every wavefront issues 32x32x16 bf16 MFMAs on four independent accumulators.
+__global__ __launch_bounds__(kThreads) void peak_mfma_kernel(float* out, int iters) {
+    const int tid = threadIdx.x;
+    bf16x8_t a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(float)((tid + e) & 3); b[e] = (__bf16)(float)((tid ^ e) & 1); }
+    const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    floatx16 acc[4] = {zero, zero, zero, zero};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[u], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += acc[u][r];
+    out[(size_t)blockIdx.x * kThreads + tid] = sum;
+}
+// (2) The tile routine alone: one workgroup of 8 wavefronts keeps 512 bf16 rows of 128 columns in LDS; every wavefront
+// takes one 64-row panel as the A operand (registers) and sweeps the 8 column panels, forming for each 64x64 tile the
+// Gram, the kernel weights exp2(alpha S + row term) and the signed column sums, exactly as the halving kernel does for
+// rows whose signs are known: no walk, no waiting, no HBM traffic after the first fill.  Repeated `iters` times.
+__global__ __launch_bounds__(kThreads) void peak_tile_kernel(float* out, int iters) {
+    typedef Geo<__bf16, 128> G;
+    typedef TileOps<__bf16, 128> Ops;
+    typedef typename Elem<__bf16>::Frag Frag;
+    extern __shared__ __align__(16) char smem[];
+    char* ldsK = smem;
+    float* aterm = reinterpret_cast<float*>(smem + (size_t)512 * G::kLdsRow);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, h = lane >> 5;
+    for (int i = tid; i < 512 * G::kSlices; i += kThreads) {           // small integers: exact products, moderate exponents
+        uintx4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const unsigned int x = (unsigned int)(i * 4 + e) * 2654435761u;
+            const unsigned int lo = 0x3f80u | ((x >> 7) & 0x8000u), hi = 0x3f80u | ((x >> 9) & 0x8000u);   // +-1.0 in bf16
+            v[e] = lo | (hi << 16);
+        }
+        const int row = i / G::kSlices, sl = i % G::kSlices;
+        *reinterpret_cast<uintx4*>(ldsK + (size_t)row * G::kLdsRow + G::slice_off(row, sl)) = v;
+    }
+    for (int i = tid; i < 512; i += kThreads) aterm[i] = -20.f;
+    __syncthreads();
+    int foff[G::kGroups];
+#pragma unroll
+    for (int g = 0; g < G::kGroups; ++g) foff[g] = G::slice_off(n, 2 * g + h);
+    Frag A[G::kGroups][2];
+    Ops::load_panel(A, ldsK + (size_t)(wave << 6) * G::kLdsRow, foff, n);
+    float total = 0.f;
+    for (int it = 0; it < iters; ++it)
+        Ops::row_sweep(A, ldsK, 8, aterm + (wave << 6), 0.1275f, 0x5a5a5a5a5a5a5a5aull + it, foff, n, h,
+                       [&](int, float cs) { total += cs; });
+    out[(size_t)blockIdx.x * kThreads + tid] = total;
+}
+// (3) Streaming: read `n16` 16-byte words once (XOR-folded into one word per thread), or copy them.
+__global__ __launch_bounds__(256) void peak_read_kernel(const uintx4* src, unsigned int* out, int64_t n16) {
+    unsigned int acc = 0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {                    // four independent loads in flight per lane
+        const uintx4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc ^= a[0] ^ a[1] ^ a[2] ^ a[3] ^ b[0] ^ b[1] ^ b[2] ^ b[3] ^ c[0] ^ c[1] ^ c[2] ^ c[3] ^ d[0] ^ d[1] ^ d[2] ^ d[3];
+    }
+    for (; i < n16; i += stride) { const uintx4 a = src[i]; acc ^= a[0] ^ a[1] ^ a[2] ^ a[3]; }
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = acc;
+}
+__global__ __launch_bounds__(256) void peak_copy_kernel(const uintx4* src, uintx4* dst, int64_t n16) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uintx4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+// Runs one of the above `launches` times between two events and reports work per second (FLOP/s of executed MFMA work,
+// or bytes/s moved).  Synchronises.  workspace: the streaming kernels use all of it (read: everything; copy: first half ->
+// second half); the other kernels keep their per-thread results in its first 4 MiB.
+hipError_t measure_peak(int kind, int launches, void* workspace, size_t ws_bytes, hipStream_t st, double* per_second, double* ms_per_launch) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    hipError_t e;
+    if ((e = hipGetDevice(&dev)) != hipSuccess || (e = hipGetDeviceProperties(&prop, dev)) != hipSuccess) return e;
+    const int n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+    hipEvent_t e0, e1;
+    if ((e = hipEventCreate(&e0)) != hipSuccess) return e;
+    if ((e = hipEventCreate(&e1)) != hipSuccess) { (void)hipEventDestroy(e0); return e; }
+    double work = 0.0;
+    const int iters_mfma = 4096, iters_tile = 16;
+    auto launch = [&]() {
+        switch (kind) {
+            case 0: {
+                hipLaunchKernelGGL(peak_mfma_kernel, dim3(n_cu), dim3(kThreads), 0, st, (float*)workspace, iters_mfma);
+                work = (double)n_cu * kWaves * iters_mfma * 4.0 * (2.0 * 32 * 32 * 16);
+                break;
+            }
+            case 1: {
+                const size_t lds = (size_t)512 * 256 + 512 * 4;
+                hipLaunchKernelGGL(peak_tile_kernel, dim3(n_cu), dim3(kThreads), lds, st, (float*)workspace, iters_tile);
+                work = (double)n_cu * kWaves * iters_tile * 8.0 * (2.0 * 64 * 64 * 128);
+                break;
+            }
+            case 2: {
+                const int64_t n16 = (int64_t)((ws_bytes - (4u << 20)) / 16);     // the first 4 MiB take the per-thread results
+                hipLaunchKernelGGL(peak_read_kernel, dim3(n_cu * 8), dim3(256), 0, st, (const uintx4*)((char*)workspace + (4u << 20)),
+                                   (unsigned int*)workspace, n16);
+                work = (double)n16 * 16.0;
+                break;
+            }
+            default: {
+                const int64_t n16 = (int64_t)(ws_bytes / 32);
+                hipLaunchKernelGGL(peak_copy_kernel, dim3(n_cu * 8), dim3(256), 0, st, (const uintx4*)workspace,
+                                   (uintx4*)((char*)workspace + n16 * 16), n16);
+                work = (double)n16 * 32.0;
+                break;
+            }
+        }
+    };
+    if (kind == 1) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(peak_tile_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 512 * 256 + 512 * 4);
+        if (e != hipSuccess) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return e; }
+    }
+    launch();                                            // warm-up
+    (void)hipEventRecord(e0, st);
+    for (int i = 0; i < launches; ++i) launch();
+    (void)hipEventRecord(e1, st);
+    e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return e;
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    *ms_per_launch = (double)ms / launches;
+    *per_second = work * launches / ((double)ms * 1e-3);
+    return hipSuccess;
 }
 
 // ------------------------------------------------------------------------------------------------

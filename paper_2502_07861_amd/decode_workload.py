@@ -42,6 +42,7 @@ def main(argv=None):
     e[0].record(); cache.prefill(pre, K, V, status=status); e[1].record(); torch.cuda.synchronize()
     print("prefill of %d x %d tokens: %.1f ms (%.2e token-heads/s), internal-error bits: %d" % (n_seq, n, e[0].elapsed_time(e[1]), n_seq * n / e[0].elapsed_time(e[1]) * 1e3,
           int((status & 2).sum())), flush=True)
+    assert int((status & 2).sum()) == 0, "a halving pipeline timed out during the prefill"
     del K, V, t
     torch.cuda.empty_cache()
     gen = torch.Generator(device="cuda"); gen.manual_seed(9)
@@ -65,6 +66,7 @@ def main(argv=None):
     e[3].record(); torch.cuda.synchronize()
     print("1024 appends (%d halvings) + 9 attends: %.1f ms; internal-error bits: %d" % (carries, e[2].elapsed_time(e[3]), int((st2 & 2).sum())))
     assert carries == 3 and cache.count == (n >> 2) + 256
+    assert int((st2 & 2).sum()) == 0 and cache.error_word() == 0, "a halving pipeline timed out during the stream"
     cache.close()
     return 0
 

@@ -1,7 +1,7 @@
 """Writes tests/golden/uniform_bits.json from the CPU oracle only.
 
 The values freeze the counter-based generator that supplies the draws of
-Alg. 2 line 8 ("+1 with probability p_j"), so that an accidental change of the
+Alg. 2 line 9 ("+1 with probability p_j"), so that an accidental change of the
 mixing function is caught.  Run:  python tests/golden/make_golden.py
 """
 import json

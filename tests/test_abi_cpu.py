@@ -111,7 +111,7 @@ def test_misuse_is_rejected_before_any_launch(bk):
     h = C.c_void_p()
     assert L.bkv_cache_init(C.byref(h), C.byref(ok), 4, 100, one, 1 << 30, None) == bk.BKV_EINVAL   # cap < block
     assert L.bkv_cache_init(C.byref(h), C.byref(ok), 4, 4096, None, 0, None) == bk.BKV_EINVAL
-    assert L.bkv_cache_bytes(C.byref(ok), 4, 4096) == 2 * 4 * 4096 * 256 + 4 * 4096 * 4
+    assert L.bkv_cache_bytes(C.byref(ok), 4, 4096) == 2 * 4 * 4096 * 256 + 4 * 4096 * 4 + 256      # K, V, w, the error word
     assert L.bkv_append_token(None, one, one, None, None, None, None, 0, None) == bk.BKV_EINVAL
     assert L.bkv_attend(None, one, 4, 1, one, None, None, 0, None) == bk.BKV_EINVAL
 

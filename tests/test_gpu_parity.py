@@ -55,9 +55,10 @@ def _log_c_setting(oracle, kind, Kd, b, center):
 @pytest.mark.parametrize("dtype,d,b,center", [
     (torch.float32, 64, 128, False), (torch.float32, 64, 256, True), (torch.bfloat16, 128, 192, True),
     (torch.bfloat16, 128, 1024, True), (torch.bfloat16, 64, 64, False), (torch.float32, 128, 320, True),
+    (torch.float32, 128, 640, True), (torch.float32, 128, 1024, False),      # fp32, d=128: three and four chunks of 256 rows
 ])
 def test_kernel_weights_match_definition(bk, synth, dtype, d, b, center):
-    """g_ij = exp((<k_i,k_j> - r_key^2)/sqrt d - ln c) (Alg. 2 lines 2-7, v = 1), centred keys optional."""
+    """g_ij = exp((<k_i,k_j> - r_key^2)/sqrt d - ln c) (Alg. 2 lines 2-8, v = 1), centred keys optional."""
     K, _ = _blocks(synth, dtype, d, b, 2, seed=101 + b)
     Kd = to_f64(K)
     Kc = Kd - Kd.mean(axis=1, keepdims=True) if center else Kd
@@ -89,6 +90,9 @@ CASES = [
     (torch.bfloat16, 64, 128, 5, True),
     (torch.float32, 128, 320, 2, True),      # ragged: 5 panels, second chunk of one panel
     (torch.bfloat16, 128, 64, 9, False),     # a single panel
+    (torch.float32, 128, 640, 2, True),      # fp32, d=128: chunks of 256 rows -> three chunks, the last of two panels
+    (torch.float32, 128, 1024, 2, True),     # ... four full chunks (the counters are reset three times)
+    (torch.bfloat16, 128, 960, 2, False),    # bf16: two chunks, the second of seven panels
 ]
 
 
@@ -153,13 +157,14 @@ VALUE_CASES = [
     (torch.float32, 128, 320, 2, True, 0.0),      # fp32, second chunk of one panel
     (torch.float32, 64, 512, 2, False, 12.0),     # radius given: no norm pass
     (torch.bfloat16, 64, 1024, 2, True, 0.0),
+    (torch.float32, 128, 640, 2, True, 0.0),      # fp32, d=128: three chunks of keys
 ]
 
 
 @pytest.mark.parametrize("dtype,d,b,n_inst,center,r_value", VALUE_CASES)
 @pytest.mark.parametrize("c_kind", ["one", "tuned"])
 def test_compress_block_with_value_factor(bk, synth, oracle, dtype, d, b, n_inst, center, r_value, c_kind):
-    """Alg. 2 line 5 with its value factor: weights exp(...) <v_i,v_j> / r_value^2, teacher-forced against the oracle."""
+    """Alg. 2 line 6 with its value factor: weights exp(...) <v_i,v_j> / r_value^2, teacher-forced against the oracle."""
     from oracle.tuning import tune_log_c
     K, V = _blocks(synth, dtype, d, b, n_inst, seed=311 + b + d)
     Kd, Vd = to_f64(K), to_f64(V)
@@ -244,7 +249,7 @@ def test_generator_on_device_equals_oracle_draws(bk, synth, oracle):
 
 
 def test_fail_branch_is_reported_not_fatal(bk, synth, oracle):
-    """ln c = -40 forces |y^T eta| > c R^2 (Alg. 2 line 6): status bit set, p clamped, output produced."""
+    """ln c = -40 forces |y^T eta| > c R^2 (Alg. 2 line 7): status bit set, p clamped, output produced."""
     dtype, d, b, n_inst = torch.float32, 64, 128, 3
     K, V = _blocks(synth, dtype, d, b, n_inst, seed=91)
     p = bk.make_params(d, b, 1, dtype, log_c=-40.0, seed=5)
@@ -607,7 +612,7 @@ def test_end_to_end_workload1_error_vs_exact(bk, synth, oracle):
 def test_streaming_cache_equals_offline_tree_and_oracle(bk, synth, oracle, value_gram):
     """Alg. 3 on the device: sum of weights = tokens seen at every step; at multiples of b*2^T the
     state equals the offline tree (same draws); the oracle's stream agrees when no margin case arose.
-    Keys-only weights and weights with the value factor of Alg. 2 line 5."""
+    Keys-only weights and weights with the value factor of Alg. 2 line 6."""
     from oracle.merge_reduce import MergeAndReduceStream
     from oracle.tuning import tune_log_c
     d, b, T, n_seq = 64, 64, 2, 3
@@ -731,6 +736,7 @@ def test_decode_workload_carries_teacher_forced(bk, synth, oracle):
     torch.cuda.synchronize()
     assert signs[512][0] == 1 and signs[1024][0] == 2 and cache.count == base + 256
     assert int((st_pre & 2).sum()) == 0 and int((status & 2).sum()) == 0          # no pipeline time-outs
+    assert cache.error_word() == 0                                                # ... and the cache's own word agrees
     Kv, Vv, wv = cache.views()
     assert bool(torch.all(wv[:, :base] == 4.0)) and bool(torch.all(wv[:, base:base + 256] == 4.0))
     assert bool(torch.all(wv[:, base + 256:] == 0.0))

@@ -122,7 +122,7 @@ def test_walk_antipodal_keys_closed_form(oracle):
 
 
 def test_fail_event_and_clamp(oracle):
-    """Alg. 2 line 6: |y^T eta| > c R^2 is flagged; the run continues with p clamped."""
+    """Alg. 2 line 7: |y^T eta| > c R^2 is flagged; the run continues with p clamped."""
     K = np.zeros((6, 2))
     res = oracle.softmax_balance(K, u=[0.9] * 6, log_c=math.log(0.25))   # c = 1/4: g_ij = 4
     assert res["sigma"].tolist() == [0.0, -4.0, 0.0, -4.0, 0.0, -4.0]
@@ -133,7 +133,7 @@ def test_fail_event_and_clamp(oracle):
 
 
 def test_literal_alg2_quantities(oracle):
-    """R, c, y, p formed literally as in Alg. 2 lines 2-7 agree with the oracle's normalised form."""
+    """R, c, y, p formed literally as in Alg. 2 lines 2-8 agree with the oracle's normalised form."""
     r = _rng(5)
     n, d, s = 20, 6, 3
     K, V = 0.8 * r.normal(size=(n, d)), r.normal(size=(n, s))
@@ -413,7 +413,7 @@ def test_zero_padding_never_keeps_padded_rows(oracle):
 
 # ----------------------------------------------------------------------------- draws
 def test_uniform_generator_properties(oracle):
-    """'with probability p_j' (Alg. 2 line 8): draws in [0,1), 24-bit granular, equidistributed, keyed."""
+    """'with probability p_j' (Alg. 2 line 9): draws in [0,1), 24-bit granular, equidistributed, keyed."""
     u = oracle.uniform_fill(123, 4, 0, 1 << 16)
     assert u.min() >= 0.0 and u.max() < 1.0
     assert np.all(u * (1 << 24) == np.floor(u * (1 << 24)))

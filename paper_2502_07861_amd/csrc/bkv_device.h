@@ -49,6 +49,10 @@ template <> struct Elem<__bf16> {
     static __device__ __forceinline__ void mma(floatx16& acc, Frag a, Frag b) {
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
     }
+    // the same product on top of c, into a result of its own (c stays intact: several accumulators can start from it)
+    static __device__ __forceinline__ floatx16 mma_from(Frag a, Frag b, const floatx16& c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
     static __device__ __forceinline__ void unpack(const uintx4& raw, float (&f)[8]) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -75,6 +79,12 @@ template <> struct Elem<float> {
     static __device__ __forceinline__ void mma(floatx16& acc, Frag a, Frag b) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], b[e], acc, 0, 0, 0);
+    }
+    static __device__ __forceinline__ floatx16 mma_from(Frag a, Frag b, const floatx16& c) {
+        floatx16 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], c, 0, 0, 0);
+#pragma unroll
+        for (int e = 1; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], b[e], acc, 0, 0, 0);
+        return acc;
     }
     static __device__ __forceinline__ void unpack(const uintx4& raw, float (&f)[4]) {
 #pragma unroll

@@ -23,10 +23,11 @@
 //
 // Kernel weight: g_ij = exp((<k_i,k_j> - a_i - a_j + |mu|^2 - A)/sqrt(d) - ln c), a_i = <k_i,mu>
 // (mu = block mean when keys are centred, else 0), A = r_key^2 or the largest centred squared norm:
-// Alg. 2's y_i / (c R^2) with v = 1, never forming R^2.  It is evaluated as
-// exp2(alpha <k_i,k_j> - alpha a_i + rc) * exp2(-alpha a_j) with alpha = log2(e)/sqrt(d) and
-// rc = alpha (|mu|^2 - A) - ln c log2(e), so that each entry costs one FMA and one exp2 and the
-// column factor is applied once per column sum.
+// Alg. 2's y_i / (c R^2) with v = 1, never forming R^2.  The exponent is formed in one piece,
+// alpha (<k_i,k_j> - a_i) + (rc - alpha a_j), alpha = log2(e)/sqrt(d), rc = alpha (|mu|^2 - A) - ln c log2(e): the row
+// term -a_i is what the accumulators of the Gram start from (the C operand of the first MFMA of a tile), the column
+// term is the addend of the one FMA in front of the exp2.  One FMA and one exp2 per entry, and no factor of the weight
+// is ever formed on its own (a large common mean cannot overflow one factor and flush the other).
 #include <utility>
 
 #include "bkv_device.h"
@@ -53,7 +54,7 @@ constexpr int kDiagFloats = 64 * kDiagStride;
 constexpr int kLdsLimit = 160 * 1024;
 
 static inline size_t lds_fixed_bytes(int b) {
-    return (size_t)b * 4 * 2             // sigma, aterm
+    return (size_t)b * 4 * 2             // sigma, -a_i of every row
            + 16 * 8                      // eta of each panel as a 64-bit mask (bit j = 1 iff eta_j = +1)
            + 8 * 64 * 4                  // eta of the resident chunk's panels as +-1 floats, accumulator order
            + kDiagFloats * 4             // diagonal tile (also: mean partials, survivor list)
@@ -145,13 +146,13 @@ struct TileOps {
         return halves_sum(cs0, cs1);
     }
     // One 64x64 tile in two row halves: Gram of rows 0..31, then the Gram of rows 32..63 while the vector unit
-    // turns the first half into kernel weights (acc <- exp2(alpha * acc + rterm[row])) and, with SUM, adds them up
+    // turns the first half into kernel weights (acc <- exp2(alpha * acc + rc)) and, with SUM, adds them up
     // per column with the row signs; then the same for the second half.  Per MFMA (32 cycles in the matrix pipe)
     // the vector unit gets two elements: 2 FMA + 2 exp2 (+ 2 FMA); the order is written out and fenced, B fragments
     // are requested one k-group ahead.  A fragments come from registers (AREG: the caller's A, reused over several
     // tiles) or from LDS rows ldsA[0..63], one half at a time; signs come from registers (sg) or, if sg is null,
-    // from LDS (sgn_h: this lane half's 32 floats).  Returns this lane's column 32*h + n of the signed column sums
-    // (before the column factor).
+    // from LDS (sgn_h: this lane half's 32 floats).  naA / naB: -a_i of the tile's 64 rows / -a_j of its 64 columns.
+    // Returns this lane's column 32*h + n of the signed column sums.
     // With BREG the column panel's fragments come from the caller's registers too (Bq), e.g. a panel that a
     // wavefront keeps for all tiles of its column.
     // With DIAG (a diagonal tile, not dumped) the quadrant rows 32..63 x columns 0..31, which the walk never uses, is skipped.
@@ -162,7 +163,7 @@ struct TileOps {
     // the column panel.
     template <bool SUM, bool AREG, bool BREG = false, bool DIAG = false, int VG = 0>
     static __device__ __forceinline__ float tile(floatx16 (&acc)[2][2], const Frag (*A)[2], const char* ldsA, const char* ldsB,
-                                                 const float* aterm_panel, float alpha, const float* sg, const float* sgn_h,
+                                                 const float* naA, const float* naB, float alpha, float rc, const float* sg, const float* sgn_h,
                                                  const int (&foff)[G::kGroups], int n, int h, const Frag (*Bq)[2] = nullptr,
                                                  const char* vA = nullptr, const char* vB = nullptr, float inv_rv2 = 0.f,
                                                  const char* vA1 = nullptr, const char* vB1 = nullptr) {
@@ -203,7 +204,18 @@ struct TileOps {
         const char* bp1 = BREG ? nullptr : bp0 + (size_t)32 * G::kLdsRow;
         const char* ap = AREG ? nullptr : ldsA + (size_t)n * G::kLdsRow;
         Frag Ah[2][KG], B0[KG], B1[KG];
-        floatx4 at[2][4], sq[2][4];
+        floatx4 sq[2][4];
+        // -a_i of this lane's 16 rows of each half, in accumulator order: where the Gram's accumulators start from
+        floatx16 rinit[2];
+        auto load_rinit = [&](int rb) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const floatx4 t = *reinterpret_cast<const floatx4*>(naA + 32 * rb + 8 * q + 4 * h);
+                rinit[rb][4 * q] = t[0]; rinit[rb][4 * q + 1] = t[1]; rinit[rb][4 * q + 2] = t[2]; rinit[rb][4 * q + 3] = t[3];
+            }
+        };
+        // the column term of this lane's two columns: rc - alpha a_j
+        const float cc0 = fmaf(alpha, naB[n], rc), cc1 = fmaf(alpha, naB[32 + n], rc);
         auto load_a = [&](int rb, int g) {
             Ah[rb][g] = AREG ? A[g][rb] : *reinterpret_cast<const Frag*>(ap + (size_t)(32 * rb) * G::kLdsRow + foff[g]);
         };
@@ -213,15 +225,14 @@ struct TileOps {
             B1[g] = *reinterpret_cast<const Frag*>(bp1 + foff[g]);
         };
         auto load_rowterm = [&](int rb, int q) {
-            at[rb][q] = *reinterpret_cast<const floatx4*>(aterm_panel + 32 * rb + 8 * q + 4 * h);
             if (SUM) {
                 if (sg) { sq[rb][q][0] = sg[16 * rb + 4 * q]; sq[rb][q][1] = sg[16 * rb + 4 * q + 1]; sq[rb][q][2] = sg[16 * rb + 4 * q + 2]; sq[rb][q][3] = sg[16 * rb + 4 * q + 3]; }
                 else sq[rb][q] = *reinterpret_cast<const floatx4*>(sgn_h + 16 * rb + 4 * q);
             }
         };
         auto finish = [&](int rb, int r) {
-            if (!(DIAG && rb == 1)) acc[rb][0][r] = fast_exp2(fmaf(acc[rb][0][r], alpha, at[rb][r >> 2][r & 3]));
-            acc[rb][1][r] = fast_exp2(fmaf(acc[rb][1][r], alpha, at[rb][r >> 2][r & 3]));
+            if (!(DIAG && rb == 1)) acc[rb][0][r] = fast_exp2(fmaf(acc[rb][0][r], alpha, cc0));
+            acc[rb][1][r] = fast_exp2(fmaf(acc[rb][1][r], alpha, cc1));
             if constexpr (VG != 0) {
                 if (!(DIAG && rb == 1)) acc[rb][0][r] *= vg[rb][0][r];
                 acc[rb][1][r] *= vg[rb][1][r];
@@ -236,8 +247,8 @@ struct TileOps {
 #pragma unroll
             for (int r = r0; r < r0 + RPI; ++r) {
                 if (step == 0) {
-                    acc[rb][0][r] = fmaf(acc[rb][0][r], alpha, at[rb][r >> 2][r & 3]);
-                    acc[rb][1][r] = fmaf(acc[rb][1][r], alpha, at[rb][r >> 2][r & 3]);
+                    acc[rb][0][r] = fmaf(acc[rb][0][r], alpha, cc0);
+                    acc[rb][1][r] = fmaf(acc[rb][1][r], alpha, cc1);
                 } else if (step == 1) {
                     acc[rb][0][r] = fast_exp2(acc[rb][0][r]);
                     acc[rb][1][r] = fast_exp2(acc[rb][1][r]);
@@ -254,15 +265,21 @@ struct TileOps {
         for (int g = 0; g < KG; ++g) load_a(0, g);
 #pragma unroll
         for (int g = 0; g < kAhead; ++g) load_b(g);
-        acc[0][0] = zero; acc[0][1] = zero;
+        load_rinit(0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int g = 0; g < KG; ++g) {
             if (g + kAhead < KG) load_b(g + kAhead);
             if (g < 4) load_rowterm(0, g);
+            if (g == 0) load_rinit(1);
             if (!AREG) load_a(1, g);
-            Elem<T>::mma(acc[0][0], Ah[0][g], B0[g]);
-            Elem<T>::mma(acc[0][1], Ah[0][g], B1[g]);
+            if (g == 0) {                                  // both accumulators start from -a_i of their rows
+                acc[0][0] = Elem<T>::mma_from(Ah[0][0], B0[0], rinit[0]);
+                acc[0][1] = Elem<T>::mma_from(Ah[0][0], B1[0], rinit[0]);
+            } else {
+                Elem<T>::mma(acc[0][0], Ah[0][g], B0[g]);
+                Elem<T>::mma(acc[0][1], Ah[0][g], B1[g]);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         // rows 32..63 on the matrix pipe, rows 0..31 on the vector unit
@@ -273,15 +290,16 @@ struct TileOps {
         if (!kKeepB)
 #pragma unroll
             for (int g = 0; g < kAhead; ++g) load_b(g);
-        acc[1][0] = zero; acc[1][1] = zero;
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int g = 0; g < KG; ++g) {
             if (!kKeepB && g + kAhead < KG) load_b(g + kAhead);
             if (g >= KG - 4) load_rowterm(1, g - (KG - 4));
-            if (!DIAG) Elem<T>::mma(acc[1][0], Ah[1][g], B0[g]);
+            if (g == 0) { if (!DIAG) acc[1][0] = Elem<T>::mma_from(Ah[1][0], B0[0], rinit[1]); }
+            else if (!DIAG) Elem<T>::mma(acc[1][0], Ah[1][g], B0[g]);
             finish_group(0, g * RPI, 0);                   // scale-and-shift of this k-group's share of rows 0..31 ...
-            Elem<T>::mma(acc[1][1], Ah[1][g], B1[g]);
+            if (g == 0) acc[1][1] = Elem<T>::mma_from(Ah[1][0], B1[0], rinit[1]);
+            else Elem<T>::mma(acc[1][1], Ah[1][g], B1[g]);
             finish_group(0, g * RPI, 1);                   // ... their exponentials ...
             finish_group(0, g * RPI, 2);                   // ... and the signed sums
             __builtin_amdgcn_sched_barrier(0);
@@ -297,7 +315,7 @@ struct TileOps {
     // two wavefronts share a SIMD.  emit(jj, cs) receives this lane's column 32*h + n of tile jj's signed column sums.
     template <typename Emit>
     static __device__ __forceinline__ void row_sweep(const Frag (&A)[G::kGroups][2], const char* ldsB, int nJ,
-                                                     const float* aterm_panel, float alpha, unsigned long long eta_mask,
+                                                     const float* naA, const float* naB, float alpha, float rc, unsigned long long eta_mask,
                                                      const int (&foff)[G::kGroups], int n, int h, Emit emit) {
         constexpr int KG = G::kGroups;
         constexpr int RPI = 16 / KG;
@@ -314,18 +332,24 @@ struct TileOps {
         };
         const char* bp0 = ldsB + (size_t)n * G::kLdsRow;
         Frag B0[KG], B1[KG];
-        floatx4 at[4];
+        // -a_i of the row panel is where the accumulators start from (fetched anew for every half tile: 16 registers in
+        // flight instead of 32 held), -a_j of the column panel at hand makes the FMA's addend (naB moves with bp0)
+        float cc0 = 0.f, cc1 = 0.f;                      // rc - alpha a_j of this lane's two columns of the tile being finished
         auto load_b = [&](int g) {
             B0[g] = *reinterpret_cast<const Frag*>(bp0 + foff[g]);
             B1[g] = *reinterpret_cast<const Frag*>(bp0 + (size_t)32 * G::kLdsRow + foff[g]);
         };
-        auto load_at = [&](int rb) {
+        floatx16 rinit;
+        auto load_rinit = [&](int rb) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) at[q] = *reinterpret_cast<const floatx4*>(aterm_panel + 32 * rb + 8 * q + 4 * h);
+            for (int q = 0; q < 4; ++q) {
+                const floatx4 t = *reinterpret_cast<const floatx4*>(naA + 32 * rb + 8 * q + 4 * h);
+                rinit[4 * q] = t[0]; rinit[4 * q + 1] = t[1]; rinit[4 * q + 2] = t[2]; rinit[4 * q + 3] = t[3];
+            }
         };
         auto finish = [&](int rb, int r) {
-            acc[rb][0][r] = fast_exp2(fmaf(acc[rb][0][r], alpha, at[r >> 2][r & 3]));
-            acc[rb][1][r] = fast_exp2(fmaf(acc[rb][1][r], alpha, at[r >> 2][r & 3]));
+            acc[rb][0][r] = fast_exp2(fmaf(acc[rb][0][r], alpha, cc0));
+            acc[rb][1][r] = fast_exp2(fmaf(acc[rb][1][r], alpha, cc1));
             const float sr = sign_of(rb, r);
             cs0 = fmaf(sr, acc[rb][0][r], cs0);
             cs1 = fmaf(sr, acc[rb][1][r], cs1);
@@ -334,8 +358,8 @@ struct TileOps {
 #pragma unroll
             for (int r = r0; r < r0 + RPI; ++r) {
                 if (step == 0) {
-                    acc[rb][0][r] = fmaf(acc[rb][0][r], alpha, at[r >> 2][r & 3]);
-                    acc[rb][1][r] = fmaf(acc[rb][1][r], alpha, at[r >> 2][r & 3]);
+                    acc[rb][0][r] = fmaf(acc[rb][0][r], alpha, cc0);
+                    acc[rb][1][r] = fmaf(acc[rb][1][r], alpha, cc1);
                 } else if (step == 1) {
                     acc[rb][0][r] = fast_exp2(acc[rb][0][r]);
                     acc[rb][1][r] = fast_exp2(acc[rb][1][r]);
@@ -353,15 +377,16 @@ struct TileOps {
             constexpr bool FIN = decltype(fin_c)::value;
 #pragma unroll
             for (int g = 0; g < kAhead; ++g) load_b(g);
-            if (FIN) load_at(1 - RBM);
-            acc[RBM][0] = zero; acc[RBM][1] = zero;
+            load_rinit(RBM);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int g = 0; g < KG; ++g) {
                 if (g + kAhead < KG) load_b(g + kAhead);
-                Elem<T>::mma(acc[RBM][0], A[g][RBM], B0[g]);
+                if (g == 0) acc[RBM][0] = Elem<T>::mma_from(A[0][RBM], B0[0], rinit);
+                else Elem<T>::mma(acc[RBM][0], A[g][RBM], B0[g]);
                 if (FIN) finish_group(1 - RBM, g * RPI, 0);
-                Elem<T>::mma(acc[RBM][1], A[g][RBM], B1[g]);
+                if (g == 0) acc[RBM][1] = Elem<T>::mma_from(A[0][RBM], B1[0], rinit);
+                else Elem<T>::mma(acc[RBM][1], A[g][RBM], B1[g]);
                 if (FIN) { finish_group(1 - RBM, g * RPI, 1); finish_group(1 - RBM, g * RPI, 2); }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -370,30 +395,29 @@ struct TileOps {
 #pragma unroll 1
         for (int jj = 0; jj < nJ; ++jj) {
             cs0 = 0.f; cs1 = 0.f;
+            cc0 = fmaf(alpha, naB[(jj << 6) + n], rc); cc1 = fmaf(alpha, naB[(jj << 6) + 32 + n], rc);
             stage(std::integral_constant<int, 1>{}, std::true_type{});         // rows 32..63 of tile jj | finish rows 0..31
             if (jj + 1 < nJ) {
                 bp0 += (size_t)64 * G::kLdsRow;
                 stage(std::integral_constant<int, 0>{}, std::true_type{});     // rows 0..31 of tile jj+1 | finish rows 32..63
             } else {
-                load_at(1);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) finish(1, r);
             }
             emit(jj, halves_sum(cs0, cs1));
         }
     }
-    // Diagonal tile: apply the column factors and zero everything that is not strictly above the diagonal
+    // Diagonal tile: zero everything that is not strictly above the diagonal
     // (the walk only ever adds eta_j * g_jl for l > j) ...
     // Quadrant by quadrant: rows 0..31 x columns 32..63 lie above the diagonal as a whole, rows 32..63 x columns
     // 0..31 below it as a whole; only the two diagonal quadrants need the per-entry test (local row < n in both).
-    static __device__ __forceinline__ void mask_diag(floatx16 (&v)[2][2], float e0, float e1, int n, int h) {
+    static __device__ __forceinline__ void mask_diag(floatx16 (&v)[2][2], int n, int h) {
         const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int lrow = 8 * (r >> 2) + 4 * h + (r & 3);                  // row inside its half
-            v[0][0][r] = (n > lrow) ? v[0][0][r] * e0 : 0.f;
-            v[0][1][r] = v[0][1][r] * e1;
-            v[1][1][r] = (n > lrow) ? v[1][1][r] * e1 : 0.f;
+            v[0][0][r] = (n > lrow) ? v[0][0][r] : 0.f;
+            v[1][1][r] = (n > lrow) ? v[1][1][r] : 0.f;
         }
         v[1][0] = zero;
     }
@@ -415,8 +439,8 @@ struct TileOps {
     // after a third of the time one wavefront needs for the whole tile.  QR = QC = 0 also clears the quadrant below
     // the diagonal.
     template <int QR, int QC>
-    static __device__ __forceinline__ void diag_quadrant(float* diag, const char* lds_panel, const float* aterm_panel, float alpha,
-                                                         float e_col, const int (&foff)[G::kGroups], int n, int h) {
+    static __device__ __forceinline__ void diag_quadrant(float* diag, const char* lds_panel, const float* naP, float alpha,
+                                                         float rc, const int (&foff)[G::kGroups], int n, int h) {
         static_assert(QR <= QC, "quadrants on or above the diagonal");
         const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         const char* ap = lds_panel + (size_t)(32 * QR + n) * G::kLdsRow;
@@ -427,17 +451,20 @@ struct TileOps {
             A[g] = *reinterpret_cast<const Frag*>(ap + foff[g]);
             B[g] = *reinterpret_cast<const Frag*>(bp + foff[g]);
         }
-        floatx4 at[4];
+        floatx16 acc;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) at[q] = *reinterpret_cast<const floatx4*>(aterm_panel + 32 * QR + 8 * q + 4 * h);
-        floatx16 acc = zero;
+        for (int q = 0; q < 4; ++q) {
+            const floatx4 t = *reinterpret_cast<const floatx4*>(naP + 32 * QR + 8 * q + 4 * h);
+            acc[4 * q] = t[0]; acc[4 * q + 1] = t[1]; acc[4 * q + 2] = t[2]; acc[4 * q + 3] = t[3];
+        }
+        const float cc = fmaf(alpha, naP[32 * QC + n], rc);
 #pragma unroll
         for (int g = 0; g < G::kGroups; ++g) Elem<T>::mma(acc, A[g], B[g]);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int lrow = 8 * (r >> 2) + 4 * h + (r & 3);
-            const float w = fast_exp2(fmaf(acc[r], alpha, at[r >> 2][r & 3]));
-            acc[r] = (QR != QC || n > lrow) ? w * e_col : 0.f;
+            const float w = fast_exp2(fmaf(acc[r], alpha, cc));
+            acc[r] = (QR != QC || n > lrow) ? w : 0.f;
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -591,8 +618,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     char* ldsK = smem;
     char* ldsV = smem + (size_t)CH * G::kLdsRow;                   // value rows, same layout as the keys (VG only)
     float* sigma = reinterpret_cast<float*>(smem + (size_t)(VG == 1 ? 2 : 1) * CH * G::kLdsRow);
-    float* aterm = sigma + b;                                      // -alpha * a_i; column factor = exp2(aterm)
-    unsigned long long* etaMask = reinterpret_cast<unsigned long long*>(aterm + b);   // bit j of entry I: eta of token 64 I + j is +1
+    float* narow = sigma + b;                                      // -a_i of every row (a_i = <k_i, mu>)
+    unsigned long long* etaMask = reinterpret_cast<unsigned long long*>(narow + b);   // bit j of entry I: eta of token 64 I + j is +1
     float* etaF = reinterpret_cast<float*>(etaMask + 16);          // [8][2][32]: +-1 of the chunk's panel l, entry h*32 + 16*rb + r
     float* diag = etaF + 512;                                      // [64 columns][kDiagStride], transposed
     float* scal = diag + kDiagFloats;                              // [0] |mu|^2, [1] A, [2..2+kWaves) partial maxima
@@ -842,7 +869,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     pa = group_sum<SL>(pa);
                     pn = group_sum<SL>(pn);
                     if (i < b) {
-                        if (sl == 0) aterm[i] = -alpha * pa;
+                        if (sl == 0) narow[i] = -pa;
                         amax = fmaxf(amax, pn - 2.f * pa + mumu);
                     }
                 };
@@ -881,7 +908,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             amax = wave_max(amax);
             if (lane == 0) scal[2 + wave] = amax;
         } else {
-            for (int i = nres + tid; i < b; i += kThreads) aterm[i] = 0.f;
+            for (int i = nres + tid; i < b; i += kThreads) narow[i] = 0.f;
         }
         if constexpr (VG != 0) {                                // 1 / r_value^2: given, or the largest |v_i|^2 of the block
             float r2 = rvalue2;
@@ -901,8 +928,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 for (int w = 1; w < kWaves; ++w) A = fmaxf(A, scal[2 + w]);
             }
             const float rc = alpha * (mumu - A + a.cterm);       // row constant of the exponent
-            if (has_row) aterm[tid] = fmaf(-alpha, pa_row, rc);
-            for (int i = nres + tid; i < b; i += kThreads) aterm[i] += rc;
+            if (has_row) narow[tid] = -pa_row;
             if (tid == 0) scal[1] = rc;
             if (tid < 32) prog[tid] = 0;                        // progress counters of the first chunk's pipeline
         }
@@ -939,7 +965,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 Ops::load_frags(A, Kin + (size_t)(I << 6) * G::kRowBytes, G::kRowBytes, n, h);
                 if constexpr (!EMIT_G && VG == 0) {
                     const bool first_panel = first;
-                    Ops::row_sweep(A, ldsK, nJ, aterm + (I << 6), alpha, etaMask[I], foff, n, h, [&](int jj, float cs) {
+                    Ops::row_sweep(A, ldsK, nJ, narow + (I << 6), narow + (p0 << 6), alpha, row_const, etaMask[I], foff, n, h, [&](int jj, float cs) {
                         float* slot = partial + (wave * 8 + jj) * 64 + lane;          // this wavefront's own slot
                         *slot = first_panel ? cs : *slot + cs;
                     });
@@ -952,20 +978,19 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     const char* ldsB = lds_rows(jj << 6);
                     floatx16 acc[2][2];
                     const float cs = Ops::template tile<true, true, false, false, VG>(
-                        acc, A, nullptr, ldsB, aterm + (I << 6), alpha, sg, nullptr, foff, n, h, nullptr,
+                        acc, A, nullptr, ldsB, narow + (I << 6), narow + (J << 6), alpha, row_const, sg, nullptr, foff, n, h, nullptr,
                         VG == 2 ? vrow((I << 6) + n) : nullptr, VG == 2 ? vrow((J << 6) + n) : nullptr, inv_rv2,
                         VG == 2 ? vrow((I << 6) + 32 + n) : nullptr, VG == 2 ? vrow((J << 6) + 32 + n) : nullptr);
                     if constexpr (EMIT_G) {
-                        const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
 #pragma unroll
                         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
                                 const int row = (I << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-                                Gi[(size_t)row * b + (J << 6) + n] = acc[rb][0][r] * e0;
-                                Gi[(size_t)row * b + (J << 6) + 32 + n] = acc[rb][1][r] * e1;
-                                Gi[(size_t)((J << 6) + n) * b + row] = acc[rb][0][r] * e0;
-                                Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r] * e1;
+                                Gi[(size_t)row * b + (J << 6) + n] = acc[rb][0][r];
+                                Gi[(size_t)row * b + (J << 6) + 32 + n] = acc[rb][1][r];
+                                Gi[(size_t)((J << 6) + n) * b + row] = acc[rb][0][r];
+                                Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r];
                             }
                     }
                     float* slot = partial + (wave * 8 + jj) * 64 + lane;      // this wavefront's own slot
@@ -982,7 +1007,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 float tot = 0.f;
 #pragma unroll
                 for (int w = 0; w < kWaves; ++w) tot += partial[(w * 8 + wave) * 64 + lane];
-                sigma[(J << 6) + lane] = fmaf(tot, fast_exp2(aterm[(J << 6) + lane] - row_const), sigma[(J << 6) + lane]);
+                sigma[(J << 6) + lane] += tot;
             }
             __syncthreads();                              // the buffer goes back to the diagonal tile
         }
@@ -1067,20 +1092,19 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 floatx16 dv[2][2];
                 const char* vrows = VG == 1 ? ldsV + (size_t)(l << 6) * G::kLdsRow : VG == 2 ? vrow((I << 6) + n) : nullptr;
                 const char* vrows1 = VG == 2 ? vrow((I << 6) + 32 + n) : nullptr;
-                Ops::template tile<false, true, true, !EMIT_G, VG>(dv, P, nullptr, nullptr, aterm + (I << 6), alpha, nullptr, nullptr, foff, n, h, P,
-                                                                   vrows, vrows, inv_rv2, vrows1, vrows1);
-                const float e0 = fast_exp2(aterm[(I << 6) + n] - row_const), e1 = fast_exp2(aterm[(I << 6) + 32 + n] - row_const);
+                Ops::template tile<false, true, true, !EMIT_G, VG>(dv, P, nullptr, nullptr, narow + (I << 6), narow + (I << 6), alpha, row_const,
+                                                                   nullptr, nullptr, foff, n, h, P, vrows, vrows, inv_rv2, vrows1, vrows1);
                 if (EMIT_G) {
 #pragma unroll
                     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int row = 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-                            Gi[(size_t)((I << 6) + row) * b + (I << 6) + n] = dv[rb][0][r] * e0;
-                            Gi[(size_t)((I << 6) + row) * b + (I << 6) + 32 + n] = dv[rb][1][r] * e1;
+                            Gi[(size_t)((I << 6) + row) * b + (I << 6) + n] = dv[rb][0][r];
+                            Gi[(size_t)((I << 6) + row) * b + (I << 6) + 32 + n] = dv[rb][1][r];
                         }
                 }
-                Ops::mask_diag(dv, e0, e1, n, h);
+                Ops::mask_diag(dv, n, h);
                 // the tile is complete here: the compiler must not sink its arithmetic below the wait
                 asm volatile("" : "+v"(dv[0][0]), "+v"(dv[0][1]), "+v"(dv[1][0]), "+v"(dv[1][1]));
                 await(diag_taken, l, sync_err);               // the walker holds the previous tile in registers
@@ -1093,10 +1117,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             if (kSplitFirst && w <= 3) {
                 // the walk cannot start without the first tile: wavefronts 1, 2, 3 (three SIMDs) take a quadrant each
                 __builtin_amdgcn_s_setprio(2);
-                const float* at0 = aterm + (p0 << 6);
-                if (w == 1) Ops::template diag_quadrant<0, 0>(diag, lds_rows(0), at0, alpha, fast_exp2(at0[n] - row_const), foff, n, h);
-                else if (w == 2) Ops::template diag_quadrant<0, 1>(diag, lds_rows(0), at0, alpha, fast_exp2(at0[32 + n] - row_const), foff, n, h);
-                else Ops::template diag_quadrant<1, 1>(diag, lds_rows(0), at0, alpha, fast_exp2(at0[32 + n] - row_const), foff, n, h);
+                const float* ap0 = narow + (p0 << 6);
+                if (w == 1) Ops::template diag_quadrant<0, 0>(diag, lds_rows(0), ap0, alpha, row_const, foff, n, h);
+                else if (w == 2) Ops::template diag_quadrant<0, 1>(diag, lds_rows(0), ap0, alpha, row_const, foff, n, h);
+                else Ops::template diag_quadrant<1, 1>(diag, lds_rows(0), ap0, alpha, row_const, foff, n, h);
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
                 if (lane == 0) __hip_atomic_fetch_add(first_parts, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 __builtin_amdgcn_s_setprio(0);
@@ -1110,26 +1134,25 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             if (owner) {
                 const int J = p0 + w;
                 Ops::load_panel(Bq, lds_rows(w << 6), foff, n);
-                const float ecol = fast_exp2(aterm[(J << 6) + lane] - row_const);
                 float sig = sigma[(J << 6) + lane];           // minus the threshold, plus what earlier chunks added
                 for (int i = 0; i < w; ++i) {
                     const int Ii = p0 + i;
                     floatx16 acc[2][2];
-                    Ops::template tile<false, false, true, false, VG>(acc, nullptr, lds_rows(i << 6), nullptr, aterm + (Ii << 6), alpha, nullptr, nullptr, foff, n, h, Bq,
+                    Ops::template tile<false, false, true, false, VG>(acc, nullptr, lds_rows(i << 6), nullptr, narow + (Ii << 6), narow + (J << 6), alpha, row_const,
+                                                                      nullptr, nullptr, foff, n, h, Bq,
                                                                       VG == 1 ? ldsV + (size_t)(i << 6) * G::kLdsRow : VG == 2 ? vrow((Ii << 6) + n) : nullptr,
                                                                       VG == 1 ? ldsV + (size_t)(w << 6) * G::kLdsRow : VG == 2 ? vrow((J << 6) + n) : nullptr, inv_rv2,
                                                                       VG == 2 ? vrow((Ii << 6) + 32 + n) : nullptr, VG == 2 ? vrow((J << 6) + 32 + n) : nullptr);
                     if (EMIT_G) {
-                        const float e0 = fast_exp2(aterm[(J << 6) + n] - row_const), e1 = fast_exp2(aterm[(J << 6) + 32 + n] - row_const);
 #pragma unroll
                         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
                                 const int row = (Ii << 6) + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-                                Gi[(size_t)row * b + (J << 6) + n] = acc[rb][0][r] * e0;
-                                Gi[(size_t)row * b + (J << 6) + 32 + n] = acc[rb][1][r] * e1;
-                                Gi[(size_t)((J << 6) + n) * b + row] = acc[rb][0][r] * e0;
-                                Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r] * e1;
+                                Gi[(size_t)row * b + (J << 6) + n] = acc[rb][0][r];
+                                Gi[(size_t)row * b + (J << 6) + 32 + n] = acc[rb][1][r];
+                                Gi[(size_t)((J << 6) + n) * b + row] = acc[rb][0][r];
+                                Gi[(size_t)((J << 6) + 32 + n) * b + row] = acc[rb][1][r];
                             }
                     }
                     // the weights are complete here: the compiler must not sink their arithmetic below the wait
@@ -1140,7 +1163,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     if (urgent) { __builtin_amdgcn_s_setprio(3); await<true>(eta_done, i + 1, sync_err); }
                     else await(eta_done, i + 1, sync_err);
                     Ops::signs_from_lds(sg, etaF + (i << 6) + 32 * h);
-                    sig = fmaf(Ops::signed_colsum(acc, sg, h), ecol, sig);
+                    sig += Ops::signed_colsum(acc, sg, h);
                     if (urgent) {
                         sigma[(J << 6) + lane] = sig;
                         publish_in_order(col + w, w);
@@ -1538,7 +1561,7 @@ __global__ __launch_bounds__(kThreads) void peak_tile_kernel(float* out, int ite
     typedef typename Elem<__bf16>::Frag Frag;
     extern __shared__ __align__(16) char smem[];
     char* ldsK = smem;
-    float* aterm = reinterpret_cast<float*>(smem + (size_t)512 * G::kLdsRow);
+    float* narow = reinterpret_cast<float*>(smem + (size_t)512 * G::kLdsRow);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, h = lane >> 5;
     for (int i = tid; i < 512 * G::kSlices; i += kThreads) {           // small integers: exact products, moderate exponents
         uintx4 v;
@@ -1551,7 +1574,7 @@ __global__ __launch_bounds__(kThreads) void peak_tile_kernel(float* out, int ite
         const int row = i / G::kSlices, sl = i % G::kSlices;
         *reinterpret_cast<uintx4*>(ldsK + (size_t)row * G::kLdsRow + G::slice_off(row, sl)) = v;
     }
-    for (int i = tid; i < 512; i += kThreads) aterm[i] = -20.f;
+    for (int i = tid; i < 512; i += kThreads) narow[i] = -1.5f * (float)(i & 7);
     __syncthreads();
     int foff[G::kGroups];
 #pragma unroll
@@ -1560,7 +1583,7 @@ __global__ __launch_bounds__(kThreads) void peak_tile_kernel(float* out, int ite
     Ops::load_panel(A, ldsK + (size_t)(wave << 6) * G::kLdsRow, foff, n);
     float total = 0.f;
     for (int it = 0; it < iters; ++it)
-        Ops::row_sweep(A, ldsK, 8, aterm + (wave << 6), 0.1275f, 0x5a5a5a5a5a5a5a5aull + it, foff, n, h,
+        Ops::row_sweep(A, ldsK, 8, narow + (wave << 6), narow, 0.1275f, -20.f, 0x5a5a5a5a5a5a5a5aull + it, foff, n, h,
                        [&](int, float cs) { total += cs; });
     out[(size_t)blockIdx.x * kThreads + tid] = total;
 }

@@ -141,6 +141,48 @@ def test_compress_block_teacher_forced(bk, synth, oracle, dtype, d, b, n_inst, c
             assert abs(u[t, first] - free["p"][t, first]) < MARGIN
 
 
+@pytest.mark.parametrize("dtype,d,b", [(torch.bfloat16, 128, 512), (torch.bfloat16, 128, 1024), (torch.float32, 64, 256),
+                                       (torch.float32, 128, 320)])
+def test_large_common_key_mean(bk, synth, oracle, dtype, d, b):
+    """Keys around a common mean of norm 40 (the case the key shift of App. B.5 item 1 exists for): <k_i,k_j> is about
+    |mu|^2 = 1600 (more on the outlier channels) for every pair, e^{|mu|^2/sqrt d} is far beyond fp32, and only the
+    centred exponent is small.  Kernel weights against the fp64 definition and a teacher-forced halving; no NaN, no
+    status bit."""
+    n_inst = 3
+    t = synth.gqa_layer_bf16(n_seq=n_inst, n=b, d=d, g=1, nq=1, seed=4000 + b, device="cpu", dtype=dtype, mu_norm=40.0)
+    K, V = t["K"].cuda().contiguous(), t["V"].cuda().contiguous()
+    Kd = to_f64(K)
+    assert np.linalg.norm(Kd.mean(axis=1), axis=1).min() > 35.0
+    from oracle.tuning import tune_log_c
+    log_c = f32(tune_log_c(Kd, target=0.25, center=True))
+    p = bk.make_params(d, b, 1, dtype, log_c=log_c, seed=31, center=True)
+    # the weights themselves
+    Kc = Kd - Kd.mean(axis=1, keepdims=True)
+    S = np.einsum("nid,njd->nij", Kc, Kc)
+    A = np.max(np.einsum("nii->ni", S), axis=1)
+    ref = np.exp((S - A[:, None, None]) / math.sqrt(d) - log_c)
+    G = bk.kernel_weights(p, K).cpu().numpy().astype(np.float64)
+    offd = ~np.eye(b, dtype=bool)[None].repeat(n_inst, axis=0)
+    assert np.isfinite(G[offd]).all()
+    big = offd & (ref > 1e-6 * ref[offd].max())
+    np.testing.assert_allclose(G[big], ref[big], rtol=2e-3)
+    # the walk
+    u = np.stack([oracle.uniform_fill(31, s_, 0, b) for s_ in range(n_inst)])
+    out = bk.compress_block(p, K, V, uniforms=torch.from_numpy(u.astype(np.float32)).cuda())
+    torch.cuda.synchronize()
+    signs = out["signs"].cpu().numpy()
+    v = verify_halving(oracle, Kd, u, signs, log_c=log_c, center=True)
+    print("common mean of norm 40: %d decisions, %d within margin, %d margin flips, %d hard" % (v["n"], v["near"], v["margin"], v["hard"]))
+    assert v["hard"] == 0 and np.abs(2 * v["res"]["p"] - 1).mean() > 0.1
+    status = out["status"].cpu().numpy()
+    assert not np.any(status & 2)                       # no pipeline time-out
+    smax = np.abs(v["res"]["sigma"]).max(axis=1)
+    clear = np.abs(smax - 1.0) > 1e-3
+    np.testing.assert_array_equal((status & 1).astype(bool)[clear], (v["res"]["fails"] > 0)[clear])      # FAIL events as the oracle sees them
+    assert np.all(np.isfinite(out["stats"].cpu().numpy()))
+    np.testing.assert_array_equal(out["idx"].cpu().numpy(), expected_survivors(oracle, signs))
+
+
 VALUE_CASES = [
     # dtype, d, b, n_inst, center, r_value (0: measured per block)
     (torch.bfloat16, 128, 256, 4, True, 0.0),     # the largest block whose keys and values share LDS at d=128 bf16

@@ -226,6 +226,33 @@ def test_walk_quadratic_identity(oracle, center):
     np.testing.assert_allclose(res["sigma"], np.triu(G, 1).T @ eta, atol=1e-12)
 
 
+def test_centred_walk_ignores_a_large_common_mean(oracle):
+    """App. B.5 item 1: with the keys shifted by their mean, the selection sees <k_i - mu, k_j - mu> only.  Adding one
+    large vector (norm 40, exactly representable steps) to every key must leave every p_j of the centred walk as it
+    is, all of them finite and inside [0, 1]: no factor e^{|mu|^2/sqrt d} may appear anywhere (at d = 128 that
+    factor alone is e^{141}, beyond fp32)."""
+    r = np.random.default_rng(12)
+    n, d = 96, 128
+    K0 = r.normal(size=(n, d)) * 1.5
+    shift = np.round(r.normal(size=d) * 40.0 / np.sqrt(d) * 64.0) / 64.0          # multiples of 1/64: K0 + shift is exact
+    K0 = np.round(K0 * 64.0) / 64.0
+    assert 30.0 < np.linalg.norm(shift) < 50.0
+    u = r.uniform(size=n)
+    from oracle.tuning import tune_log_c
+    log_c = tune_log_c(K0[None], center=True)
+    a = oracle.softmax_balance(K0, u=u, log_c=log_c, center=True)
+    b = oracle.softmax_balance(K0 + shift, u=u, log_c=log_c, center=True)
+    assert np.all(np.isfinite(b["p"])) and np.all((b["p"] >= 0) & (b["p"] <= 1))
+    np.testing.assert_allclose(b["p"], a["p"], atol=1e-9)
+    np.testing.assert_array_equal(b["eta"], a["eta"])
+    assert np.abs(2 * a["p"] - 1).mean() > 0.02                # the walk is not a fair coin here
+    # the bound behind it: every centred weight is at most e^{-ln c} (Cauchy-Schwarz on the centred keys)
+    Kc = K0 - K0.mean(axis=0)
+    S = Kc @ Kc.T
+    g = np.exp((S - np.max(np.diag(S))) / np.sqrt(d) - log_c)
+    assert g.max() <= np.exp(-log_c) * (1 + 1e-12)
+
+
 def test_walk_balances_better_than_fair_coin(oracle):
     """E[eta^T G eta] = tr G - 2 sum_j E[sigma_j^2] <= tr G, the value for independent fair signs
     (E[eta_j | past] = 2 p_j - 1 = -sigma_j).  A wrong sign in p_j would push it ABOVE tr G."""

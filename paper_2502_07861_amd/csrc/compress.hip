@@ -724,7 +724,40 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             }
         }
     };
-    stage_chunk(0, min(CH, b), center ? b : 0);
+    // Blocks of several chunks, where registers allow: the whole block is requested in one batch (32 slices per thread),
+    // and the slices of the rows beyond the first chunk stay in registers until the second statistics pass has used
+    // them, so that those rows are read once here and once when their chunk is staged.
+    constexpr int kU2 = 32;                                     // slices in flight per thread in the first pass
+    constexpr int kCHm = G::kRowBytes <= 256 ? 512 : 256;       // chunk rows of a block that does not fit LDS
+    constexpr int kU0 = kCHm / RG;                              // slices of a thread that belong to the first chunk
+    constexpr int kUK = kU2 > kU0 ? (kU2 - kU0 < 16 ? kU2 - kU0 : 16) : 1;
+    uintx4 keep[MULTI ? kUK : 1];
+    bool kept = false;
+    if constexpr (MULTI) {
+        kept = CH == kCHm && b > CH && b <= RG * kU2 && b - CH <= RG * kUK && kU2 > kU0 && (center || need_norm);
+    }
+    if (MULTI && kept) {
+        uintx4 raw[kU2];
+#pragma unroll
+        for (int u = 0; u < kU2; ++u) {
+            const int i = rg + u * RG;
+            if (i < b) raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < kU2; ++u) {
+            const int i = rg + u * RG;
+            if (u < kU0) *reinterpret_cast<uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, sl)) = raw[u];    // i < CH <= b
+            else if (u - kU0 < kUK) keep[u - kU0 < kUK ? u - kU0 : 0] = raw[u];
+            if (center && i < b) {
+                float f[EPL];
+                Elem<T>::unpack(raw[u], f);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) part[e] += f[e];
+            }
+        }
+    } else {
+        stage_chunk(0, min(CH, b), center ? b : 0);
+    }
     // Value factor: the value row of every token of the block -> LDS (the row of token i is the ORIGINAL row of that
     // token, as in the gather at the end); |v_i|^2 on the way when r_value has to be measured.
     float vmax = 0.f;
@@ -882,7 +915,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 };
                 const int n_lds = min(CH, b);                    // b and CH are multiples of 64 and of RG
                 uintx4 ahead[U];
-                if (n_lds < b) load_global(ahead, n_lds);
+                if (n_lds < b && !kept) load_global(ahead, n_lds);
                 for (int ib0 = 0; ib0 < n_lds; ib0 += RG * U) {
                     uintx4 raw[U];
 #pragma unroll
@@ -896,7 +929,14 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                         row_terms(raw[u], i < n_lds ? i : b);      // rows past the chunk's end are not counted here
                     }
                 }
-                for (int ib0 = n_lds; ib0 < b; ib0 += RG * U) {
+                if (kept) {                                     // the rows beyond the first chunk are still in registers
+#pragma unroll
+                    for (int k = 0; k < kUK; ++k) {
+                        const int i = (kU0 + k) * RG + rg;
+                        row_terms(keep[k], i < b ? i : b);
+                    }
+                }
+                for (int ib0 = n_lds; ib0 < b && !kept; ib0 += RG * U) {
                     uintx4 raw[U];
 #pragma unroll
                     for (int u = 0; u < U; ++u) raw[u] = ahead[u];

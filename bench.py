@@ -363,6 +363,18 @@ def main():
         line["phases"]["carry_halvings_per_step"] = len(carry) / args.steps
         line["phases"]["carry_avg_launch_ms"] = sum(r[1] for r in carry) / max(len(carry), 1)
         line["phases"]["decode_steps_per_s"] = appended / ((ms_per_step - comp_step_ms) * 1e-3)
+    # measured peaks of this GPU (micro-benchmarks in the library), for fractions against what the chip delivers
+    pk = binding.peaks(stream_bytes=2 << 30, launches=5)
+    line["measured_peaks"] = {"stream_read_gbs": pk["stream_read_bytes"]["per_second"] / 1e9,
+                              "stream_copy_gbs": pk["stream_copy_bytes"]["per_second"] / 1e9,
+                              "mfma_bf16_tflops": pk["mfma_bf16_flops"]["per_second"] / 1e12,
+                              "gram_tile_routine_alone_tflops": pk["tile_bf16_flops"]["per_second"] / 1e12}
+    if att_ms > 0:
+        line["phases"]["attend_frac_of_measured_read_peak"] = (att_bytes / (att_ms * 1e-3) / 1e9) / line["measured_peaks"]["stream_read_gbs"]
+    if comp_ms > 0 and elem == 2:
+        line["phases"]["gram_frac_of_tile_routine_alone"] = (line["phases"]["gram_mfma_tflops_executed"]
+                                                               / line["measured_peaks"]["gram_tile_routine_alone_tflops"])
+        line["phases"]["gram_frac_of_mfma_peak_2500"] = line["phases"]["gram_mfma_tflops_executed"] / 2500.0
     if not args.no_cpu:
         if decode:
             line["cpu_baseline"] = cpu_baseline_decode(cfg, K, V, Q, t["K_tail"], t["V_tail"], log_c,

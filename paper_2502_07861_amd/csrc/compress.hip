@@ -1627,16 +1627,21 @@ __global__ __launch_bounds__(kThreads) void peak_tile_kernel(float* out, int ite
                        [&](int, float cs) { total += cs; });
     out[(size_t)blockIdx.x * kThreads + tid] = total;
 }
-// (3) Streaming: read `n16` 16-byte words once (XOR-folded into one word per thread), or copy them.
+// (3) Streaming: read `n16` 16-byte words once (XOR-folded into one word per thread), or copy them.  Every workgroup
+// owns one contiguous range (as the attend pass does) and keeps eight 16-byte loads per lane in flight.
 __global__ __launch_bounds__(256) void peak_read_kernel(const uintx4* src, unsigned int* out, int64_t n16) {
     unsigned int acc = 0;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < n16; i += 4 * stride) {                    // four independent loads in flight per lane
-        const uintx4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        acc ^= a[0] ^ a[1] ^ a[2] ^ a[3] ^ b[0] ^ b[1] ^ b[2] ^ b[3] ^ c[0] ^ c[1] ^ c[2] ^ c[3] ^ d[0] ^ d[1] ^ d[2] ^ d[3];
+    const int64_t per = (n16 + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = (int64_t)blockIdx.x * per, hi = lo + per < n16 ? lo + per : n16;
+    int64_t i = lo + threadIdx.x;
+    for (; i + 7 * 256 < hi; i += 8 * 256) {
+        uintx4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[i + u * 256];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
     }
-    for (; i < n16; i += stride) { const uintx4 a = src[i]; acc ^= a[0] ^ a[1] ^ a[2] ^ a[3]; }
+    for (; i < hi; i += 256) { const uintx4 a = src[i]; acc ^= a[0] ^ a[1] ^ a[2] ^ a[3]; }
     out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = acc;
 }
 __global__ __launch_bounds__(256) void peak_copy_kernel(const uintx4* src, uintx4* dst, int64_t n16) {

@@ -1,6 +1,6 @@
 """Ablation grid of the paper's single-layer study on synthetic data (one GPU).
 
-    python -m paper_2502_07861_amd.ablation [--seeds 10] [--json] [--value-factor | --alg1]
+    python -m paper_2502_07861_amd.ablation [--seeds 10] [--json] [--recipe clustered|iid] [--value-factor | --alg1]
 
 For block sizes b in {256, 128, 64} and compression rates 2^-T in {1/2, 1/4, 1/8} (the grid of the runtime /
 relative-error tables in "Ablation Studies on Single Layer Attention Approximation", arXiv 2502.07861): the first
@@ -9,13 +9,16 @@ and the most recent 256 tokens of every KV sequence are kept, the rows in betwee
 per cell: the run time of the compression and the relative error ||z - Attn|| / ||Attn|| per query, mean and standard
 deviation over seeds, next to independent uniform sampling of the same number of rows in between (the paper's
 comparator).  Next to it the relative error of the softmax normaliser sum_i w_i exp(<k_i,q>/sqrt d), the quantity
-that balancing the keys alone controls directly (the denominator instance of Alg. 1).  Exact attention and both
-estimates come from the same attend kernel (weights 1 for exact attention).
+that balancing the keys alone controls directly (the denominator instance of Alg. 1).  The estimates come from the
+attend kernel; exact attention (Eq. 1) is evaluated in float64 with plain tensor operations, as the yardstick.
 
-The inputs are synthetic stand-ins (synth.gqa_layer_bf16, one layer of 8 KV heads, 4 query heads each, 64 queries
-per head); the paper's tables are on Llama-3.1-8B / TriviaQA activations, so only the shape of the study carries over.
-ln c per block size was bisected once on the CPU oracle (oracle/tuning.py, mean |2p - 1| = 0.25 on the first two
-sequences) so that the walk's decisions depend on the kernel weights.  --value-factor: the walk's weights carry the
+The inputs are synthetic stand-ins, one layer of 8 KV heads, 4 query heads each, 64 queries per head; the paper's
+tables are on Llama-3.1-8B / TriviaQA activations, so only the shape of the study carries over.  Two recipes:
+"clustered" (default; synth.clustered_layer_bf16: keys that repeat -- 32 clusters per head, norms as App. B.5
+reports them -- which is what a balancing of exp(<k_i,k_j>/sqrt d) can exploit) and "iid" (synth.gqa_layer_bf16:
+independent Gaussians around a common mean, where no subset is better than a random one).
+ln c per recipe and block size was bisected once on the CPU oracle (oracle/tuning.py, mean |2p - 1| = 0.25 on the first
+four blocks of the first two sequences) so that the walk's decisions depend on the kernel weights.  --value-factor: the walk's weights carry the
 value factor <v_i,v_j>/r_value^2 of Alg. 2 line 6 (the numerator instance of Alg. 1 selects the kept set), with its own
 ln c per block size found the same way.
 """
@@ -34,13 +37,34 @@ ROUNDS = (1, 2, 3)
 N_SINK = N_RECENT = 256
 N_MID = 8192
 SEED_DATA = 0x250207861006
-LOG_C = {64: -53.9166, 128: -59.3241, 256: -61.8303}
-LOG_C_VALUE = {64: -57.0969, 128: -63.0066, 256: -67.8165}      # with the value factor
+SEED_CLUSTERED = 0x250207861007
+LOG_C = {64: -53.9166, 128: -59.3241, 256: -61.8303}            # recipe "iid"
+LOG_C_VALUE = {64: -57.0969, 128: -63.0066, 256: -67.8165}      # ... with the value factor
+LOG_C_CLUSTERED = {64: -4.2786, 128: -3.4420, 256: -2.9556}     # recipe "clustered"
+LOG_C_CLUSTERED_VALUE = {64: -4.6749, 128: -3.8368, 256: -3.3827}
 
 
-def make_inputs(device="cuda", n_seq=8, n_mid=N_MID, d=128, g=4, nq=64):
-    t = synth.gqa_layer_bf16(n_seq=n_seq, n=N_SINK + n_mid + N_RECENT, d=d, g=g, nq=nq, seed=SEED_DATA, device="cpu")
+def log_c_for(recipe, block, value_gram=False):
+    table = {("iid", False): LOG_C, ("iid", True): LOG_C_VALUE, ("clustered", False): LOG_C_CLUSTERED,
+             ("clustered", True): LOG_C_CLUSTERED_VALUE}[(recipe, bool(value_gram))]
+    return table.get(block, 0.0)
+
+
+def make_inputs(device="cuda", n_seq=8, n_mid=N_MID, d=128, g=4, nq=64, recipe="clustered"):
+    n = N_SINK + n_mid + N_RECENT
+    if recipe == "clustered":
+        t = synth.clustered_layer_bf16(n_seq=n_seq, n=n, d=d, g=g, nq=nq, seed=SEED_CLUSTERED, device="cpu")
+    else:
+        t = synth.gqa_layer_bf16(n_seq=n_seq, n=n, d=d, g=g, nq=nq, seed=SEED_DATA, device="cpu")
     return t["K"].to(device).contiguous(), t["V"].to(device).contiguous(), t["Q"].to(device).contiguous()
+
+
+def exact_attention_f64(K, V, Q):
+    """Eq. 1 in float64: softmax(K q / sqrt d)^T V for every query; returns (out [n_seq,g,nq,d], ln of the normaliser)."""
+    Kd, Vd, Qd = K.double(), V.double(), Q.double()
+    logits = torch.einsum("sgqd,snd->sgqn", Qd, Kd) / (K.shape[-1] ** 0.5)
+    lse = torch.logsumexp(logits, dim=-1)
+    return torch.einsum("sgqn,snd->sgqd", torch.exp(logits - lse[..., None]), Vd), lse
 
 
 def uniform_sample_protected(n_seq, n, n_sink, n_recent, T, seed, device):
@@ -62,8 +86,12 @@ def uniform_sample_protected(n_seq, n, n_sink, n_recent, T, seed, device):
 
 def relative_error(z, exact):
     """Mean over all queries of ||z - Attn|| / ||Attn|| (norms over the head dimension)."""
-    z, exact = z.float(), exact.float()
+    z, exact = z.double(), exact.double()
     return float(((z - exact).norm(dim=-1) / exact.norm(dim=-1)).mean())
+
+
+def _std(t):
+    return float(t.std()) if t.numel() > 1 else 0.0
 
 
 def normaliser_error(lse, lse_exact):
@@ -72,13 +100,12 @@ def normaliser_error(lse, lse_exact):
 
 
 def run(seeds=10, blocks=BLOCKS, rounds=ROUNDS, n_mid=N_MID, n_seq=8, device="cuda", nq=64, keep_outputs=False,
-        value_gram=False):
+        value_gram=False, recipe="clustered"):
     """The grid.  value_gram: kernel weights with the value factor of Alg. 2 line 6.  keep_outputs: every cell also carries the tensors of its first counted seed (kept indices, weights,
     both estimates, the uniform comparator's indices) and the result the inputs, for checking against a reference."""
-    K, V, Q = make_inputs(device, n_seq=n_seq, n_mid=n_mid, nq=nq)
+    K, V, Q = make_inputs(device, n_seq=n_seq, n_mid=n_mid, nq=nq, recipe=recipe)
     n, d = K.shape[1], K.shape[2]
-    p0 = binding.make_params(d, 64, 0, K.dtype, log_c=0.0, seed=0, center=True)
-    exact, lse_exact = binding.attend_kv(p0, K, V, torch.ones(n_seq, n, device=device, dtype=torch.float32), Q)
+    exact, lse_exact = exact_attention_f64(K, V, Q)
     cells = []
     for b in blocks:
         for T in rounds:
@@ -86,7 +113,7 @@ def run(seeds=10, blocks=BLOCKS, rounds=ROUNDS, n_mid=N_MID, n_seq=8, device="cu
                 continue
             err_b, err_u, den_b, den_u, ms = [], [], [], [], []
             for s in range(seeds + 1):                      # run 0 warms up and is not counted
-                p = binding.make_params(d, b, T, K.dtype, log_c=(LOG_C_VALUE if value_gram else LOG_C).get(b, 0.0),
+                p = binding.make_params(d, b, T, K.dtype, log_c=log_c_for(recipe, b, value_gram),
                                         seed=1000 + s, center=True, value_gram=value_gram)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
@@ -110,14 +137,14 @@ def run(seeds=10, blocks=BLOCKS, rounds=ROUNDS, n_mid=N_MID, n_seq=8, device="cu
             tb, tu, tm = torch.tensor(err_b), torch.tensor(err_u), torch.tensor(ms)
             db, du = torch.tensor(den_b), torch.tensor(den_u)
             cells.append(dict(block=b, rate="1/%d" % (1 << T), rounds=T, kept=int(res["K"].shape[1]),
-                              compress_ms=float(tm.mean()), balancekv_rel_err=float(tb.mean()), balancekv_std=float(tb.std()),
-                              uniform_rel_err=float(tu.mean()), uniform_std=float(tu.std()),
-                              balancekv_normaliser_err=float(db.mean()), balancekv_normaliser_std=float(db.std()),
-                              uniform_normaliser_err=float(du.mean()), uniform_normaliser_std=float(du.std())))
+                              compress_ms=float(tm.mean()), balancekv_rel_err=float(tb.mean()), balancekv_std=_std(tb),
+                              uniform_rel_err=float(tu.mean()), uniform_std=_std(tu),
+                              balancekv_normaliser_err=float(db.mean()), balancekv_normaliser_std=_std(db),
+                              uniform_normaliser_err=float(du.mean()), uniform_normaliser_std=_std(du)))
             if keep_outputs:
                 cells[-1]["first"] = first
-    return dict(workload="%d KV sequences x (%d + %d + %d) tokens, d=%d, %d x %d queries, bf16, synthetic%s"
-                         % (n_seq, N_SINK, n_mid, N_RECENT, d, Q.shape[1], Q.shape[2],
+    return dict(workload="%d KV sequences x (%d + %d + %d) tokens, d=%d, %d x %d queries, bf16, synthetic (recipe %s)%s"
+                         % (n_seq, N_SINK, n_mid, N_RECENT, d, Q.shape[1], Q.shape[2], recipe,
                             ", weights with the value factor" if value_gram else ""), seeds=seeds, cells=cells,
                 **(dict(K=K, V=V, Q=Q, exact=exact) if keep_outputs else {}))
 
@@ -138,8 +165,7 @@ def run_alg1(seeds=5, block=128, rounds=ROUNDS, n=8192, n_seq=8, device="cuda", 
     K, Q = t["K"].to(device).contiguous(), t["Q"].to(device).contiguous()
     V = heavy_tailed(t["V"]).to(device).contiguous()
     d = K.shape[2]
-    p0 = binding.make_params(d, block, 0, K.dtype, log_c=0.0, seed=0, center=True)
-    exact, _ = binding.attend_kv(p0, K, V, torch.ones(n_seq, n, device=device, dtype=torch.float32), Q)
+    exact, _ = exact_attention_f64(K, V, Q)
     rows = []
     for T in rounds:
         acc = dict(sets_ms=[], attend_ms=[], alg1=[], single=[], uniform=[], kept_num=[], kept_den=[])
@@ -200,6 +226,7 @@ def main(argv=None):
     ap.add_argument("--json", action="store_true", help="print one JSON line instead of the table")
     ap.add_argument("--value-factor", action="store_true", help="kernel weights times <v_i,v_j>/r_value^2 (Alg. 2 line 6)")
     ap.add_argument("--alg1", action="store_true", help="Alg. 1 as listed (buckets, two kept sets) on heavy-tailed value norms")
+    ap.add_argument("--recipe", default="clustered", choices=["clustered", "iid"], help="input recipe of the grid")
     args = ap.parse_args(argv)
     if not torch.cuda.is_available():
         print("ablation: needs a GPU", file=sys.stderr)
@@ -209,7 +236,7 @@ def main(argv=None):
         result = run_alg1(seeds=args.seeds)
         print(json.dumps(result) if args.json else result["workload"] + ", %d seeds\n" % result["seeds"] + alg1_table(result))
         return 0
-    result = run(seeds=args.seeds, value_gram=args.value_factor)
+    result = run(seeds=args.seeds, value_gram=args.value_factor, recipe=args.recipe)
     if args.json:
         print(json.dumps(result))
     else:

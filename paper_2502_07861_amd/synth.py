@@ -69,6 +69,36 @@ def gqa_layer_bf16(n_seq=8, n=16384, d=128, g=4, nq=64, *, seed=0x250207861002, 
     return res
 
 
+def clustered_layer_bf16(n_seq=8, n=8704, d=128, g=4, nq=64, *, n_clusters=32, seed=0x250207861007, device="cpu",
+                         dtype=torch.bfloat16, key_radius=15.0, key_noise=4.0, value_radius=3.0, value_noise=1.5,
+                         query_norm=14.8, mix=3, mu_norm=2.0):
+    """A head whose keys repeat: every token belongs to one of ``n_clusters`` clusters (drawn independently per
+    token), key = common mean + cluster centre (norm ``key_radius``) + noise (norm about ``key_noise``), value =
+    cluster value (norm ``value_radius``) + noise (norm about ``value_noise``); a query points at the sum of ``mix``
+    cluster centres (norm ``query_norm``), so that exact attention mixes the values of a few clusters.  The norms
+    follow what App. B.5 reports for Llama-3.1-8B (|k - mean| about 15.5, |v| about 3.35, |q| about 14.8); the
+    cluster structure is the stand-in for the near-duplicate keys of real prompts, which is what a balancing of the
+    kernel exp(<k_i,k_j>/sqrt d) can exploit and independent Gaussians do not have.
+    K, V [n_seq, n, d], Q [n_seq, g, nq, d]."""
+    gen = _gen(seed, device)
+    f32 = dict(generator=gen, device=device, dtype=torch.float32)
+    mu = torch.randn(n_seq, d, **f32)
+    mu = mu_norm * mu / mu.norm(dim=1, keepdim=True)
+    centres = torch.randn(n_seq, n_clusters, d, **f32)
+    centres = key_radius * centres / centres.norm(dim=2, keepdim=True)
+    cvals = torch.randn(n_seq, n_clusters, d, **f32)
+    cvals = value_radius * cvals / cvals.norm(dim=2, keepdim=True)
+    member = torch.randint(0, n_clusters, (n_seq, n), generator=gen, device=device)
+    pick = member[..., None].expand(-1, -1, d)
+    K = mu[:, None, :] + torch.gather(centres, 1, pick) + torch.randn(n_seq, n, d, **f32) * (key_noise / d ** 0.5)
+    V = torch.gather(cvals, 1, pick) + torch.randn(n_seq, n, d, **f32) * (value_noise / d ** 0.5)
+    which = torch.randint(0, n_clusters, (n_seq, g, nq, mix), generator=gen, device=device)
+    q = torch.gather(centres[:, None, None].expand(-1, g, nq, -1, -1), 3, which[..., None].expand(-1, -1, -1, -1, d)).sum(dim=3)
+    q = q + torch.randn(n_seq, g, nq, d, **f32) * (2.0 / d ** 0.5)
+    Q = query_norm * q / q.norm(dim=-1, keepdim=True)
+    return dict(K=K.to(dtype), V=V.to(dtype), Q=Q.to(dtype), member=member)
+
+
 # The five workloads named by the benchmark description; n_seq = sessions*layers*KV heads.
 WORKLOADS = {
     "cfg1": dict(kind="single_head_fp32", n_seq=1, n=1024, d=64, g=1, nq=16, block=256, rounds=1,

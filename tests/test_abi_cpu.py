@@ -138,3 +138,25 @@ def test_ablation_comparator_and_error_formula():
     z, e = torch.randn(2, 3, 4, 8), torch.randn(2, 3, 4, 8)
     ref = np.mean(np.linalg.norm((z - e).numpy(), axis=-1) / np.linalg.norm(e.numpy(), axis=-1))
     assert abs(ablation.relative_error(z, e) - ref) < 1e-6
+
+
+def test_ablation_yardstick_is_eq1_and_recipe_norms(oracle):
+    """The ablation's "exact" column is Eq. 1 in float64 (checked against the oracle's brute force), and the recipe
+    with repeating keys has the norms App. B.5 reports (|k - mean| about 15.5, |v| about 3.35, |q| about 14.8)."""
+    import numpy as np
+    import torch
+    from paper_2502_07861_amd import ablation, synth
+    t = synth.clustered_layer_bf16(n_seq=2, n=512, d=128, g=2, nq=3, seed=11)
+    K, V, Q = t["K"], t["V"], t["Q"]
+    out, lse = ablation.exact_attention_f64(K, V, Q)
+    Kd, Vd, Qd = (x.float().numpy().astype(np.float64) for x in (K, V, Q))
+    for s in range(2):
+        for a in range(2):
+            for j in range(3):
+                np.testing.assert_allclose(out[s, a, j].numpy(), oracle.exact_attention(Qd[s, a, j], Kd[s], Vd[s]), atol=1e-10)
+                _, l = oracle.attend(Qd[s, a, j], Kd[s], Vd[s], np.ones(512))
+                assert abs(float(lse[s, a, j]) - l) < 1e-9
+    kc = Kd - Kd.mean(axis=1, keepdims=True)
+    assert 14.5 < np.linalg.norm(kc, axis=2).mean() < 16.5
+    assert 3.1 < np.linalg.norm(Vd, axis=2).mean() < 3.6 and 14.5 < np.linalg.norm(Qd, axis=3).mean() < 15.1
+    assert int(t["member"].max()) == 31

@@ -930,19 +930,27 @@ def test_prefill_and_attend_replay_from_a_captured_graph(bk, synth):
 
 
 # ------------------------------------------------------------------------------------------ ablation grid
-def test_ablation_grid_cell_against_oracle(bk, synth, oracle):
-    """The single-layer ablation (grid of block size x rate, uniform-sampling comparator) on a small instance: every
-    number of a cell is recomputed by the oracle from the kept sets (Alg. 1 output line in fp64 against Eq. 1)."""
+@pytest.mark.parametrize("recipe", ["clustered", "iid"])
+def test_ablation_grid_cell_against_oracle(bk, synth, oracle, recipe):
+    """The single-layer ablation (grid of block size x rate, uniform-sampling comparator) on a small instance: the
+    per-query errors behind a cell's figures are recomputed by the oracle from the kept sets of the cell's first seed
+    (Alg. 1 output line in fp64 against Eq. 1 in fp64), for BalanceKV and for the comparator."""
     from paper_2502_07861_amd import ablation
-    r = ablation.run(seeds=2, blocks=(64,), rounds=(1, 2), n_mid=1024, n_seq=2, nq=4, keep_outputs=True)
+    r = ablation.run(seeds=1, blocks=(64,), rounds=(1, 2), n_mid=1024, n_seq=2, nq=4, keep_outputs=True, recipe=recipe)
     K, V, Q = to_f64(r["K"]), to_f64(r["V"]), to_f64(r["Q"])
     n = K.shape[1]
+    # the yardstick of the study is Eq. 1 itself
+    ex = r["exact"].cpu().numpy()
+    for s in range(K.shape[0]):
+        for a in range(Q.shape[1]):
+            np.testing.assert_allclose(ex[s, a, 0], oracle.exact_attention(Q[s, a, 0], K[s], V[s]), rtol=0, atol=1e-9)
     assert [c["rate"] for c in r["cells"]] == ["1/2", "1/4"]
     for c in r["cells"]:
         f = c["first"]
         T = c["rounds"]
         assert c["kept"] == 256 + (1024 >> T) + 256 and c["compress_ms"] > 0
-        for idx_t, w_t, z_t in ((f["idx"], f["w"], f["z"]), (f["idx_uniform"], f["w_uniform"], f["z_uniform"])):
+        for idx_t, w_t, z_t, key in ((f["idx"], f["w"], f["z"], "balancekv_rel_err"),
+                                     (f["idx_uniform"], f["w_uniform"], f["z_uniform"], "uniform_rel_err")):
             idx, w, z = idx_t.cpu().numpy().astype(np.int64), w_t.cpu().numpy().astype(np.float64), to_f64(z_t)
             errs = []
             for s in range(K.shape[0]):
@@ -953,14 +961,30 @@ def test_ablation_grid_cell_against_oracle(bk, synth, oracle):
                         est = oracle.attend(Q[s, a, j], K[s][idx[s]], V[s][idx[s]], w[s])[0]
                         np.testing.assert_allclose(z[s, a, j], est, rtol=0, atol=2e-2 * np.linalg.norm(est))
                         errs.append(np.linalg.norm(est - exact) / np.linalg.norm(exact))
-            # the cell's figure is a mean over two seeds of values like this one
-            assert 0.2 * np.mean(errs) < (c["balancekv_rel_err"] if idx_t is f["idx"] else c["uniform_rel_err"]) < 5 * np.mean(errs) + 2e-2
+            # one counted seed: the cell's figure is the mean of exactly these per-query errors, up to the bf16 rounding
+            # of the kernel's output (2^-9 relative per element, against |exact|)
+            bf16 = 2.0 ** -8 * np.mean([np.linalg.norm(to_f64(z_t)[s]) / np.linalg.norm(ex[s]) for s in range(K.shape[0])])
+            assert abs(c[key] - np.mean(errs)) <= 0.02 * np.mean(errs) + bf16
         # the comparator keeps the windows and a duplicate-free sample of the right size in between
         iu = f["idx_uniform"].cpu().numpy()
         assert np.all(iu[:, :256] == np.arange(256)) and np.all(iu[:, -256:] == np.arange(n - 256, n))
         mid = iu[:, 256:-256]
         assert mid.shape[1] == 1024 >> T and np.all((mid >= 256) & (mid < n - 256))
 
+
+def test_ablation_shows_the_method_on_repeating_keys(bk):
+    """On the recipe with repeating keys (norms as App. B.5 reports them) the kept set of BalanceKV answers better than
+    a uniform sample of the same size, as Section 4.1 reports for real activations: the softmax normaliser, which
+    the keys-only walk balances directly, clearly, and the attention output at rates 1/2 and 1/4."""
+    from paper_2502_07861_amd import ablation
+    r = ablation.run(seeds=4, blocks=(256,), rounds=(1, 2), recipe="clustered")
+    for c in r["cells"]:
+        print(c["rate"], "BalanceKV %.4f +- %.4f, uniform %.4f +- %.4f; normaliser %.4f vs %.4f"
+              % (c["balancekv_rel_err"], c["balancekv_std"], c["uniform_rel_err"], c["uniform_std"],
+                 c["balancekv_normaliser_err"], c["uniform_normaliser_err"]))
+        assert c["balancekv_normaliser_err"] < 0.85 * c["uniform_normaliser_err"]
+        assert c["balancekv_rel_err"] < c["uniform_rel_err"] - max(c["balancekv_std"], c["uniform_std"])
+        assert c["balancekv_rel_err"] < 0.5                      # far from answering zero
 
 
 # ------------------------------------------------------------------------------------------ Alg. 1: buckets, two instances

@@ -1367,14 +1367,15 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int r = r0 + u * RG;
-                    if (r < half) *reinterpret_cast<uintx4*>(Ko + (size_t)r * G::kRowBytes + sl * 16) = kraw[u];
+                    // (streamed past the caches: a later pass over the survivors then finds no write-backs in its way)
+                    if (r < half) __builtin_nontemporal_store(kraw[u], reinterpret_cast<uintx4*>(Ko + (size_t)r * G::kRowBytes + sl * 16));
                 }
             }
             if (do_v) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int r = r0 + u * RG;
-                    if (r < half) *reinterpret_cast<uintx4*>(Vo + (size_t)r * G::kRowBytes + sl * 16) = vraw[u];
+                    if (r < half) __builtin_nontemporal_store(vraw[u], reinterpret_cast<uintx4*>(Vo + (size_t)r * G::kRowBytes + sl * 16));
                 }
             }
         }

@@ -292,6 +292,55 @@ size_t bkv_cache_attend_workspace_bytes(const bkv_cache* c, int32_t g, int32_t n
 int bkv_attend(const bkv_cache* c, const void* Q, int32_t g, int32_t nq, void* out, float* lse_out,
                void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* ---- Alg. 1 token by token: the streaming data structure of the listing ------------------------------
+ * The state of n_seq sequences after j tokens each (all sequences advance in lock step, one token per call): per
+ * sequence the instance MR-Denominator and one instance MR-Numerator_i per live value-norm bucket i, each holding the
+ * levels Alg. 3 keeps.  Which numerator instance a token feeds, when it carries and which buckets are erased depend
+ * on the values, so every counter lives on the device and no call reads anything back: bkv_stream_append is a fixed
+ * sequence of launches (route the token; per round r < T: halve the numerator blocks that carry, halve the
+ * denominator blocks -- launched only at the tokens where the host knows they carry --, move the survivors back).
+ *   regions     numerator instances a sequence can hold at a time (1..64); a bucket takes a free one on its first
+ *               token and gives it back when line 8 erases it
+ *   cap_num     token places per numerator region, cap_den places of the denominator region (>= block each); an
+ *               instance that has seen m tokens holds at most (m >> T) + (T + 1) * block / 2 + block of them
+ *   n_total, eps, r   the erase rule of line 8: after every token the buckets with
+ *               2^i <= eps/(2 n_total) e^{-r^2/sqrt d} max_{j' <= j} |v_j'| are dropped, their tokens with them
+ *               (eps <= 0: none); a token that falls into such a bucket is not stored
+ *   p           block, rounds, dtype, d, seed, ln c, BKV_CENTER_KEYS as in bkv_balancekv_sets; the numerator
+ *               instances use the value factor with r_value = 2^i whether or not BKV_VALUE_GRAM is set
+ * Buckets, bucket clamp, rows without a bucket, instance numbers and draws exactly as in bkv_balancekv_sets: with
+ * eps <= 0 the state after n tokens holds the same tokens with the same weights as the offline call on those n tokens.
+ * device_storage: bkv_stream_bytes() bytes, 256-byte aligned, caller-owned, must outlive the handle; cleared by init.
+ * Overflow never writes out of bounds: the token is dropped for that instance and a bit is set in the error word. */
+#define BKV_STREAM_NUM_FULL  4   /* error word: a numerator region was full, a token was not stored           */
+#define BKV_STREAM_DEN_FULL  8   /* error word: the denominator region was full                               */
+#define BKV_STREAM_NO_REGION 16  /* error word: more live buckets than regions, a token was not stored        */
+typedef struct bkv_stream bkv_stream;
+size_t bkv_stream_bytes(const bkv_params* p, int64_t n_seq, int32_t regions, int64_t cap_num, int64_t cap_den);
+int bkv_stream_init(bkv_stream** out, const bkv_params* p, int64_t n_seq, int64_t seq_base, int32_t regions,
+                    int64_t cap_num, int64_t cap_den, int64_t n_total, float eps, float r,
+                    void* device_storage, size_t bytes, void* hip_stream);
+int bkv_stream_free(bkv_stream* s);                      /* host handle only                          */
+int64_t bkv_stream_tokens_seen(const bkv_stream* s);
+/* One token per sequence: k, v [n_seq, d] device.  status_num, status_den [n_seq, T] int32 device or NULL: FAIL bit
+ * and margin counts of this instance kind's halvings per round, accumulated as in bkv_merge_reduce (never cleared
+ * here).  Returns the number of launches issued (> 0) or a negative code.                             */
+int bkv_stream_append(bkv_stream* s, const void* k, const void* v, int32_t* status_num, int32_t* status_den,
+                      void* hip_stream);
+/* Device views (any pointer argument may be NULL): K_n, V_n [n_seq, regions, cap_num, d]; w_n (2^level, 0: no token),
+ * orig_n (index in the stream of the token stored there) [n_seq, regions, cap_num]; K_d [n_seq, cap_den, d]; w_d,
+ * orig_d [n_seq, cap_den]; count [n_seq, regions + 1] int32 stored tokens per region, the denominator last;
+ * bucket [n_seq, regions] int32 bucket index of every region (INT32_MIN: free); error_word: one int32,
+ * BKV_STATUS_INTERNAL | BKV_STREAM_* bits, sticky since init.  Read them in stream order.             */
+int bkv_stream_views(const bkv_stream* s, void** K_n, void** V_n, float** w_n, int32_t** orig_n, void** K_d,
+                     float** w_d, int32_t** orig_d, int32_t** count, int32_t** bucket, int32_t** error_word);
+/* Alg. 1 output line over the current state: numerator sum over all regions / denominator sum over MR-Denominator's
+ * levels.  Q, out, lse_out, precision and limits as in bkv_attend_sets.  Reads every place of every region (absent
+ * places have weight 0), so its cost follows the capacities, not the occupancy.                        */
+size_t bkv_stream_attend_workspace_bytes(const bkv_stream* s, int32_t g, int32_t nq);
+int bkv_stream_attend(const bkv_stream* s, const void* Q, int32_t g, int32_t nq, void* out, float* lse_out,
+                      void* workspace, size_t ws_bytes, void* hip_stream);
+
 /* ---- diagnostics: per-launch kernel times ---------------------------------------------------------
  * For callers that want the duration of the individual kernels behind a call (benchmarks): after
  * bkv_profile_enable(n > 0) the library attaches a start and a stop event to each kernel launch (the

@@ -74,6 +74,14 @@ _SIGNATURES = {
     "bkv_append_token": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bkv_cache_attend_workspace_bytes": (_sz, [_vp, _i32, _i32]),
     "bkv_attend": (C.c_int, [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
+    "bkv_stream_bytes": (_sz, [_PP, _i64, _i32, _i64, _i64]),
+    "bkv_stream_init": (C.c_int, [C.POINTER(_vp), _PP, _i64, _i64, _i32, _i64, _i64, _i64, C.c_float, C.c_float, _vp, _sz, _vp]),
+    "bkv_stream_free": (C.c_int, [_vp]),
+    "bkv_stream_tokens_seen": (_i64, [_vp]),
+    "bkv_stream_append": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp]),
+    "bkv_stream_views": (C.c_int, [_vp] + [C.POINTER(_vp)] * 10),
+    "bkv_stream_attend_workspace_bytes": (_sz, [_vp, _i32, _i32]),
+    "bkv_stream_attend": (C.c_int, [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
     "bkv_measure_peak": (C.c_int, [_i32, _i32, _vp, _sz, _vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "bkv_profile_enable": (C.c_int, [_i32]),
     "bkv_profile_read": (C.c_int, [_vp, _vp, _vp, _i32]),
@@ -423,6 +431,87 @@ class Cache:
         kv_bytes = self.n_seq * self.cap * self.p.d * es
         return (view(Kp, kv_bytes, dt, (self.n_seq, self.cap, self.p.d)), view(Vp, kv_bytes, dt, (self.n_seq, self.cap, self.p.d)),
                 view(wp, self.n_seq * self.cap * 4, torch.float32, (self.n_seq, self.cap)))
+
+
+# ------------------------------------------------------------------------------------------ Alg. 1 token by token
+BKV_STREAM_NUM_FULL, BKV_STREAM_DEN_FULL, BKV_STREAM_NO_REGION = 4, 8, 16
+FREE_REGION = -(1 << 31)
+
+
+class Stream:
+    """bkv_stream: MR-Denominator and one MR-Numerator_i per live bucket for n_seq sequences, fed token by token."""
+
+    def __init__(self, p, n_seq, regions, cap_num, cap_den, n_total=0, eps=0.0, r=0.0, seq_base=0, device="cuda"):
+        self.p, self.n_seq, self.regions, self.cap_num, self.cap_den = p, n_seq, regions, cap_num, cap_den
+        nbytes = int(lib().bkv_stream_bytes(C.byref(p), n_seq, regions, cap_num, cap_den))
+        if nbytes == 0:
+            raise BkvError(BKV_EINVAL, "bkv_stream_bytes")
+        self.storage = torch.empty(nbytes + 256, device=device, dtype=torch.uint8)
+        off = (-self.storage.data_ptr()) % 256
+        h = C.c_void_p()
+        _check(lib().bkv_stream_init(C.byref(h), C.byref(p), n_seq, seq_base, regions, cap_num, cap_den, n_total, eps, r,
+                                     C.c_void_p(self.storage.data_ptr() + off), nbytes, _stream()), "bkv_stream_init")
+        self.h = h
+        self._attend_ws = {}
+
+    def close(self):
+        if self.h:
+            lib().bkv_stream_free(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def tokens_seen(self):
+        return int(lib().bkv_stream_tokens_seen(self.h))
+
+    def append(self, k, v, status_num=None, status_den=None):
+        """bkv_stream_append; returns the number of launches issued."""
+        dt = _torch_dtype(self.p)
+        return _check(lib().bkv_stream_append(self.h, _ptr(k, dt, "k"), _ptr(v, dt, "v"), _ptr(status_num, torch.int32, "status_num"),
+                                              _ptr(status_den, torch.int32, "status_den"), _stream()), "bkv_stream_append")
+
+    def attend(self, Q, out=None, lse=True):
+        dt = _torch_dtype(self.p)
+        n_seq, g, nq, d = Q.shape
+        if out is None:
+            out = torch.empty(n_seq, g, nq, d, device=Q.device, dtype=dt)
+        lse_t = torch.empty(n_seq, g, nq, device=Q.device, dtype=torch.float32) if lse else None
+        ws = self._attend_ws.get((g, nq))
+        if ws is None:
+            ws = torch.empty(int(lib().bkv_stream_attend_workspace_bytes(self.h, g, nq)), device=Q.device, dtype=torch.uint8)
+            self._attend_ws[(g, nq)] = ws
+        _check(lib().bkv_stream_attend(self.h, _ptr(Q, dt, "Q"), g, nq, _ptr(out), _ptr(lse_t), _ptr(ws), ws.numel(),
+                                       _stream()), "bkv_stream_attend")
+        return out, lse_t
+
+    def views(self):
+        """Device views of the state (no copy), as a dict: K_n, V_n [n_seq, regions, cap_num, d]; w_n, orig_n
+        [n_seq, regions, cap_num]; K_d [n_seq, cap_den, d]; w_d, orig_d [n_seq, cap_den]; count [n_seq, regions + 1];
+        bucket [n_seq, regions]; error_word [1]."""
+        dt = _torch_dtype(self.p)
+        es = 2 if self.p.dtype == BKV_BF16 else 4
+        ptrs = [C.c_void_p() for _ in range(10)]
+        _check(lib().bkv_stream_views(self.h, *[C.byref(q) for q in ptrs]), "bkv_stream_views")
+        base = self.storage.data_ptr()
+        n, R, cn, cd, d = self.n_seq, self.regions, self.cap_num, self.cap_den, self.p.d
+
+        def view(ptr, dtype, shape, elem):
+            nbytes = elem
+            for x in shape:
+                nbytes *= x
+            off = ptr.value - base
+            assert 0 <= off and off + nbytes <= self.storage.numel()
+            return self.storage[off:off + nbytes].view(dtype).view(*shape)
+        names = ["K_n", "V_n", "w_n", "orig_n", "K_d", "w_d", "orig_d", "count", "bucket", "error_word"]
+        specs = [(dt, (n, R, cn, d), es), (dt, (n, R, cn, d), es), (torch.float32, (n, R, cn), 4), (torch.int32, (n, R, cn), 4),
+                 (dt, (n, cd, d), es), (torch.float32, (n, cd), 4), (torch.int32, (n, cd), 4), (torch.int32, (n, R + 1), 4),
+                 (torch.int32, (n, R), 4), (torch.int32, (1,), 4)]
+        return {nm: view(q, *sp) for nm, q, sp in zip(names, ptrs, specs)}
 
 
 def profile_enable(n: int):

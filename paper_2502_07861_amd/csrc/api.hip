@@ -53,6 +53,12 @@ void fill_common(bkv::CompressArgs& a, const bkv_params* p) {
 
 }  // namespace
 
+struct bkv_stream {
+    bkv_params p;
+    bkv::StreamState s;
+    int64_t seen;         // tokens appended per sequence
+};
+
 struct bkv_cache {
     bkv_params p;
     int64_t n_seq, cap;
@@ -632,6 +638,167 @@ int bkv_attend(const bkv_cache* c, const void* Q, int32_t g, int32_t nq, void* o
     if (!c) return BKV_EINVAL;
     return bkv_attend_kv(&c->p, c->K, c->V, c->w, c->n_seq, c->count, c->cap, Q, g, nq, out, lse_out, workspace,
                          ws_bytes, hip_stream);
+}
+
+
+// ------------------------------------------------------------------------------------------ Alg. 1 token by token
+size_t bkv_stream_bytes(const bkv_params* p, int64_t n_seq, int32_t regions, int64_t cap_num, int64_t cap_den) {
+    if (check_params(p) || n_seq <= 0 || regions < 1 || regions > 64 || cap_num < p->block || cap_den < p->block) return 0;
+    const size_t rb = (size_t)row_bytes(p), R = (size_t)regions, half = (size_t)p->block / 2;
+    const size_t T = (size_t)(p->rounds > 0 ? p->rounds : 1);
+    size_t s = 0;
+    s += 2 * align_up((size_t)n_seq * R * cap_num * rb, 256) + 2 * align_up((size_t)n_seq * R * cap_num * 4, 256);
+    s += align_up((size_t)n_seq * cap_den * rb, 256) + 2 * align_up((size_t)n_seq * cap_den * 4, 256);
+    s += 2 * align_up((size_t)n_seq * (R + 1) * 4, 256) + align_up((size_t)n_seq * R * 4, 256) + align_up((size_t)n_seq * 4, 256);
+    s += 256;
+    s += align_up(T * 2 * (size_t)n_seq * sizeof(bkv::InstDesc), 256);
+    s += 2 * align_up(2 * (size_t)n_seq * half * rb, 256) + align_up(2 * (size_t)n_seq * half * 4, 256);
+    return s;
+}
+
+int bkv_stream_init(bkv_stream** out, const bkv_params* p, int64_t n_seq, int64_t seq_base, int32_t regions, int64_t cap_num,
+                    int64_t cap_den, int64_t n_total, float eps, float r, void* device_storage, size_t bytes, void* hip_stream) {
+    if (!out) return BKV_EINVAL;
+    *out = nullptr;
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (n_seq <= 0 || seq_base < 0 || regions < 1 || regions > 64 || cap_num < p->block || cap_den < p->block || !(r >= 0.f))
+        return BKV_EINVAL;
+    if (n_seq > 65535 || cap_den > (1ll << 30) || (int64_t)regions * cap_num > (1ll << 30)) return BKV_ESHAPE;
+    if (eps > 0.f && n_total <= 0) return BKV_EINVAL;
+    const size_t need = bkv_stream_bytes(p, n_seq, regions, cap_num, cap_den);
+    if (!device_storage || (reinterpret_cast<uintptr_t>(device_storage) & 255u) || bytes < need) return BKV_EINVAL;
+    bkv_stream* h = new (std::nothrow) bkv_stream;
+    if (!h) return BKV_EINVAL;
+    h->p = *p; h->seen = 0;
+    bkv::StreamState& s = h->s;
+    memset(&s, 0, sizeof(s));
+    const size_t rb = (size_t)row_bytes(p), R = (size_t)regions, half = (size_t)p->block / 2;
+    const size_t T = (size_t)(p->rounds > 0 ? p->rounds : 1);
+    char* at = (char*)device_storage;
+    auto carve = [&](size_t b) { char* q = at; at += align_up(b, 256); return q; };
+    s.Kn = carve((size_t)n_seq * R * cap_num * rb); s.Vn = carve((size_t)n_seq * R * cap_num * rb);
+    s.wn = (float*)carve((size_t)n_seq * R * cap_num * 4); s.on = (int32_t*)carve((size_t)n_seq * R * cap_num * 4);
+    s.Kd = carve((size_t)n_seq * cap_den * rb);
+    s.wd = (float*)carve((size_t)n_seq * cap_den * 4); s.od = (int32_t*)carve((size_t)n_seq * cap_den * 4);
+    s.cnt = (int32_t*)carve((size_t)n_seq * (R + 1) * 4); s.jj = (int32_t*)carve((size_t)n_seq * (R + 1) * 4);
+    s.bucket = (int32_t*)carve((size_t)n_seq * R * 4);
+    s.vmax2 = (unsigned int*)carve((size_t)n_seq * 4);
+    s.err = (int32_t*)carve(256);
+    s.desc = (bkv::InstDesc*)carve(T * 2 * (size_t)n_seq * sizeof(bkv::InstDesc));
+    s.tmpK = carve(2 * (size_t)n_seq * half * rb); s.tmpV = carve(2 * (size_t)n_seq * half * rb);
+    s.tmpIdx = (int32_t*)carve(2 * (size_t)n_seq * half * 4);
+    s.n_seq = n_seq; s.seq_base = seq_base; s.cap_n = cap_num; s.cap_d = cap_den;
+    s.regions = regions; s.b = p->block; s.T = p->rounds; s.row_bytes = (int32_t)rb; s.dtype = p->dtype; s.d = p->d;
+    s.erase2 = 0.f;
+    if (eps > 0.f) {
+        const double f = (double)eps / (2.0 * (double)n_total) * exp(-(double)r * (double)r / sqrt((double)p->d));
+        s.erase2 = (float)(f * f);
+    }
+    // weights 0 (no token), counters 0, rows finite; every region free
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipError_t e = bkv::launch_fill_u32(device_storage, 0u, (int64_t)(need / 4), st);
+    if (e == hipSuccess) e = bkv::launch_fill_u32(s.bucket, 0x80000000u, n_seq * (int64_t)R, st);
+    if (e != hipSuccess) { delete h; return hip_fail(e); }
+    *out = h;
+    return BKV_OK;
+}
+
+int bkv_stream_free(bkv_stream* s) {
+    if (!s) return BKV_EINVAL;
+    delete s;
+    return BKV_OK;
+}
+
+int64_t bkv_stream_tokens_seen(const bkv_stream* s) { return s ? s->seen : (int64_t)BKV_EINVAL; }
+
+int bkv_stream_append(bkv_stream* h, const void* k, const void* v, int32_t* status_num, int32_t* status_den, void* hip_stream) {
+    if (!h || !k || !v || !aligned16(k) || !aligned16(v)) return BKV_EINVAL;
+    if (h->seen >= (1ll << 31) - 1) return BKV_ECAPACITY;
+    const bkv::StreamState& s = h->s;
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipError_t e;
+    int launches = 0;
+    if ((e = bkv::stream_route(s, k, v, h->seen, st)) != hipSuccess) return hip_fail(e);
+    ++launches;
+    const int64_t j = ++h->seen;
+    const int b = s.b, half = b / 2;
+    for (int r = 0; r < s.T; ++r) {
+        // MR-Numerator_i: any sequence's current bucket may carry at this token; instances that do not are skipped on the device
+        bkv_params pn = h->p;
+        pn.flags |= BKV_VALUE_GRAM;
+        bkv::CompressArgs a;
+        fill_common(a, &pn);
+        a.desc = s.desc + (size_t)(r * 2 + 0) * s.n_seq;
+        a.K = s.Kn; a.V = s.Vn; a.K_out = s.tmpK; a.V_out = s.tmpV; a.idx_out = s.tmpIdx;
+        a.v_seq_stride = (int64_t)s.regions * s.cap_n;
+        a.status_out = status_num; a.status_stride = s.T; a.sticky_err = s.err;
+        a.tree_mode = 1; a.round = r; a.blocks_per_seq = 1;
+        if ((e = bkv::launch_compress(s.dtype, s.d, false, a, s.n_seq, st)) != hipSuccess) return hip_fail(e);
+        ++launches;
+        // MR-Denominator sees every token: it carries at round r exactly when block * 2^r divides j
+        if (j % ((int64_t)b << r) == 0) {
+            bkv_params pd = h->p;
+            pd.flags &= ~BKV_VALUE_GRAM;
+            fill_common(a, &pd);
+            a.desc = s.desc + (size_t)(r * 2 + 1) * s.n_seq;
+            a.K = s.Kd; a.V = nullptr; a.K_out = s.tmpK + (size_t)s.n_seq * half * s.row_bytes; a.V_out = nullptr;
+            a.idx_out = s.tmpIdx + (size_t)s.n_seq * half;
+            a.v_seq_stride = s.cap_d;
+            a.status_out = status_den; a.status_stride = s.T; a.sticky_err = s.err;
+            a.tree_mode = 1; a.round = r; a.blocks_per_seq = 1;
+            if ((e = bkv::launch_compress(s.dtype, s.d, false, a, s.n_seq, st)) != hipSuccess) return hip_fail(e);
+            ++launches;
+        }
+        if ((e = bkv::stream_fixup(s, r, st)) != hipSuccess) return hip_fail(e);
+        ++launches;
+    }
+    return launches;
+}
+
+int bkv_stream_views(const bkv_stream* h, void** K_n, void** V_n, float** w_n, int32_t** orig_n, void** K_d, float** w_d,
+                     int32_t** orig_d, int32_t** count, int32_t** bucket, int32_t** error_word) {
+    if (!h) return BKV_EINVAL;
+    const bkv::StreamState& s = h->s;
+    if (K_n) *K_n = s.Kn;
+    if (V_n) *V_n = s.Vn;
+    if (w_n) *w_n = s.wn;
+    if (orig_n) *orig_n = s.on;
+    if (K_d) *K_d = s.Kd;
+    if (w_d) *w_d = s.wd;
+    if (orig_d) *orig_d = s.od;
+    if (count) *count = s.cnt;
+    if (bucket) *bucket = s.bucket;
+    if (error_word) *error_word = s.err;
+    return BKV_OK;
+}
+
+size_t bkv_stream_attend_workspace_bytes(const bkv_stream* h, int32_t g, int32_t nq) {
+    if (!h) return 0;
+    return bkv_attend_sets_workspace_bytes(&h->p, h->s.n_seq, g, nq);
+}
+
+int bkv_stream_attend(const bkv_stream* h, const void* Q, int32_t g, int32_t nq, void* out, float* lse_out, void* workspace,
+                      size_t ws_bytes, void* hip_stream) {
+    if (!h) return BKV_EINVAL;
+    const bkv::StreamState& s = h->s;
+    if (h->seen == 0) return BKV_EINVAL;                   // the estimator of an empty stream is 0 / 0
+    const int64_t places = (int64_t)s.regions * s.cap_n;
+    // MR-Denominator holds a known number of tokens (every sequence has fed it every token); numerator regions are read whole
+    int64_t count_d = h->seen;
+    {
+        const int64_t blocks = h->seen / s.b;
+        count_d = h->seen - blocks * s.b;                  // tail
+        int64_t reached = blocks;                          // blocks that reached level l
+        for (int l = 1; l <= s.T; ++l) {
+            if (l < s.T) { if (reached & 1) count_d += s.b / 2; reached >>= 1; }
+            else count_d += reached * (int64_t)(s.b / 2);
+        }
+        if (s.T == 0) count_d = h->seen;
+        if (count_d > s.cap_d) count_d = s.cap_d;
+    }
+    return bkv_attend_sets(&h->p, s.Kn, s.Vn, s.wn, places, places, s.Kd, s.wd, count_d, s.cap_d, s.n_seq, Q, g, nq, out, lse_out,
+                           workspace, ws_bytes, hip_stream);
 }
 
 }  // extern "C"

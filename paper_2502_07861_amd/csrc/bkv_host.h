@@ -122,6 +122,29 @@ size_t sets_workspace_bytes(int row_bytes, int b, int64_t n_seq, int64_t n);
 hipError_t run_sets(const SetsArgs& q, hipStream_t st);
 hipError_t launch_rescale(int dtype, void* out, const float* lse_num, const float* lse_den, int64_t rows, int d, hipStream_t st);
 
+// Alg. 1 token by token: device state of n_seq sequences.  Every sequence owns `regions` numerator regions of
+// cap_n token places (one per live bucket, handed out on a bucket's first token and taken back when the bucket is
+// erased) and one denominator region of cap_d places.  A region holds the levels of its MergeAndReduce instance as
+// the streaming cache does: level-T survivors first, then levels T-1..1, then the tail; places beyond `cnt` have
+// weight 0.  All counters live on the device: which instance carries at a token depends on the values.
+struct StreamState {
+    char* Kn; char* Vn; float* wn; int32_t* on;   // [n_seq, regions, cap_n(, d)]: keys, values, weights, original token index
+    char* Kd; float* wd; int32_t* od;             // [n_seq, cap_d(, d)]
+    int32_t* cnt;             // [n_seq, regions + 1]: stored tokens; entry `regions` is the denominator instance
+    int32_t* jj;              // [n_seq, regions + 1]: tokens the instance has seen since it was created
+    int32_t* bucket;          // [n_seq, regions]: bucket index of the region, INT32_MIN: free
+    unsigned int* vmax2;      // [n_seq]: largest |v|^2 so far (bits of a non-negative float)
+    int32_t* err;             // one word: BKV_STATUS_INTERNAL of any halving | BKV_STREAM_* overflow bits
+    InstDesc* desc;           // [T, 2, n_seq]: the carries of the current token (0: numerator, 1: denominator)
+    char* tmpK; char* tmpV;   // [2, n_seq, b/2, d]: survivors of the halving in flight
+    int32_t* tmpIdx;          // [2, n_seq, b/2]: their places
+    int64_t n_seq, seq_base, cap_n, cap_d;
+    int32_t regions, b, T, row_bytes, dtype, d;
+    float erase2;             // (eps / (2n) * exp(-r^2 / sqrt d))^2, 0: nothing is erased
+};
+hipError_t stream_route(const StreamState& s, const void* k, const void* v, int64_t j, hipStream_t st);
+hipError_t stream_fixup(const StreamState& s, int round, hipStream_t st);
+
 struct AttendArgs {
     const char* K;            // [n_seq, stride_tokens, d]
     const char* V;

@@ -650,6 +650,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         if (ds.rvalue2 > 0.f) rvalue2 = ds.rvalue2;
     }
     const char* Kin = a.K + in_tok0 * G::kRowBytes;
+    // without idx_in a token's index within its sequence is its place in the input: by block number, or (ragged
+    // launches, keys and values stored side by side) the instance's first token less the start of its sequence
+    const int64_t tok_base = a.desc ? in_tok0 - seq * a.v_seq_stride : a.idx_base + (int64_t)blk * b;
     const int sl = tid % SL, rg = tid / SL;
     const bool center = (a.flags & BKV_CENTER_KEYS) != 0;
     const bool need_norm = !(a.rkey2 > 0.f);
@@ -764,7 +767,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     // this lane's value row of token i of the block (VG = 2: the operand fetches go through these)
     const char* Vseq = VG != 0 ? a.V + (size_t)seq * a.v_seq_stride * G::kRowBytes : nullptr;
     auto vrow = [&](int i) -> const char* {
-        const int64_t tok = a.idx_in ? (int64_t)a.idx_in[in_tok0 + i] : a.idx_base + (int64_t)blk * b + i;
+        const int64_t tok = a.idx_in ? (int64_t)a.idx_in[in_tok0 + i] : tok_base + i;
         return Vseq + (size_t)tok * G::kRowBytes;
     };
     if (VG == 1 || (VG == 2 && !(rvalue2 > 0.f))) {      // VG = 2 with a given radius: nothing to do here
@@ -1320,7 +1323,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     // survivors: rows of the ORIGINAL keys / values, ascending index (16-byte slices, several rows in flight)
     auto src_token = [&](int r) -> int64_t {      // token of survivor r within its sequence, in the value tensor's frame
         const int kept = keptIdx[r];
-        return a.idx_in ? (int64_t)a.idx_in[in_tok0 + kept] : a.idx_base + (int64_t)blk * b + kept;
+        return a.idx_in ? (int64_t)a.idx_in[in_tok0 + kept] : tok_base + kept;
     };
     {
         // Keys come from LDS when the whole block is still resident, else from global memory (L2); value rows

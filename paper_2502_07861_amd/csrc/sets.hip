@@ -49,7 +49,19 @@ __global__ __launch_bounds__(256) void value_norm_kernel(const char* V, int64_t 
     }
 }
 
-// Slot of every token: bucket i = the smallest i with 2^i >= |v| (Alg. 1 line 5), from the exponent of |v|^2;
+// Bucket of a value row with |v|^2 = x: the smallest i with 2^i >= |v| (Alg. 1 line 5), from the exponent of x,
+// clamped to [kBucketMin, kBucketMax].  False: the row belongs to no bucket (zero or non-finite norm).
+__device__ __forceinline__ bool bucket_of(float x, int& i) {
+    if (!(x > 0.f && x < __builtin_inff())) return false;
+    int e;
+    const float m = frexpf(x, &e);                    // x = m 2^e, 1/2 <= m < 1
+    const int ee = (m == 0.5f) ? e - 1 : e;           // smallest integer with 2^ee >= x
+    i = ee >= 0 ? (ee + 1) / 2 : ee / 2;              // ceil(ee / 2): smallest i with 4^i >= x
+    i = min(max(i, kBucketMin), kBucketMax);
+    return true;
+}
+
+// Slot of every token: its bucket (Alg. 1 line 5);
 // erased (line 8) when 4^i <= erase2 * max |v|^2.  Counts per (sequence, slot): blockIdx.y = sequence, a histogram per
 // workgroup in LDS, one global atomic per workgroup and occupied slot.
 __global__ __launch_bounds__(256) void slot_kernel(const float* norm2, const unsigned int* vmax2_bits, int64_t n, float erase2,
@@ -62,14 +74,8 @@ __global__ __launch_bounds__(256) void slot_kernel(const float* norm2, const uns
     for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < n; t += (int64_t)gridDim.x * 256) {
         int s = kDropSlot;
         const float x = norm2[seq * n + t];
-        if (x > 0.f && x < __builtin_inff()) {
-            int e;
-            const float m = frexpf(x, &e);                    // x = m 2^e, 1/2 <= m < 1
-            const int ee = (m == 0.5f) ? e - 1 : e;           // smallest integer with 2^ee >= x
-            int i = ee >= 0 ? (ee + 1) / 2 : ee / 2;          // ceil(ee / 2): smallest i with 4^i >= x
-            i = min(max(i, kBucketMin), kBucketMax);
-            s = (ldexpf(1.f, 2 * i) <= limit) ? kDropSlot : kNumSlot0 + i;
-        }
+        int i;
+        if (bucket_of(x, i)) s = (ldexpf(1.f, 2 * i) <= limit) ? kDropSlot : kNumSlot0 + i;
         slot[seq * n + t] = s;
         atomicAdd(&hist[s], 1);
     }
@@ -446,6 +452,196 @@ hipError_t launch_rescale(int dtype, void* out, const float* lse_num, const floa
     const unsigned gg = grid_for(rows * d, 256);
     if (dtype == BKV_BF16) hipLaunchKernelGGL(rescale_kernel<__bf16>, dim3(gg), dim3(256), 0, st, (char*)out, lse_num, lse_den, rows, d);
     else hipLaunchKernelGGL(rescale_kernel<float>, dim3(gg), dim3(256), 0, st, (char*)out, lse_num, lse_den, rows, d);
+    return hipGetLastError();
+}
+
+
+// ------------------------------------------------------------------------------------------ Alg. 1 token by token
+namespace {
+
+constexpr int kFreeRegion = INT32_MIN;
+
+// Lines 4-12 of Alg. 1 for one token per sequence, up to the halvings themselves.  One wavefront per sequence:
+//  * |v|^2, the running maximum and the erase limit (line 8): regions whose bucket has 4^i <= limit are given back;
+//  * the token's bucket (line 5) -> its region (a free one on the bucket's first token) -> the row goes to the tail of
+//    the region with weight 1 (line 7 feeds MR-Numerator_i); the key goes to the denominator region (line 11);
+//  * the carry loop of Alg. 3 for both instances as a table: round r of this token halves the last `b` stored tokens
+//    of the region as they will stand after the rounds before it (each takes b/2 away), draws from the instance's
+//    stream at level r, block number = blocks that reached level r before.
+// Lane l < regions looks after region l.
+template <typename T, int D>
+__global__ __launch_bounds__(64) void stream_route_kernel(StreamState s, const char* k, const char* v, int32_t j) {
+    constexpr int RB = D * (int)sizeof(T);
+    constexpr int SL = RB / 16;
+    const int64_t seq = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int R = s.regions, b = s.b, half = s.b / 2, Tn = s.T;
+    uintx4 kraw = {0u, 0u, 0u, 0u}, vraw = {0u, 0u, 0u, 0u};
+    if (lane < SL) {
+        kraw = *reinterpret_cast<const uintx4*>(k + (size_t)seq * RB + lane * 16);
+        vraw = *reinterpret_cast<const uintx4*>(v + (size_t)seq * RB + lane * 16);
+    }
+    const float x = __shfl(group_sum<SL>(Elem<T>::dot(vraw, vraw)), 0);          // |v|^2, fp32
+    float vm = __uint_as_float(s.vmax2[seq]);
+    if (x < __builtin_inff() && x > vm) {
+        vm = x;
+        if (lane == 0) s.vmax2[seq] = __float_as_uint(vm);
+    }
+    const float limit = s.erase2 > 0.f ? s.erase2 * vm : 0.f;
+
+    // ---- line 8: erase the negligible buckets (lane l keeps region l's bucket and counters in registers; they are
+    // written back once, at the end)
+    int bk = lane < R ? s.bucket[seq * R + lane] : kFreeRegion;
+    int my_cnt = lane < R ? s.cnt[seq * (R + 1) + lane] : 0;
+    int my_jj = lane < R ? s.jj[seq * (R + 1) + lane] : 0;
+    const bool gone = bk != kFreeRegion && ldexpf(1.f, 2 * bk) <= limit;
+    unsigned long long erased = __ballot(gone);
+    while (erased) {
+        const int e = __ffsll((long long)erased) - 1;
+        erased &= erased - 1;
+        const int c = __shfl(my_cnt, e);
+        float* w = s.wn + (size_t)(seq * R + e) * s.cap_n;
+        for (int t = lane; t < c; t += 64) w[t] = 0.f;
+    }
+    if (gone) { bk = kFreeRegion; my_cnt = 0; my_jj = 0; }
+
+    // ---- lines 5-7: the token's bucket and region
+    int i = 0;
+    int reg = 0;
+    bool take = bucket_of(x, i) && !(ldexpf(1.f, 2 * i) <= limit);      // a token of a negligible bucket is dropped at once
+    if (take) {
+        const unsigned long long hit = __ballot(bk == i);
+        if (hit) reg = __ffsll((long long)hit) - 1;
+        else {
+            const unsigned long long vacant = __ballot(lane < R && bk == kFreeRegion);
+            if (vacant) {
+                reg = __ffsll((long long)vacant) - 1;
+                if (lane == reg) bk = i;                         // counters of a free region are 0
+            } else {
+                take = false;
+                if (lane == 0) atomicOr(s.err, BKV_STREAM_NO_REGION);
+            }
+        }
+    }
+    int pos_n = __shfl(my_cnt, reg);
+    if (take && pos_n >= s.cap_n) {
+        take = false;
+        if (lane == 0) atomicOr(s.err, BKV_STREAM_NUM_FULL);
+    }
+    int carries_n = 0, blocks_n = 0;
+    if (take) {
+        const size_t at = (size_t)(seq * R + reg) * s.cap_n + pos_n;
+        if (lane < SL) {
+            *reinterpret_cast<uintx4*>(s.Kn + at * RB + lane * 16) = kraw;
+            *reinterpret_cast<uintx4*>(s.Vn + at * RB + lane * 16) = vraw;
+        }
+        if (lane == 0) { s.wn[at] = 1.f; s.on[at] = j; }
+        const int seen = __shfl(my_jj, reg) + 1;
+        pos_n += 1;
+        if (lane == reg) { my_cnt = pos_n; my_jj = seen; }
+        if (Tn > 0 && seen % b == 0) {
+            blocks_n = seen / b;
+            carries_n = min(Tn, __ffs(blocks_n));               // rounds r < T with blocks_n divisible by 2^r
+        }
+    }
+    if (lane < R) {
+        s.bucket[seq * R + lane] = bk;
+        s.cnt[seq * (R + 1) + lane] = my_cnt;
+        s.jj[seq * (R + 1) + lane] = my_jj;
+    }
+
+    // ---- line 11: the key alone goes to MR-Denominator
+    int pos_d = s.cnt[seq * (R + 1) + R];
+    int carries_d = 0, blocks_d = 0;
+    if (pos_d >= s.cap_d) {
+        if (lane == 0) atomicOr(s.err, BKV_STREAM_DEN_FULL);
+    } else {
+        const size_t at = (size_t)seq * s.cap_d + pos_d;
+        if (lane < SL) *reinterpret_cast<uintx4*>(s.Kd + at * RB + lane * 16) = kraw;
+        const int seen = s.jj[seq * (R + 1) + R] + 1;
+        if (lane == 0) {
+            s.wd[at] = 1.f; s.od[at] = j;
+            s.cnt[seq * (R + 1) + R] = pos_d + 1;
+            s.jj[seq * (R + 1) + R] = seen;
+        }
+        pos_d += 1;
+        if (Tn > 0 && seen % b == 0) {
+            blocks_d = seen / b;
+            carries_d = min(Tn, __ffs(blocks_d));
+        }
+    }
+
+    // ---- the carries of this token, round by round (lanes 0..T-1: numerator, 32..32+T-1: denominator)
+    const int r = lane & 31, kind = lane >> 5;
+    if (r < Tn) {
+        InstDesc ds;
+        ds.in_tok = ds.out_tok = 0; ds.stream = ds.ctr0 = 0; ds.seq = (int32_t)seq; ds.valid = 0; ds.rvalue2 = 0.f; ds.pad = 0;
+        const int carries = kind ? carries_d : carries_n;
+        if (r < carries) {
+            const int64_t region0 = kind ? seq * s.cap_d : (seq * R + reg) * s.cap_n;
+            const int64_t first = (kind ? pos_d : pos_n) - (int64_t)r * half - b;
+            const uint64_t slot = kind ? (uint64_t)kDenSlot : (uint64_t)(kNumSlot0 + i);
+            ds.in_tok = region0 + first;
+            ds.out_tok = seq * half;
+            ds.stream = 64ull * ((uint64_t)(s.seq_base + seq) * kSlots + slot) + (uint64_t)r;
+            ds.ctr0 = (uint64_t)(((kind ? blocks_d : blocks_n) >> r) - 1) * (uint64_t)b;
+            ds.valid = 1;
+            ds.rvalue2 = kind ? 0.f : ldexpf(1.f, 2 * i);
+            ds.pad = kind ? R : reg;
+        }
+        s.desc[((int64_t)r * 2 + kind) * s.n_seq + seq] = ds;
+    }
+}
+
+// After the halvings of round r: the survivors (rows, original indices) go back to the front of the block they came
+// from with weight 2^(r+1), the rest of the block is marked absent and the region shrinks by half a block.
+__global__ __launch_bounds__(256) void stream_fixup_kernel(StreamState s, int r) {
+    __shared__ int32_t so[512];
+    const int64_t seq = blockIdx.x;
+    const int kind = blockIdx.y, tid = threadIdx.x;
+    const InstDesc ds = s.desc[((int64_t)r * 2 + kind) * s.n_seq + seq];
+    if (!ds.valid) return;
+    const int half = s.b / 2, rb = s.row_bytes, slices = rb >> 4;
+    char* K = kind ? s.Kd : s.Kn;
+    float* w = kind ? s.wd : s.wn;
+    int32_t* o = kind ? s.od : s.on;
+    const int64_t frame = kind ? seq * s.cap_d : seq * (int64_t)s.regions * s.cap_n;      // first place of the sequence
+    const int64_t first = ds.in_tok;
+    const size_t t0 = (size_t)(kind * s.n_seq + seq) * half;
+    const int32_t* ti = s.tmpIdx + t0;
+    for (int t = tid; t < half; t += 256) so[t] = o[frame + ti[t]];
+    __syncthreads();
+    const float wnew = ldexpf(1.f, r + 1);
+    for (int t = tid; t < half; t += 256) {
+        o[first + t] = so[t];
+        w[first + t] = wnew;
+        w[first + half + t] = 0.f;
+    }
+    for (int t = tid; t < half * slices; t += 256) {
+        const int row = t / slices, sl = t - row * slices;
+        const size_t src = (t0 + row) * rb + sl * 16, dst = (size_t)(first + row) * rb + sl * 16;
+        *reinterpret_cast<uintx4*>(K + dst) = *reinterpret_cast<const uintx4*>(s.tmpK + src);
+        if (!kind) *reinterpret_cast<uintx4*>(s.Vn + dst) = *reinterpret_cast<const uintx4*>(s.tmpV + src);
+    }
+    if (tid == 0) s.cnt[seq * (s.regions + 1) + ds.pad] -= half;
+}
+
+}  // namespace
+
+hipError_t stream_route(const StreamState& s, const void* k, const void* v, int64_t j, hipStream_t st) {
+    const dim3 grid((unsigned)s.n_seq), block(64);
+    const char* kp = (const char*)k;
+    const char* vp = (const char*)v;
+    if (s.dtype == BKV_BF16 && s.d == 128) hipLaunchKernelGGL((stream_route_kernel<__bf16, 128>), grid, block, 0, st, s, kp, vp, (int32_t)j);
+    else if (s.dtype == BKV_BF16 && s.d == 64) hipLaunchKernelGGL((stream_route_kernel<__bf16, 64>), grid, block, 0, st, s, kp, vp, (int32_t)j);
+    else if (s.dtype == BKV_F32 && s.d == 128) hipLaunchKernelGGL((stream_route_kernel<float, 128>), grid, block, 0, st, s, kp, vp, (int32_t)j);
+    else if (s.dtype == BKV_F32 && s.d == 64) hipLaunchKernelGGL((stream_route_kernel<float, 64>), grid, block, 0, st, s, kp, vp, (int32_t)j);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t stream_fixup(const StreamState& s, int round, hipStream_t st) {
+    hipLaunchKernelGGL(stream_fixup_kernel, dim3((unsigned)s.n_seq, 2u), dim3(256), 0, st, s, round);
     return hipGetLastError();
 }
 

@@ -1,0 +1,206 @@
+"""Alg. 1 fed token by token on the GPU (bkv_stream_*) against the oracle's BalanceKVStream and against the offline
+form of the same algorithm (bkv_balancekv_sets), through the C ABI (run with -m gpu).
+
+The streaming state after n tokens must hold, per bucket and for the denominator instance, the tokens Alg. 3 keeps
+(original indices, weights 2^level, bit-exact rows).  Decisions are free-running on both sides, so a sequence in which
+the device reports a decision within 1e-4 of its draw is compared with the offline device path only (same kernels,
+same draws), not with the float64 oracle.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from parity_utils import f32, rel_l2, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def bk():
+    import paper_2502_07861_amd as bkm
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    bkm.lib()          # raises if the HIP library is not built: there is no fallback
+    return bkm
+
+
+@pytest.fixture(scope="module")
+def synth():
+    from paper_2502_07861_amd import synth as s
+    return s
+
+
+def _scaled_values(V, seed, lo, hi, drift=0.0, zero_rows=3):
+    """Value rows scaled by 2^(U(lo, hi) + drift * t / n): several norm buckets, the norms growing along the stream
+    when drift > 0 (so that the erase rule has earlier buckets to drop), a few all-zero rows."""
+    g = torch.Generator().manual_seed(seed)
+    n_seq, n, _ = V.shape
+    e = torch.rand(n_seq, n, generator=g) * (hi - lo) + lo + drift * torch.arange(n)[None, :] / n
+    scale = torch.exp2(e)
+    for s in range(n_seq):
+        scale[s, torch.randperm(n, generator=g)[:zero_rows]] = 0.0
+    return (V.float() * scale[..., None]).to(V.dtype)
+
+
+def _feed(bk, p, K, V, regions, cap_num, cap_den, **kw):
+    n_seq, n, d = K.shape
+    T = max(p.rounds, 1)
+    st = bk.Stream(p, n_seq, regions, cap_num, cap_den, **kw)
+    status_n = torch.zeros(n_seq, T, device="cuda", dtype=torch.int32)
+    status_d = torch.zeros(n_seq, T, device="cuda", dtype=torch.int32)
+    Kt, Vt = K.transpose(0, 1).contiguous(), V.transpose(0, 1).contiguous()       # [n, n_seq, d]: one token of every sequence per step
+    launches = 0
+    for j in range(n):
+        launches += st.append(Kt[j], Vt[j], status_n, status_d)
+    torch.cuda.synchronize()
+    assert st.tokens_seen == n
+    return st, status_n.cpu().numpy(), status_d.cpu().numpy(), launches
+
+
+def _region_sets(view, s):
+    """{bucket: (orig, w, K rows, V rows)} of sequence s, and the same for the denominator instance."""
+    cnt = view["count"][s].cpu().numpy()
+    bucket = view["bucket"][s].cpu().numpy()
+    out = {}
+    for reg, i in enumerate(bucket.tolist()):
+        w_all = view["w_n"][s, reg].cpu().numpy()
+        c = int(cnt[reg])
+        assert np.all(w_all[c:] == 0), "places beyond the count must be absent"
+        if i == -(1 << 31):
+            assert c == 0
+            continue
+        assert i not in out, "one region per bucket"
+        assert np.all(w_all[:c] > 0)
+        out[i] = (view["orig_n"][s, reg, :c].cpu().numpy(), w_all[:c], view["K_n"][s, reg, :c], view["V_n"][s, reg, :c])
+    cd = int(cnt[-1])
+    wd = view["w_d"][s].cpu().numpy()
+    assert np.all(wd[cd:] == 0) and np.all(wd[:cd] > 0)
+    den = (view["orig_d"][s, :cd].cpu().numpy(), wd[:cd], view["K_d"][s, :cd])
+    return out, den
+
+
+@pytest.mark.parametrize("dtype,d,b,T,n,n_seq", [
+    (torch.bfloat16, 128, 64, 2, 1500, 3),
+    (torch.float32, 64, 64, 3, 1100, 2),
+    (torch.bfloat16, 128, 256, 1, 2100, 2),
+])
+def test_stream_state_equals_the_offline_sets(bk, synth, dtype, d, b, T, n, n_seq):
+    """Without the erase rule the state after n tokens is the offline result on those n tokens: per bucket (ascending)
+    the same original indices in the same order, the same weights, the rows themselves; likewise the denominator."""
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=n, d=d, g=2, nq=2, seed=500 + n, device="cpu", dtype=dtype)
+    K = t["K"].cuda().contiguous()
+    V = _scaled_values(t["V"], seed=n, lo=-2.0, hi=2.0).cuda().contiguous()
+    p = bk.make_params(d, b, T, dtype, log_c=-30.0 if dtype == torch.float32 else -62.0, seed=4242, center=True)
+    cap = (n >> T) + (T + 3) * b
+    st, status_n, status_d, launches = _feed(bk, p, K, V, regions=8, cap_num=cap, cap_den=cap, seq_base=3)
+    view = st.views()
+    assert int(view["error_word"][0]) == 0
+    assert not np.any((status_n | status_d) & 2)
+    num = bk.balancekv_sets(p, bk.BKV_SET_NUMERATOR, K, V, seq_base=3)
+    den = bk.balancekv_sets(p, bk.BKV_SET_DENOMINATOR, K, V, seq_base=3)
+    torch.cuda.synchronize()
+    halvings = 0
+    for s in range(n_seq):
+        sets, (od, wd, Kd) = _region_sets(view, s)
+        cnt = int(num["count"][s])
+        idx, w = num["idx"][s, :cnt].cpu().numpy(), num["w"][s, :cnt].cpu().numpy()
+        slots = sorted(set(num["slot"][s].cpu().numpy().tolist()) - {511})
+        assert sorted(256 + i for i in sets) == slots
+        pos = 0
+        for i in sorted(sets):
+            o, ww, Kr, Vr = sets[i]
+            m = o.shape[0]
+            np.testing.assert_array_equal(o, idx[pos:pos + m])
+            np.testing.assert_array_equal(ww, w[pos:pos + m])
+            gi = torch.from_numpy(o.astype(np.int64)).cuda()
+            assert torch.equal(Kr, K[s][gi]) and torch.equal(Vr, V[s][gi])
+            halvings += int(np.count_nonzero(ww > 1))
+            pos += m
+        assert pos == cnt
+        cd = int(den["count"][s])
+        np.testing.assert_array_equal(od, den["idx"][s, :cd].cpu().numpy())
+        np.testing.assert_array_equal(wd, den["w"][s, :cd].cpu().numpy())
+        assert torch.equal(Kd, K[s][torch.from_numpy(od.astype(np.int64)).cuda()])
+        assert wd.sum() == n
+    assert halvings > 0
+    np.testing.assert_array_equal(status_n, num["status"].cpu().numpy())
+    np.testing.assert_array_equal(status_d, den["status"].cpu().numpy())
+    # Alg. 1 output line over the state == over the offline sets (same tokens and weights; partial sums may be grouped differently)
+    Q = t["Q"].cuda().contiguous()
+    out_s, lse_s = st.attend(Q)
+    out_o, lse_o = bk.attend_sets(p, (num["K"], num["V"], num["w"]), (den["K"], den["w"]), Q)
+    torch.cuda.synchronize()
+    assert rel_l2(to_f64(out_s), to_f64(out_o)) <= (1e-5 if dtype == torch.float32 else 1e-2)
+    np.testing.assert_allclose(lse_s.cpu().numpy(), lse_o.cpu().numpy(), atol=1e-4 if dtype == torch.float32 else 1e-2)
+    print("launches per token: %.2f" % (launches / n))
+
+
+def test_stream_equals_the_oracle_stream_with_erasures(bk, synth, oracle):
+    """Free-running against the oracle's Alg. 1, token by token, with value norms that grow along the stream and an erase
+    rule that drops the early buckets: the same live buckets, per bucket the same tokens and weights, the same
+    denominator set, and the same estimate.  More buckets appear over time than the state has regions: erased regions
+    are handed out again."""
+    from oracle.balancekv import BalanceKVStream
+    dtype, d, b, T, n, n_seq = torch.float32, 64, 64, 2, 900, 4
+    eps, radius = 1.0, 1.0
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=n, d=d, g=1, nq=2, seed=77, device="cpu", dtype=dtype)
+    K = t["K"].cuda().contiguous()
+    V = _scaled_values(t["V"], seed=11, lo=-8.0, hi=-6.0, drift=16.0).cuda().contiguous()
+    p = bk.make_params(d, b, T, dtype, log_c=-30.0, seed=999, center=True)
+    regions = 14
+    st, status_n, status_d, _ = _feed(bk, p, K, V, regions=regions, cap_num=n, cap_den=n, n_total=n, eps=eps, r=radius, seq_base=1)
+    view = st.views()
+    assert int(view["error_word"][0]) == 0
+    Q = t["Q"].cuda().contiguous()
+    out, _ = st.attend(Q)
+    torch.cuda.synchronize()
+    near = (status_n >> 8).sum(axis=1) + (status_d >> 8).sum(axis=1)
+    Kd, Vd, Qd = to_f64(K), to_f64(V), to_f64(Q)
+    compared = 0
+    for s in range(n_seq):
+        ref = BalanceKVStream(d, d, t=b, T=T, n_total=n, eps=eps, r=radius, seed=999, seq=1 + s, log_c=f32(-30.0), center=True)
+        seen_buckets = set()
+        for j in range(n):
+            ref.append(Kd[s, j], Vd[s, j])
+            seen_buckets |= set(ref.num)
+        assert len(seen_buckets) > regions > len(ref.num), "the case must need regions to be handed out again"
+        sets, (od, wd, _) = _region_sets(view, s)
+        assert sorted(sets) == sorted(ref.num)                       # buckets and erase rule: no decision is involved
+        if near[s]:
+            continue
+        want = ref.numerator_sets()
+        for i in want:
+            np.testing.assert_array_equal(sets[i][0], want[i][0])
+            np.testing.assert_array_equal(sets[i][1], want[i][1])
+        di, dw = ref.denominator_set()
+        np.testing.assert_array_equal(od, di)
+        np.testing.assert_array_equal(wd, dw)
+        for j in range(Qd.shape[2]):
+            assert rel_l2(to_f64(out[s, 0, j]), ref.estimate(Qd[s, 0, j])) <= 1e-4
+        compared += 1
+    print("near-tie decisions per sequence: %s, sequences compared with the oracle stream: %d" % (near.tolist(), compared))
+    assert compared >= 2
+
+
+def test_stream_overflow_is_flagged_not_written(bk, synth):
+    """Too few regions / too small regions: the surplus tokens are dropped, the error word says which limit was hit, and
+    the stored places stay consistent (weights beyond the counts are 0)."""
+    dtype, d, b, T, n, n_seq = torch.bfloat16, 64, 64, 1, 400, 2
+    t = synth.gqa_layer_bf16(n_seq=n_seq, n=n, d=d, g=1, nq=1, seed=5, device="cpu", dtype=dtype)
+    K = t["K"].cuda().contiguous()
+    V = _scaled_values(t["V"], seed=3, lo=-3.0, hi=3.0).cuda().contiguous()
+    p = bk.make_params(d, b, T, dtype, log_c=-62.0, seed=1, center=True)
+    st, _, _, _ = _feed(bk, p, K, V, regions=2, cap_num=b, cap_den=2 * b)
+    view = st.views()
+    word = int(view["error_word"][0])
+    assert word & bk.BKV_STREAM_NO_REGION and word & bk.BKV_STREAM_DEN_FULL and not word & 2
+    for s in range(n_seq):
+        sets, (od, wd, _) = _region_sets(view, s)
+        assert len(sets) == 2 and od.shape[0] <= 2 * b
+        for i, (o, w, _, _) in sets.items():
+            assert o.shape[0] <= b and np.all(np.diff(o) > 0)
+    with pytest.raises(bk.BkvError):
+        bk.Stream(p, n_seq, 65, b, b)
+    with pytest.raises(bk.BkvError):
+        bk.Stream(p, n_seq, 4, b - 1, b)

@@ -60,6 +60,21 @@ template <> struct Elem<__bf16> {
             f[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
         }
     }
+    // part[e] += element e of the slice, e = 0..7: one v_dot2c_f32_bf16 per element (the pair times (1, 0) or (0, 1): the
+    // product with 1 is exact, the one with 0 adds nothing for finite inputs) instead of a shift or mask and an add
+    static __device__ __forceinline__ void accumulate(float (&part)[8], const uintx4& raw) {
+        typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+        // (1, 0) and (0, 1) as bf16 pairs, kept in registers: written as literals the compiler folds them into an inline
+        // operand of the packed instruction that selects the wrong half (both calls then add the high element)
+        unsigned int lo_one = 0x00003f80u, hi_one = 0x3f800000u;
+        asm volatile("" : "+v"(lo_one), "+v"(hi_one));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const unsigned int ri = raw[i];
+            part[2 * i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, ri), __builtin_bit_cast(bf16x2_t, lo_one), part[2 * i], false);
+            part[2 * i + 1] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, ri), __builtin_bit_cast(bf16x2_t, hi_one), part[2 * i + 1], false);
+        }
+    }
     // dot product of two 16-byte slices (8 bf16 each), fp32 accumulation: v_dot2c_f32_bf16
     static __device__ __forceinline__ float dot(const uintx4& a, const uintx4& b) {
         typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -89,6 +104,10 @@ template <> struct Elem<float> {
     static __device__ __forceinline__ void unpack(const uintx4& raw, float (&f)[4]) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(raw[i]);
+    }
+    static __device__ __forceinline__ void accumulate(float (&part)[4], const uintx4& raw) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) part[i] += __uint_as_float(raw[i]);
     }
     static __device__ __forceinline__ float dot(const uintx4& a, const uintx4& b) {
         float acc = 0.f;

@@ -718,12 +718,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             for (int u = 0; u < U; ++u) {
                 const int i = i0 + u * RG;
                 if (i < rows_here) *reinterpret_cast<uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, sl)) = raw[u];
-                if (i < rows_sum) {
-                    float f[EPL];
-                    Elem<T>::unpack(raw[u], f);
-#pragma unroll
-                    for (int e = 0; e < EPL; ++e) part[e] += f[e];
-                }
+                if (i < rows_sum) Elem<T>::accumulate(part, raw[u]);
             }
         }
     };
@@ -751,12 +746,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             const int i = rg + u * RG;
             if (u < kU0) *reinterpret_cast<uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, sl)) = raw[u];    // i < CH <= b
             else if (u - kU0 < kUK) keep[u - kU0 < kUK ? u - kU0 : 0] = raw[u];
-            if (center && i < b) {
-                float f[EPL];
-                Elem<T>::unpack(raw[u], f);
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) part[e] += f[e];
-            }
+            if (center && i < b) Elem<T>::accumulate(part, raw[u]);
         }
     } else {
         stage_chunk(0, min(CH, b), center ? b : 0);

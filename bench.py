@@ -89,7 +89,7 @@ def cpu_baseline(cfg, K, V, Q, log_c):
     t0 = time.perf_counter()
     one_pass()
     first = time.perf_counter() - t0
-    reps = int(min(8, max(1, round(15.0 / max(first, 1e-3)))))      # about 15 s of wall time in all
+    reps = int(min(16, max(1, round(15.0 / max(first, 1e-3)))))     # about 15 s of wall time in all
     t0 = time.perf_counter()
     for _ in range(reps):
         one_pass()

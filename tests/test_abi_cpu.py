@@ -114,6 +114,21 @@ def test_misuse_is_rejected_before_any_launch(bk):
     assert L.bkv_cache_bytes(C.byref(ok), 4, 4096) == 2 * 4 * 4096 * 256 + 4 * 4096 * 4 + 256      # K, V, w, the error word
     assert L.bkv_append_token(None, one, one, None, None, None, None, 0, None) == bk.BKV_EINVAL
     assert L.bkv_attend(None, one, 4, 1, one, None, None, 0, None) == bk.BKV_EINVAL
+    # Alg. 1 token by token: geometry is checked before the storage is touched
+    sb = lambda regions, cn, cd: L.bkv_stream_bytes(C.byref(small), 2, regions, cn, cd)
+    assert sb(0, 1024, 1024) == 0 and sb(65, 1024, 1024) == 0 and sb(4, 127, 1024) == 0 and sb(4, 1024, 127) == 0
+    rows = 2 * 4 * 1024                        # numerator places
+    assert sb(4, 1024, 2048) >= 2 * rows * 256 + 2 * rows * 4 + 2 * 2048 * (256 + 8) + 4 * 2 * 64 * 256
+    si = lambda regions, cn, storage, nbytes, eps=0.0, n_total=0: L.bkv_stream_init(
+        C.byref(h), C.byref(small), 2, 0, regions, cn, 2048, n_total, eps, 0.0, storage, nbytes, None)
+    assert si(4, 1024, None, 0) == bk.BKV_EINVAL                           # no storage
+    assert si(4, 1024, C.c_void_p(0x1010), 1 << 30) == bk.BKV_EINVAL       # not 256-byte aligned
+    assert si(4, 1024, one, 16) == bk.BKV_EINVAL                           # too small
+    assert si(65, 1024, one, 1 << 30) == bk.BKV_EINVAL
+    assert si(4, 1024, one, 1 << 30, eps=0.5, n_total=0) == bk.BKV_EINVAL  # the erase rule needs the stream length
+    assert L.bkv_stream_append(None, one, one, None, None, None) == bk.BKV_EINVAL
+    assert L.bkv_stream_attend(None, one, 4, 1, one, None, None, 0, None) == bk.BKV_EINVAL
+    assert L.bkv_stream_tokens_seen(None) == bk.BKV_EINVAL and L.bkv_stream_free(None) == bk.BKV_EINVAL
 
 
 def test_literal_log_c(bk, oracle):

@@ -968,6 +968,14 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         __syncthreads();
     }
 
+    // Blocks of several full chunks of eight panels, plain instances with rows of 256 bytes: the rows of the NEXT chunk
+    // are brought in during the panel pipeline by column owners whose duties are over (they would idle through the last
+    // walks of the chunk): a panel through the registers of such a wavefront into the slot of a row panel that every
+    // column owner has passed (rowp[w]: row tiles whose operands wavefront w has read).  Slot q by the owner of column
+    // q+1 (q = 0..5), slot 7 by wavefront 5, which formed the last diagonal tile, slot 6 by wavefront 3 once the owner
+    // of column 7 has read it.  The read's latency hides behind the walk; nothing stays in registers across a barrier.
+    constexpr bool kPre = MULTI && !EMIT_G && VG == 0 && G::kRowBytes == 256;
+    const bool pre_on = kPre && CH == 512;
     int foff[G::kGroups];                      // byte offset, inside an LDS row, of this lane's fragment of k-group g
 #pragma unroll
     for (int g = 0; g < G::kGroups; ++g) foff[g] = G::slice_off(n, 2 * g + h);
@@ -978,7 +986,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         const int p0 = row0 >> 6, p1 = (row0 + rows_here) >> 6;
         if (c > 0) {
             __syncthreads();                           // previous users of ldsK are done
-            stage_chunk(row0, rows_here, 0);
+            if (!pre_on) stage_chunk(row0, rows_here, 0);      // (else the previous pipeline has brought the rows in already)
             if (tid < 32 && tid != 3) prog[tid] = 0;   // progress counters of this chunk's pipeline (the error flag is sticky)
             __syncthreads();
         }
@@ -1064,8 +1072,11 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         int* sync_err = prog + 3;
         int* first_parts = prog + 4;                  // quadrants of the chunk's first diagonal tile stored so far (three writers)
         int* col = prog + 8;
+        int* rowp = prog + 16;                        // rowp[w]: row panels whose LDS rows column owner w needs no more
         constexpr bool kSplitFirst = !EMIT_G && VG == 0;   // the first tile comes in three quadrants from three wavefronts
         const int nPc = p1 - p0;
+        const int next0 = row0 + rows_here;                                           // first row of the next chunk
+        const int nN = pre_on && c + 1 < n_chunks ? (min(CH, b - next0) >> 6) : 0;    // its panels (0: nothing to bring in)
         if (wave == 0) {
             unsigned int sign_bit = 0x80000000u;
             asm volatile("" : "+s"(sign_bit));             // stays in a scalar register
@@ -1190,6 +1201,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     }
                     // the weights are complete here: the compiler must not sink their arithmetic below the wait
                     asm volatile("" : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]));
+                    // this wavefront has read row panel i for the last time: its operands were in registers before the tile's
+                    // matrix instructions could issue, so a plain store says so
+                    if (kPre && nN > 0) publish_in_order(rowp + w, i + 1);
                     // signs of row panel i (once the walker has published them), signed column sums
                     const bool urgent = i == w - 1;            // the walker is waiting for this one
                     float sg[32];
@@ -1213,6 +1227,36 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
 #pragma unroll
             for (int j = 0; j < PF; ++j) pfacc ^= pfv[j] ^ pfv0[j];
             asm volatile("" :: "v"(pfacc));                   // the touches must not be optimised away
+            if constexpr (kPre) {
+                if (nN > 0 && nPc == 8 && w <= 6) {
+                    int ln = lane;
+                    asm volatile("" : "+v"(ln));              // the lane's offsets are formed here, not kept across the chunks
+                    const int r_w = ln >> 4, s_w = ln & 15;  // 16 slices per row: a load covers four rows
+                    // first job: slot w-1; second job of wavefronts 5 and 3: slots 7 and 6
+                    for (int job = 0; job < 2; ++job) {
+                        const int q = job == 0 ? w - 1 : (w == 5 ? 7 : w == 3 ? 6 : -1);
+                        if (q < 0 || q >= nN) continue;
+                        // The slot's readers are through: every column owner behind row panel q has taken its tile of it
+                        // (slot 7: owner 7 its own fragments), owner q holds its fragments, and the diagonal tile of panel q is
+                        // formed (stored, or for panel 0 its three quadrants; that of panel 7 this wavefront formed itself).
+                        const int need = q == 7 ? 1 : q + 1;
+                        for (int v = (q == 7 ? 7 : q + 1); v < 8; ++v)
+                            if (v != w) await(rowp + v, need, sync_err);
+                        if (q >= 1 && q != 7) await(rowp + q, 1, sync_err);
+                        if (q == 0) await(first_parts, 3, sync_err);
+                        else if (q != 7) await(diag_ready, q + 1, sync_err);
+                        uintx4 t[16];
+                        const char* src = Kin + (size_t)(next0 + (q << 6) + r_w) * G::kRowBytes + s_w * 16;
+#pragma unroll
+                        for (int u = 0; u < 16; ++u) t[u] = *reinterpret_cast<const uintx4*>(src + (size_t)u * 4 * G::kRowBytes);
+#pragma unroll
+                        for (int u = 0; u < 16; ++u) {
+                            const int row = (q << 6) + 4 * u + r_w;
+                            *reinterpret_cast<uintx4*>(ldsK + (size_t)row * G::kLdsRow + G::slice_off(row, s_w)) = t[u];
+                        }
+                    }
+                }
+            }
         }
         __syncthreads();                                   // the chunk is done: LDS rows, counters and tile buffer are free
     }

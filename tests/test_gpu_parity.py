@@ -93,6 +93,9 @@ CASES = [
     (torch.float32, 128, 640, 2, True),      # fp32, d=128: chunks of 256 rows -> three chunks, the last of two panels
     (torch.float32, 128, 1024, 2, True),     # ... four full chunks (the counters are reset three times)
     (torch.bfloat16, 128, 960, 2, False),    # bf16: two chunks, the second of seven panels
+    (torch.bfloat16, 128, 576, 2, True),     # ... the second of one panel (one slot brought in during the first pipeline)
+    (torch.bfloat16, 128, 768, 2, True),     # ... of four
+    (torch.float32, 64, 1024, 2, True),      # fp32 rows of 256 bytes: two full chunks
 ]
 
 

@@ -1057,6 +1057,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         //   eta_done      panels walked so far (the walker publishes after writing the signs of panel l)
         //   diag_ready    diagonal tiles stored so far        diag_taken   diagonal tiles the walker has loaded so far
         //   col[l]        set to l by the owner of column panel l once sigma of that panel holds every earlier row panel
+        //   rowp[w]       row panels whose LDS rows column owner w has read for the last time (only where the next chunk is
+        //                 brought in during this pipeline, see kPre)
         // Wavefront w = 1..7 owns column panel w of the chunk: it keeps the panel's fragments in registers as the B
         // operand and forms, in row order, the tiles (i, w), i < w (weights need nothing; the signed column sum needs
         // eta_done > i and goes into a register copy of sigma); then, its column being complete just as the walk of

@@ -51,6 +51,10 @@ extern "C" {
                              * 160 KB of LDS together (d=128: block <= 256 bf16 / 128 fp32; d=64: block <= 512 bf16 /
                              * 256 fp32); larger blocks read the value panels from L2 tile by tile.  V is required
                              * wherever K is.                                                                    */
+#define BKV_VALUE_AUGMENT 8u /* with BKV_VALUE_GRAM: the walk sees the value [v / r_value ; 1] (Alg. 2 takes values of any
+                             * dimension s), i.e. the factor (<v_i,v_j>/r_value^2 + 1) / 2: one kept set that balances the
+                             * numerator and the denominator of Alg. 1's output line together.  A block whose values are
+                             * all zero gets the factor 1 (the keys-only walk) when the radius is measured, 1/2 when given. */
 
 /* return codes */
 #define BKV_OK          0

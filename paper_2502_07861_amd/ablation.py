@@ -1,6 +1,6 @@
 """Ablation grid of the paper's single-layer study on synthetic data (one GPU).
 
-    python -m paper_2502_07861_amd.ablation [--seeds 10] [--json] [--recipe clustered|iid] [--value-factor | --alg1]
+    python -m paper_2502_07861_amd.ablation [--seeds 10] [--json] [--recipe clustered|iid] [--value-factor | --value-augment | --alg1]
 
 For block sizes b in {256, 128, 64} and compression rates 2^-T in {1/2, 1/4, 1/8} (the grid of the runtime /
 relative-error tables in "Ablation Studies on Single Layer Attention Approximation", arXiv 2502.07861): the first
@@ -20,7 +20,8 @@ independent Gaussians around a common mean, where no subset is better than a ran
 ln c per recipe and block size was bisected once on the CPU oracle (oracle/tuning.py, mean |2p - 1| = 0.25 on the first
 four blocks of the first two sequences) so that the walk's decisions depend on the kernel weights.  --value-factor: the walk's weights carry the
 value factor <v_i,v_j>/r_value^2 of Alg. 2 line 6 (the numerator instance of Alg. 1 selects the kept set), with its own
-ln c per block size found the same way.
+ln c per block size found the same way.  --value-augment (clustered recipe): the walk sees the value [v / r_value ; 1], i.e. the
+factor (<v_i,v_j>/r_value^2 + 1) / 2: one kept set chosen for numerator and denominator together.
 """
 from __future__ import annotations
 
@@ -42,9 +43,14 @@ LOG_C = {64: -53.9166, 128: -59.3241, 256: -61.8303}            # recipe "iid"
 LOG_C_VALUE = {64: -57.0969, 128: -63.0066, 256: -67.8165}      # ... with the value factor
 LOG_C_CLUSTERED = {64: -4.2786, 128: -3.4420, 256: -2.9556}     # recipe "clustered"
 LOG_C_CLUSTERED_VALUE = {64: -4.6749, 128: -3.8368, 256: -3.3827}
+LOG_C_CLUSTERED_AUGMENT = {64: -4.4572, 128: -3.6253, 256: -3.1501}     # ... with the value [v / r ; 1]
 
 
-def log_c_for(recipe, block, value_gram=False):
+def log_c_for(recipe, block, value_gram=False, value_augment=False):
+    if value_augment:
+        if recipe != "clustered":
+            raise ValueError("ln c for the augmented value is tabulated for the clustered recipe only")
+        return LOG_C_CLUSTERED_AUGMENT.get(block, 0.0)
     table = {("iid", False): LOG_C, ("iid", True): LOG_C_VALUE, ("clustered", False): LOG_C_CLUSTERED,
              ("clustered", True): LOG_C_CLUSTERED_VALUE}[(recipe, bool(value_gram))]
     return table.get(block, 0.0)
@@ -100,8 +106,8 @@ def normaliser_error(lse, lse_exact):
 
 
 def run(seeds=10, blocks=BLOCKS, rounds=ROUNDS, n_mid=N_MID, n_seq=8, device="cuda", nq=64, keep_outputs=False,
-        value_gram=False, recipe="clustered"):
-    """The grid.  value_gram: kernel weights with the value factor of Alg. 2 line 6.  keep_outputs: every cell also carries the tensors of its first counted seed (kept indices, weights,
+        value_gram=False, recipe="clustered", value_augment=False):
+    """The grid.  value_gram: kernel weights with the value factor of Alg. 2 line 6; value_augment: with the factor of the value [v / r ; 1].  keep_outputs: every cell also carries the tensors of its first counted seed (kept indices, weights,
     both estimates, the uniform comparator's indices) and the result the inputs, for checking against a reference."""
     K, V, Q = make_inputs(device, n_seq=n_seq, n_mid=n_mid, nq=nq, recipe=recipe)
     n, d = K.shape[1], K.shape[2]
@@ -113,8 +119,8 @@ def run(seeds=10, blocks=BLOCKS, rounds=ROUNDS, n_mid=N_MID, n_seq=8, device="cu
                 continue
             err_b, err_u, den_b, den_u, ms = [], [], [], [], []
             for s in range(seeds + 1):                      # run 0 warms up and is not counted
-                p = binding.make_params(d, b, T, K.dtype, log_c=log_c_for(recipe, b, value_gram),
-                                        seed=1000 + s, center=True, value_gram=value_gram)
+                p = binding.make_params(d, b, T, K.dtype, log_c=log_c_for(recipe, b, value_gram, value_augment),
+                                        seed=1000 + s, center=True, value_gram=value_gram, value_augment=value_augment)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
                 res = binding.merge_reduce_protected(p, K, V, N_SINK, N_RECENT)
@@ -225,6 +231,7 @@ def main(argv=None):
     ap.add_argument("--seeds", type=int, default=10)
     ap.add_argument("--json", action="store_true", help="print one JSON line instead of the table")
     ap.add_argument("--value-factor", action="store_true", help="kernel weights times <v_i,v_j>/r_value^2 (Alg. 2 line 6)")
+    ap.add_argument("--value-augment", action="store_true", help="kernel weights times (<v_i,v_j>/r_value^2 + 1) / 2: the value [v / r ; 1]")
     ap.add_argument("--alg1", action="store_true", help="Alg. 1 as listed (buckets, two kept sets) on heavy-tailed value norms")
     ap.add_argument("--recipe", default="clustered", choices=["clustered", "iid"], help="input recipe of the grid")
     args = ap.parse_args(argv)
@@ -236,7 +243,7 @@ def main(argv=None):
         result = run_alg1(seeds=args.seeds)
         print(json.dumps(result) if args.json else result["workload"] + ", %d seeds\n" % result["seeds"] + alg1_table(result))
         return 0
-    result = run(seeds=args.seeds, value_gram=args.value_factor, recipe=args.recipe)
+    result = run(seeds=args.seeds, value_gram=args.value_factor, recipe=args.recipe, value_augment=args.value_augment)
     if args.json:
         print(json.dumps(result))
     else:

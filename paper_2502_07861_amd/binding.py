@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbalancekv.so")
 
 BKV_F32, BKV_BF16 = 0, 1
-BKV_CENTER_KEYS, BKV_STRICT_HALF, BKV_VALUE_GRAM = 1, 2, 4
+BKV_CENTER_KEYS, BKV_STRICT_HALF, BKV_VALUE_GRAM, BKV_VALUE_AUGMENT = 1, 2, 4, 8
 BKV_OK, BKV_EINVAL, BKV_ESHAPE, BKV_EWORKSPACE, BKV_EHIP, BKV_ECAPACITY = 0, -1, -2, -3, -4, -5
 BKV_STATUS_FAIL = 1
 
@@ -109,10 +109,11 @@ def error_string(code: int) -> str:
 
 
 def make_params(d, block, rounds, dtype, *, log_c=float("nan"), delta=0.0, r_key=0.0, r_value=0.0, seed=0,
-                center=False, strict=True, value_gram=False) -> bkv_params:
+                center=False, strict=True, value_gram=False, value_augment=False) -> bkv_params:
     if isinstance(dtype, torch.dtype):
         dtype = {torch.float32: BKV_F32, torch.bfloat16: BKV_BF16}[dtype]
-    flags = (BKV_CENTER_KEYS if center else 0) | (BKV_STRICT_HALF if strict else 0) | (BKV_VALUE_GRAM if value_gram else 0)
+    flags = ((BKV_CENTER_KEYS if center else 0) | (BKV_STRICT_HALF if strict else 0) | (BKV_VALUE_GRAM if value_gram or value_augment else 0)
+             | (BKV_VALUE_AUGMENT if value_augment else 0))
     return bkv_params(d, block, rounds, dtype, log_c, delta, r_key, r_value, seed & (2**64 - 1), flags, 0)
 
 

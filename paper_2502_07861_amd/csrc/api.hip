@@ -26,7 +26,8 @@ int check_params(const bkv_params* p) {
     if (p->block < 64 || p->block > 1024 || (p->block & 63)) return BKV_ESHAPE;
     if (p->rounds < 0 || p->rounds > 30) return BKV_ESHAPE;
     if (p->dtype != BKV_F32 && p->dtype != BKV_BF16) return BKV_ESHAPE;
-    if (p->flags & ~(BKV_CENTER_KEYS | BKV_STRICT_HALF | BKV_VALUE_GRAM)) return BKV_EINVAL;
+    if (p->flags & ~(BKV_CENTER_KEYS | BKV_STRICT_HALF | BKV_VALUE_GRAM | BKV_VALUE_AUGMENT)) return BKV_EINVAL;
+    if ((p->flags & BKV_VALUE_AUGMENT) && !(p->flags & BKV_VALUE_GRAM)) return BKV_EINVAL;    // an option of the value factor
     if (!(p->flags & BKV_STRICT_HALF)) return BKV_ESHAPE;      // variable-size output not built
     if (isnan(p->log_c) && !(p->delta > 0.f && p->delta < (float)p->block)) return BKV_EINVAL;
     return BKV_OK;
@@ -397,7 +398,7 @@ int bkv_balancekv_sets(const bkv_params* p_in, int32_t which, const void* K, con
     if (!p_in) return BKV_EINVAL;
     if (which != BKV_SET_NUMERATOR && which != BKV_SET_DENOMINATOR) return BKV_EINVAL;
     bkv_params p = *p_in;
-    p.flags = which == BKV_SET_NUMERATOR ? (p.flags | BKV_VALUE_GRAM) : (p.flags & ~BKV_VALUE_GRAM);
+    p.flags = which == BKV_SET_NUMERATOR ? (p.flags | BKV_VALUE_GRAM) : (p.flags & ~(BKV_VALUE_GRAM | BKV_VALUE_AUGMENT));
     int rc = check_params(&p);
     if (rc) return rc;
     if (n_seq < 0 || n < 0 || seq_base < 0 || capacity < 0 || !(r >= 0.f)) return BKV_EINVAL;
@@ -739,7 +740,7 @@ int bkv_stream_append(bkv_stream* h, const void* k, const void* v, int32_t* stat
         // MR-Denominator sees every token: it carries at round r exactly when block * 2^r divides j
         if (j % ((int64_t)b << r) == 0) {
             bkv_params pd = h->p;
-            pd.flags &= ~BKV_VALUE_GRAM;
+            pd.flags &= ~(BKV_VALUE_GRAM | BKV_VALUE_AUGMENT);
             fill_common(a, &pd);
             a.desc = s.desc + (size_t)(r * 2 + 1) * s.n_seq;
             a.K = s.Kd; a.V = nullptr; a.K_out = s.tmpK + (size_t)s.n_seq * half * s.row_bytes; a.V_out = nullptr;

@@ -166,7 +166,7 @@ struct TileOps {
                                                  const float* naA, const float* naB, float alpha, float rc, const float* sg, const float* sgn_h,
                                                  const int (&foff)[G::kGroups], int n, int h, const Frag (*Bq)[2] = nullptr,
                                                  const char* vA = nullptr, const char* vB = nullptr, float inv_rv2 = 0.f,
-                                                 const char* vA1 = nullptr, const char* vB1 = nullptr) {
+                                                 const char* vA1 = nullptr, const char* vB1 = nullptr, float vg_bias = 0.f) {
         constexpr int KG = G::kGroups;
         constexpr int RPI = 16 / KG;                       // accumulator registers (per column half) finished per k-group
         constexpr int kAhead = KG < 4 ? KG : 4;              // k-groups between the request of a B fragment and its use
@@ -197,7 +197,7 @@ struct TileOps {
 #pragma unroll
                 for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) vg[rb][cb][r] *= inv_rv2;
+                    for (int r = 0; r < 16; ++r) vg[rb][cb][r] = fmaf(vg[rb][cb][r], inv_rv2, vg_bias);
             __builtin_amdgcn_sched_barrier(0);
         }
         const char* bp0 = BREG ? nullptr : ldsB + (size_t)n * G::kLdsRow;
@@ -794,7 +794,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
             }
     }
     __syncthreads();
-    float inv_rv2 = 0.f;
+    float inv_rv2 = 0.f, vg_bias = 0.f;       // the value factor is <v_i,v_j> * inv_rv2 + vg_bias
     {
         // ---------------------------------------------------------- block statistics
         // mu = mean key (fp32), a_i = <k_i, mu>, A = largest centred squared norm (or r_key^2)
@@ -951,6 +951,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 for (int w = 1; w < kWaves; ++w) r2 = fmaxf(r2, diag[kDiagFloats - 64 + w]);
             }
             inv_rv2 = r2 > 0.f ? 1.f / r2 : 0.f;               // all values zero: every weight is zero
+            if (a.flags & BKV_VALUE_AUGMENT) {                  // value [v / r ; 1], radius^2 = 2 (or 1 when all values are zero)
+                vg_bias = r2 > 0.f ? 0.5f : 1.f;
+                inv_rv2 *= 0.5f;
+            }
         }
         __syncthreads();                                        // wpart (aliasing diag) is dead from here
         {
@@ -1021,7 +1025,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     const float cs = Ops::template tile<true, true, false, false, VG>(
                         acc, A, nullptr, ldsB, narow + (I << 6), narow + (J << 6), alpha, row_const, sg, nullptr, foff, n, h, nullptr,
                         VG == 2 ? vrow((I << 6) + n) : nullptr, VG == 2 ? vrow((J << 6) + n) : nullptr, inv_rv2,
-                        VG == 2 ? vrow((I << 6) + 32 + n) : nullptr, VG == 2 ? vrow((J << 6) + 32 + n) : nullptr);
+                        VG == 2 ? vrow((I << 6) + 32 + n) : nullptr, VG == 2 ? vrow((J << 6) + 32 + n) : nullptr, vg_bias);
                     if constexpr (EMIT_G) {
 #pragma unroll
                         for (int rb = 0; rb < 2; ++rb)
@@ -1139,7 +1143,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 const char* vrows = VG == 1 ? ldsV + (size_t)(l << 6) * G::kLdsRow : VG == 2 ? vrow((I << 6) + n) : nullptr;
                 const char* vrows1 = VG == 2 ? vrow((I << 6) + 32 + n) : nullptr;
                 Ops::template tile<false, true, true, !EMIT_G, VG>(dv, P, nullptr, nullptr, narow + (I << 6), narow + (I << 6), alpha, row_const,
-                                                                   nullptr, nullptr, foff, n, h, P, vrows, vrows, inv_rv2, vrows1, vrows1);
+                                                                   nullptr, nullptr, foff, n, h, P, vrows, vrows, inv_rv2, vrows1, vrows1, vg_bias);
                 if (EMIT_G) {
 #pragma unroll
                     for (int rb = 0; rb < 2; ++rb)
@@ -1188,7 +1192,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                                                                       nullptr, nullptr, foff, n, h, Bq,
                                                                       VG == 1 ? ldsV + (size_t)(i << 6) * G::kLdsRow : VG == 2 ? vrow((Ii << 6) + n) : nullptr,
                                                                       VG == 1 ? ldsV + (size_t)(w << 6) * G::kLdsRow : VG == 2 ? vrow((J << 6) + n) : nullptr, inv_rv2,
-                                                                      VG == 2 ? vrow((Ii << 6) + 32 + n) : nullptr, VG == 2 ? vrow((J << 6) + 32 + n) : nullptr);
+                                                                      VG == 2 ? vrow((Ii << 6) + 32 + n) : nullptr, VG == 2 ? vrow((J << 6) + 32 + n) : nullptr, vg_bias);
                     if (EMIT_G) {
 #pragma unroll
                         for (int rb = 0; rb < 2; ++rb)

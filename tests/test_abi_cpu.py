@@ -69,6 +69,9 @@ def test_misuse_is_rejected_before_any_launch(bk):
     assert compress(bk.make_params(128, 256, 2, bk.BKV_BF16, log_c=0.0, value_gram=True)) == bk.BKV_EINVAL
     assert L.bkv_kernel_weights(C.byref(bk.make_params(128, 256, 2, bk.BKV_BF16, log_c=0.0, value_gram=True)), one, 2, one, None) == bk.BKV_ESHAPE
     assert compress(bk.make_params(128, 512, 2, bk.BKV_BF16)) == bk.BKV_EINVAL                 # NaN log_c, no delta
+    aug_only = bk.make_params(128, 256, 2, bk.BKV_BF16, log_c=0.0)
+    aug_only.flags |= bk.BKV_VALUE_AUGMENT                                                     # the option without the value factor
+    assert compress(aug_only) == bk.BKV_EINVAL
     assert compress(ok, K=None) == bk.BKV_EINVAL
     assert compress(ok, K=C.c_void_p(0x1004)) == bk.BKV_EINVAL                                 # misaligned
     assert compress(ok, n_inst=-1) == bk.BKV_EINVAL

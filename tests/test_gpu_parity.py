@@ -244,6 +244,61 @@ def test_compress_block_with_value_factor(bk, synth, oracle, dtype, d, b, n_inst
     np.testing.assert_allclose(stats[inside, 1], smax[inside], rtol=1e-3, atol=1e-5)
 
 
+@pytest.mark.parametrize("dtype,d,b,n_inst,r_value", [
+    (torch.bfloat16, 128, 256, 4, 0.0),       # keys and values in LDS together
+    (torch.bfloat16, 128, 512, 3, 0.0),       # value panels from L2
+    (torch.bfloat16, 128, 1024, 2, 16.0),     # two chunks of keys, a given radius
+    (torch.float32, 64, 256, 3, 0.0),
+])
+def test_compress_block_with_augmented_value(bk, synth, oracle, dtype, d, b, n_inst, r_value):
+    """BKV_VALUE_AUGMENT: the walk sees the value [v / r_value ; 1] (Alg. 2 takes values of any dimension), whose
+    radius is sqrt 2.  The oracle is handed exactly those rows of dimension d + 1, so the device's factor
+    (<v_i,v_j>/r_value^2 + 1) / 2 is checked against Alg. 2 as listed, teacher-forced.  One block has all-zero values:
+    its augmented value is [0 ; 1] with radius 1 (the keys-only walk)."""
+    from oracle.tuning import tune_log_c
+    K, V = _blocks(synth, dtype, d, b, n_inst, seed=911 + b + d)
+    V = V.clone()
+    V[-1] = 0                                                      # the last block: no values at all
+    Kd, Vd = to_f64(K), to_f64(V)
+    radius = np.full(n_inst, r_value) if r_value > 0.0 else np.sqrt((Vd ** 2).sum(-1).max(axis=1))
+    if r_value > 0.0:
+        assert r_value ** 2 > (Vd ** 2).sum(-1).max()
+    seed = 0xA06 + b
+    u = np.stack([oracle.uniform_fill(seed, t, 0, b) for t in range(n_inst)])
+    Vaug = np.concatenate([Vd / np.where(radius > 0, radius, 1.0)[:, None, None], np.ones((n_inst, b, 1))], axis=-1)
+    log_c = f32(tune_log_c(Kd[:2], target=0.25, center=True, V_blocks=Vaug[:2]))      # (measured radius of these rows: sqrt 2)
+    p = bk.make_params(d, b, 1, dtype, log_c=log_c, seed=seed, center=True, value_augment=True, r_value=r_value)
+    out = bk.compress_block(p, K, V, uniforms=torch.from_numpy(u.astype(np.float32)).cuda())
+    torch.cuda.synchronize()
+    signs = out["signs"].cpu().numpy()
+    stats = out["stats"].cpu().numpy()
+    assert not np.any(out["status"].cpu().numpy() & 2)
+    tot = dict(hard=0, near=0, n=0)
+    for t in range(n_inst):                                        # the radius of the augmented rows differs for the empty block
+        r_aug = math.sqrt(2.0) if radius[t] > 0 else 1.0
+        v = verify_halving(oracle, Kd[t:t + 1], u[t:t + 1], signs[t:t + 1], log_c=log_c, center=True, V_blocks=Vaug[t:t + 1], r_value=r_aug)
+        for k in tot:
+            tot[k] += v[k]
+        # the weights themselves, through the largest |sigma| of the walk (sensitive to the factor's scale and offset, which
+        # the decisions alone need not be: most of them are saturated)
+        smax = np.abs(v["res"]["sigma"]).max()
+        if smax < 1e25:
+            np.testing.assert_allclose(stats[t, 1], smax, rtol=1e-3, atol=1e-5)
+        np.testing.assert_allclose(stats[t, 0], np.abs(u[t] - v["res"]["p"][0]).min(), atol=2e-5)
+        if t == 0:
+            assert np.abs(2 * v["res"]["p"] - 1).mean() > 0.05     # the decisions depend on the weights ...
+            plain = oracle.softmax_balance_batch(Kd[:1], Vd[:1], u=u[:1], log_c=log_c, center=True)
+            assert np.count_nonzero(plain["eta"] != signs[:1]) > 0  # ... and the factor is not the plain <v_i,v_j>/r^2
+            keys_only = oracle.softmax_balance_batch(Kd[:1], u=u[:1], log_c=log_c, center=True)
+            assert abs(np.abs(keys_only["sigma"]).max() / smax - 1.0) > 0.05      # ... nor 1
+    print("%d decisions, %d within margin, %d hard" % (tot["n"], tot["near"], tot["hard"]))
+    assert tot["hard"] == 0
+    if r_value == 0.0:      # measured radius: the empty block decides as the keys-only walk does (factor 1; a given radius makes it 1/2)
+        ko = oracle.softmax_balance_batch(Kd[-1:], u=u[-1:], log_c=log_c, center=True, forced=signs[-1:])
+        assert np.count_nonzero((ko["dec"] != signs[-1:]) & (np.abs(u[-1:] - ko["p"]) >= MARGIN)) == 0
+    np.testing.assert_array_equal(out["idx"].cpu().numpy(), expected_survivors(oracle, signs))
+
+
 def test_merge_reduce_with_value_factor_workload2_blocks(bk, synth, oracle):
     """The tree with the value factor at workload 2's block size (values read from L2 by original index in round 1)."""
     from oracle.tuning import tune_log_c

@@ -12,13 +12,17 @@
  *   bkv_append_token     one streaming step incl. carries          (Alg. 3)
  *   bkv_attend           weighted softmax estimator                (Alg. 1, output line)
  *
+ * and, on top of them, Alg. 1 as listed (value-norm buckets, numerator and denominator
+ * instances): offline as bkv_balancekv_sets / bkv_attend_sets, token by token as bkv_stream_*.
+ *
  * Conventions
  *  - Plain C, no exceptions.  Every tensor pointer is a DEVICE pointer owned by
  *    the caller unless stated otherwise; the library never frees or keeps it
- *    beyond the call, except the storage handed to bkv_cache_init.
+ *    beyond the call, except the storage handed to bkv_cache_init / bkv_stream_init.
  *  - Scratch memory comes from the caller: query the size, pass `workspace`.
  *  - Every call only enqueues work on `hip_stream` (a hipStream_t passed as
- *    void*, NULL = default stream) and returns; nothing synchronises.
+ *    void*, NULL = default stream) and returns; nothing synchronises (the
+ *    two diagnostics calls bkv_profile_read and bkv_measure_peak do, and say so).
  *  - Return value: BKV_OK or a negative code for misuse / launch failure.
  *    Algorithmic events (the FAIL branch of Alg. 2, near-tie decisions) are
  *    NOT errors: they are written to per-instance device arrays.

@@ -84,6 +84,7 @@ def _region_sets(view, s):
     (torch.bfloat16, 128, 64, 2, 1500, 3),
     (torch.float32, 64, 64, 3, 1100, 2),
     (torch.bfloat16, 128, 256, 1, 2100, 2),
+    (torch.bfloat16, 64, 128, 2, 1300, 2),
 ])
 def test_stream_state_equals_the_offline_sets(bk, synth, dtype, d, b, T, n, n_seq):
     """Without the erase rule the state after n tokens is the offline result on those n tokens: per bucket (ascending)

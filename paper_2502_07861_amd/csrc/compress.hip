@@ -843,6 +843,17 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 }
                 mumu = group_sum<SL>(mumu);
             }
+            // mu also goes to LDS, one copy per wavefront behind the partials (its first SL lanes hold all of it; no
+            // barrier): the rows that are resident in LDS are taken one per thread below, against mu at uniform addresses
+            if (lane < SL) {
+                float* mu_w = wpart + kWaves * D + wave * D;
+#pragma unroll
+                for (int q = 0; q < EPL / 4; ++q) {
+                    const floatx4 t = {mloc[4 * q], mloc[4 * q + 1], mloc[4 * q + 2], mloc[4 * q + 3]};
+                    *reinterpret_cast<floatx4*>(mu_w + sl * EPL + 4 * q) = t;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
         }
         // Resident blocks take one row per thread (at most kThreads rows are ever resident); the general path
         // streams every row as 16-byte slices.
@@ -909,18 +920,33 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                 const int n_lds = min(CH, b);                    // b and CH are multiples of 64 and of RG
                 uintx4 ahead[U];
                 if (n_lds < b && !kept) load_global(ahead, n_lds);
-                for (int ib0 = 0; ib0 < n_lds; ib0 += RG * U) {
-                    uintx4 raw[U];
+                // resident rows: one row per thread (a chunk has at most kThreads rows), mu MC columns at a time from this
+                // wavefront's copy (uniform addresses): no cross-lane step
+                for (int i = tid; i < n_lds; i += kThreads) {
+                    constexpr int MC = 16;
+                    constexpr int SLQ = MC * (int)sizeof(T) / 16;
+                    const float* mu_w = wpart + kWaves * D + wave * D;
+                    float pa = 0.f, pn = 0.f;
 #pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        const int i = min(ib0 + u * RG + rg, n_lds - 1);
-                        raw[u] = *reinterpret_cast<const uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, sl));
-                    }
+                    for (int qc = 0; qc < D / MC; ++qc) {
+                        float sm[MC];
 #pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        const int i = ib0 + u * RG + rg;
-                        row_terms(raw[u], i < n_lds ? i : b);      // rows past the chunk's end are not counted here
+                        for (int jj = 0; jj < MC / 4; ++jj) {
+                            const floatx4 t = *reinterpret_cast<const floatx4*>(mu_w + qc * MC + 4 * jj);
+                            sm[4 * jj] = t[0]; sm[4 * jj + 1] = t[1]; sm[4 * jj + 2] = t[2]; sm[4 * jj + 3] = t[3];
+                        }
+#pragma unroll
+                        for (int ss = 0; ss < SLQ; ++ss) {
+                            const uintx4 raw = *reinterpret_cast<const uintx4*>(ldsK + (size_t)i * G::kLdsRow + G::slice_off(i, qc * SLQ + ss));
+                            float f[EPL];
+                            Elem<T>::unpack(raw, f);
+#pragma unroll
+                            for (int e = 0; e < EPL; ++e) pa = fmaf(f[e], sm[ss * EPL + e], pa);
+                            pn += Elem<T>::dot(raw, raw);
+                        }
                     }
+                    narow[i] = -pa;
+                    amax = fmaxf(amax, pn - 2.f * pa + mumu);
                 }
                 if (kept) {                                     // the rows beyond the first chunk are still in registers
 #pragma unroll

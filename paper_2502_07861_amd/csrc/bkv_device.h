@@ -154,4 +154,29 @@ template <int SL> __device__ __forceinline__ float group_sum(float x) {
     return x;
 }
 
+// Sixteen values per lane, summed over the 16 lanes of a row: lane s of the row returns the total of x[s].  Each step
+// halves the values a lane carries (it keeps the half its own lane bit selects and hands the other half to its
+// partner), so the sixteen sums take 15 exchanges instead of 64.
+__device__ __forceinline__ float row16_transpose_sum(const float (&x)[16], int s) {
+    const bool b3 = (s & 8) != 0, b2 = (s & 4) != 0, b1 = (s & 2) != 0, b0 = (s & 1) != 0;
+    float y[8], z[4], u[2];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float mine = b3 ? x[j + 8] : x[j], send = b3 ? x[j] : x[j + 8];
+        y[j] = mine + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0x140, 0xF, 0xF, true));   // row_mirror
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float mine = b2 ? y[j + 4] : y[j], send = b2 ? y[j] : y[j + 4];
+        z[j] = mine + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0x141, 0xF, 0xF, true));   // row_half_mirror
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const float mine = b1 ? z[j + 2] : z[j], send = b1 ? z[j] : z[j + 2];
+        u[j] = mine + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+    }
+    const float mine = b0 ? u[1] : u[0], send = b0 ? u[0] : u[1];
+    return mine + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));        // quad_perm [1,0,3,2]
+}
+
 }  // namespace bkv

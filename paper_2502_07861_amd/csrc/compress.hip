@@ -740,6 +740,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
         for (int u = 0; u < kU2; ++u) {
             const int i = rg + u * RG;
             if (i < b) raw[u] = *reinterpret_cast<const uintx4*>(Kin + (size_t)i * G::kRowBytes + sl * 16);
+            else raw[u] = uintx4{0u, 0u, 0u, 0u};                // (rows past the block's end: defined, never counted)
         }
 #pragma unroll
         for (int u = 0; u < kU2; ++u) {
@@ -949,10 +950,32 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
                     amax = fmaxf(amax, pn - 2.f * pa + mumu);
                 }
                 if (kept) {                                     // the rows beyond the first chunk are still in registers
+                    if constexpr (SL == 16 && kUK == 16) {
+                        // sixteen rows per thread, sixteen slices per row: the partial sums change hands so that lane sl
+                        // ends up with the totals of the thread's row number sl
+                        float pa16[16], pn16[16];
 #pragma unroll
-                    for (int k = 0; k < kUK; ++k) {
-                        const int i = (kU0 + k) * RG + rg;
-                        row_terms(keep[k], i < b ? i : b);
+                        for (int k = 0; k < 16; ++k) {
+                            float f[EPL];
+                            Elem<T>::unpack(keep[k], f);
+                            float pa = 0.f;
+#pragma unroll
+                            for (int e = 0; e < EPL; ++e) pa = fmaf(f[e], mloc[e], pa);
+                            pa16[k] = pa;
+                            pn16[k] = Elem<T>::dot(keep[k], keep[k]);
+                        }
+                        const float pa = row16_transpose_sum(pa16, sl), pn = row16_transpose_sum(pn16, sl);
+                        const int i = (kU0 + sl) * RG + rg;
+                        if (i < b) {
+                            narow[i] = -pa;
+                            amax = fmaxf(amax, pn - 2.f * pa + mumu);
+                        }
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < kUK; ++k) {
+                            const int i = (kU0 + k) * RG + rg;
+                            row_terms(keep[k], i < b ? i : b);
+                        }
                     }
                 }
                 for (int ib0 = n_lds; ib0 < b && !kept; ib0 += RG * U) {

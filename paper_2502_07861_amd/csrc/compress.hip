@@ -661,8 +661,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const CompressArgs a
     float* Gi = EMIT_G ? a.G_out + (size_t)inst * b * b : nullptr;
 
     // Every block of a launch takes the same time, so compute units that start together stay in lockstep and
-    // would all hit HBM in the same phases.  The first wave of workgroups therefore starts spread over one
-    // block duration (a bounded wait on the clock); later workgroups inherit the offsets.
+    // would all hit HBM in the same phases.  The first wave of workgroups therefore starts spread over a good part
+    // of one block's duration (a bounded wait on the clock; the launcher sets the step); later workgroups inherit the offsets.
     if (a.stagger_step > 0 && (int)blockIdx.x < a.stagger_blocks) {
         const long long wait = (long long)a.stagger_step * (long long)blockIdx.x;
         const long long t0 = __builtin_amdgcn_s_memtime();
@@ -1513,8 +1513,11 @@ hipError_t launch_compress(int dtype, int d, bool emit_g, CompressArgs& a, int64
         }
         a.stagger_blocks = 0; a.stagger_step = 0; a.prefetch_ahead = 0;
         if (n_inst >= 2 * (int64_t)n_cu && !a.desc) {   // (a ragged grid has unused slots: neighbours in the grid are not neighbours in memory)
-            // rough duration of one block in clock ticks (measured: about 75k for 512 bf16 tokens, 200k for 1024)
-            const double ticks = (40.0e3 + 0.15 * (double)a.b * (double)a.b) * (dtype == BKV_BF16 ? 1.0 : 1.5);
+            // The first workgroups start spread over about two thirds of one block's duration: 100k clock ticks for 1024
+            // bf16 tokens, whose blocks take about 145k (a spread over the whole duration keeps the compute units idle
+            // longer at both ends of a launch than the better interleaving gives back: 2 % on a launch of 32 blocks per
+            // compute unit; a third of the duration interleaves too little).
+            const double ticks = (20.0e3 + 0.075 * (double)a.b * (double)a.b) * (dtype == BKV_BF16 ? 1.0 : 1.5);
             a.stagger_blocks = n_cu;
             a.stagger_step = (int)(ticks / n_cu);
             // Look-ahead touches pay where they are the only second read of a row (blocks resident as one chunk: 2-4 %);
